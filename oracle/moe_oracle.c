@@ -1,0 +1,326 @@
+/*
+ * moe_oracle.c -- plain CPU definition of the sparse-MoE FFN layer forward.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the yardstick the GPU library is
+ * compared with; it is loaded by the tests, by the smoke check and by the
+ * benchmark's CPU-baseline leg, and by nothing else.  It shares no code with
+ * the GPU path and must never be called from it.
+ *
+ * What it computes.  The paper (MoESD, arXiv 2505.19645) describes the layer
+ * only in words (Introduction: several expert networks plus a router that
+ * activates K of them per token; Sec. 3.2: K per token out of E) and models
+ * its cost through the number of activated experts N (Eq. N(t)).  The layer's
+ * arithmetic is the standard SwiGLU mixture, fixed by the benchmark configs:
+ *
+ *   logit[t,e] = sum_j X[t,j] * Wr[e,j]  (+ bias[e])
+ *   key[t,e]   = fp32(logit[t,e])                       (one rounding)
+ *   ids[t,:]   = the K experts with the largest key, equal keys -> lower index,
+ *                listed in that order
+ *   score      = softmax over all E of logit, or sigmoid(logit)
+ *   w[t,s]     = score[ids[t,s]] / sum_s' score[ids[t,s']]   (if renormalize)
+ *                times routed_scale
+ *   permutation= stable counting sort of the flat slots f = t*K+s by expert
+ *   y[p,:]     = Wd_e . ( silu(Wg_e . x) * (Wu_e . x) ),  x = X[perm[p]/K],
+ *                e = expert owning sorted row p
+ *   out[t,:]   = sum_s w[t,s] * y[inv[t*K+s],:]  +  g_t * shared(x_t)
+ *   g_t        = sigmoid(x_t . w_sg) or 1
+ *
+ * Everything is evaluated in fp64 from the bf16-valued inputs, sums run over
+ * the contraction index in ascending order, and nothing is rounded in between
+ * except the selection key.  Loops are parallelised with OpenMP over
+ * independent outputs only; no sum is split or reordered.
+ *
+ * Pins (tests/test_oracle_*.py): brute-force subset routing on tiny inputs,
+ * sum_s w = 1, numpy stable argsort for the permutation, reductions to plain
+ * matrix products (E=1,K=1; K=E; identical experts; expert relabelling), the
+ * closed form N(t) against Monte-Carlo and against exact enumeration.
+ * Absolute output values have no worked example in the paper: they are pinned
+ * only through those reductions ("parity unpinned" by the paper itself).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+typedef struct {
+  int32_t d, E, top_k, inter, shared_inter;
+  int32_t score_func;  /* 0 softmax, 1 sigmoid */
+  int32_t renormalize;
+  int32_t shared_gate;
+  double  routed_scale;
+} oracle_desc;
+
+/* bf16 word -> double (exact) */
+static double bf16_to_f64(uint16_t b) {
+  uint32_t u = ((uint32_t)b) << 16;
+  float f;
+  memcpy(&f, &u, 4);
+  return (double)f;
+}
+
+/* double -> bf16 word, round to nearest even in ONE step (no detour via fp32,
+ * which could round twice).  Finite inputs of ordinary magnitude only. */
+static uint16_t f64_to_bf16(double v) {
+  if (v == 0.0 || !isfinite(v)) {
+    float f = (float)v;
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    return (uint16_t)(u >> 16);
+  }
+  int ex;
+  double m = frexp(v, &ex);         /* v = m * 2^ex, 0.5 <= |m| < 1 */
+  double r = nearbyint(ldexp(m, 8)); /* 8 significant bits, ties to even */
+  float f = (float)ldexp(r, ex - 8); /* exactly representable */
+  uint32_t u;
+  memcpy(&u, &f, 4);
+  return (uint16_t)(u >> 16);
+}
+
+static double dot_bf16(const uint16_t *a, const uint16_t *b, int64_t n) {
+  double s = 0.0;
+  for (int64_t j = 0; j < n; ++j) s += bf16_to_f64(a[j]) * bf16_to_f64(b[j]);
+  return s;
+}
+
+static double sigmoid64(double z) { return 1.0 / (1.0 + exp(-z)); }
+static double silu64(double z) { return z / (1.0 + exp(-z)); }
+
+/* ---- closed forms of Sec. 3.2 ------------------------------------------- */
+
+/* Eq. N(t) */
+double oracle_expected_active_experts(int32_t E, int32_t K, int64_t t) {
+  if (E < 1 || K < 0 || K > E || t < 0) return NAN;
+  return (double)E * (1.0 - pow((double)(E - K) / (double)E, (double)t));
+}
+
+/* Eq. Texp */
+double oracle_expected_tokens_per_expert(int32_t E, int32_t K, int64_t t) {
+  if (E < 1 || K < 0 || K > E || t < 0) return NAN;
+  if (t == 0 || K == 0) return 0.0;
+  return (double)t * (double)K / oracle_expected_active_experts(E, K, t);
+}
+
+/* Eq. T_thres: smallest t with N(t) >= tau*E, found by stepping t (no log) */
+int64_t oracle_token_threshold(int32_t E, int32_t K, double tau) {
+  if (E < 1 || K < 1 || K > E || !(tau >= 0.0) || !(tau < 1.0)) return -1;
+  double miss = 1.0; /* (1-rho)^t */
+  double q = (double)(E - K) / (double)E;
+  for (int64_t t = 0; t < (int64_t)1 << 40; ++t) {
+    if (1.0 - miss >= tau) return t < 1 ? 1 : t;
+    miss *= q;
+  }
+  return -1;
+}
+
+/* ---- routing -------------------------------------------------------------- */
+
+/* logits [T,E] f64 (may be NULL), ids [T,K], w [T,K] f64 */
+int32_t oracle_route(const oracle_desc *c, const uint16_t *x, const uint16_t *wr,
+                     const float *bias, int32_t T, double *logits_out, int32_t *ids,
+                     double *w) {
+  const int E = c->E, K = c->top_k, d = c->d;
+  if (E < 1 || K < 1 || K > E || T < 0) return 1;
+#pragma omp parallel
+  {
+    double *l = (double *)malloc(sizeof(double) * E);
+    double *p = (double *)malloc(sizeof(double) * E);
+    float *key = (float *)malloc(sizeof(float) * E);
+    char *taken = (char *)malloc(E);
+#pragma omp for schedule(static)
+    for (int t = 0; t < T; ++t) {
+      for (int e = 0; e < E; ++e) {
+        l[e] = dot_bf16(x + (int64_t)t * d, wr + (int64_t)e * d, d);
+        if (bias) l[e] += (double)bias[e];
+        key[e] = (float)l[e];
+        if (logits_out) logits_out[(int64_t)t * E + e] = l[e];
+      }
+      /* scores from the fp64 logits */
+      if (c->score_func == 0) {
+        double mx = l[0];
+        for (int e = 1; e < E; ++e) if (l[e] > mx) mx = l[e];
+        double z = 0.0;
+        for (int e = 0; e < E; ++e) { p[e] = exp(l[e] - mx); z += p[e]; }
+        for (int e = 0; e < E; ++e) p[e] /= z;
+      } else {
+        for (int e = 0; e < E; ++e) p[e] = sigmoid64(l[e]);
+      }
+      /* K rounds of "largest remaining key, first index on equality" */
+      memset(taken, 0, E);
+      for (int s = 0; s < K; ++s) {
+        int best = -1;
+        for (int e = 0; e < E; ++e) {
+          if (taken[e]) continue;
+          if (best < 0 || key[e] > key[best]) best = e;
+        }
+        taken[best] = 1;
+        ids[(int64_t)t * K + s] = best;
+      }
+      double den = 1.0;
+      if (c->renormalize) {
+        den = 0.0;
+        for (int s = 0; s < K; ++s) den += p[ids[(int64_t)t * K + s]];
+      }
+      for (int s = 0; s < K; ++s)
+        w[(int64_t)t * K + s] = p[ids[(int64_t)t * K + s]] / den * c->routed_scale;
+    }
+    free(l); free(p); free(key); free(taken);
+  }
+  return 0;
+}
+
+/* ---- permutation ---------------------------------------------------------- */
+
+int32_t oracle_permute(int32_t E, int32_t K, int32_t T, const int32_t *ids, int32_t *counts,
+                       int32_t *offsets, int32_t *perm, int32_t *inv, int32_t *n_active) {
+  if (E < 1 || K < 1 || T < 0) return 1;
+  const int64_t n = (int64_t)T * K;
+  for (int e = 0; e < E; ++e) counts[e] = 0;
+  for (int64_t f = 0; f < n; ++f) {
+    if (ids[f] < 0 || ids[f] >= E) return 1;
+    counts[ids[f]]++;
+  }
+  offsets[0] = 0;
+  for (int e = 0; e < E; ++e) offsets[e + 1] = offsets[e] + counts[e];
+  int32_t *rank = (int32_t *)calloc(E, sizeof(int32_t));
+  for (int64_t f = 0; f < n; ++f) {
+    int e = ids[f];
+    int32_t p = offsets[e] + rank[e]++;
+    perm[p] = (int32_t)f;
+    inv[f] = p;
+  }
+  free(rank);
+  int na = 0;
+  for (int e = 0; e < E; ++e) na += counts[e] > 0;
+  *n_active = na;
+  return 0;
+}
+
+/* ---- one SwiGLU FFN on one token: y[0..d) ---------------------------------- */
+static void ffn_row(const uint16_t *xrow, const uint16_t *wg, const uint16_t *wu,
+                    const uint16_t *wd, int d, int I, double *h, double *y) {
+#pragma omp parallel for schedule(static)
+  for (int i = 0; i < I; ++i) {
+    double g = dot_bf16(xrow, wg + (int64_t)i * d, d);
+    double u = dot_bf16(xrow, wu + (int64_t)i * d, d);
+    h[i] = silu64(g) * u;
+  }
+#pragma omp parallel for schedule(static)
+  for (int cidx = 0; cidx < d; ++cidx) {
+    const uint16_t *row = wd + (int64_t)cidx * I;
+    double s = 0.0;
+    for (int i = 0; i < I; ++i) s += h[i] * bf16_to_f64(row[i]);
+    y[cidx] = s;
+  }
+}
+
+/*
+ * Whole layer.  tok_list/n_list select the tokens whose output is wanted
+ * (NULL / 0 = all T, in order); routing and the permutation always cover all T.
+ * out_f64 / out_bf16: [n_out, d].  Optional outputs (NULL to skip): ids [T,K],
+ * w [T,K], counts [E], offsets [E+1], perm [T*K], inv [T*K], n_active [1],
+ * gate [T] (shared-expert gate of every token).
+ */
+int32_t oracle_moe_forward(const oracle_desc *c, const uint16_t *x, const uint16_t *wr,
+                           const float *bias, const uint16_t *wg, const uint16_t *wu,
+                           const uint16_t *wd, const uint16_t *sg, const uint16_t *su,
+                           const uint16_t *sd, const uint16_t *wsg, int32_t T,
+                           const int32_t *tok_list, int32_t n_list, double *out_f64,
+                           uint16_t *out_bf16, int32_t *ids_o, double *w_o, int32_t *counts_o,
+                           int32_t *offsets_o, int32_t *perm_o, int32_t *inv_o,
+                           int32_t *n_active_o, double *gate_o) {
+  const int E = c->E, K = c->top_k, d = c->d, I = c->inter, S = c->shared_inter;
+  if (T < 0) return 1;
+  const int64_t n = (int64_t)T * K;
+  int32_t *ids = (int32_t *)malloc(sizeof(int32_t) * (n ? n : 1));
+  double *w = (double *)malloc(sizeof(double) * (n ? n : 1));
+  int32_t *counts = (int32_t *)malloc(sizeof(int32_t) * E);
+  int32_t *offsets = (int32_t *)malloc(sizeof(int32_t) * (E + 1));
+  int32_t *perm = (int32_t *)malloc(sizeof(int32_t) * (n ? n : 1));
+  int32_t *inv = (int32_t *)malloc(sizeof(int32_t) * (n ? n : 1));
+  int32_t n_active = 0;
+  int32_t rc = oracle_route(c, x, wr, bias, T, NULL, ids, w);
+  if (!rc) rc = oracle_permute(E, K, T, ids, counts, offsets, perm, inv, &n_active);
+  if (rc) goto done;
+
+  {
+    const int n_out = tok_list ? n_list : T;
+    const int Imax = I > S ? I : S;
+    double *h = (double *)malloc(sizeof(double) * (Imax ? Imax : 1));
+    double *y = (double *)malloc(sizeof(double) * d * K);
+    double *sh = (double *)malloc(sizeof(double) * d);
+    for (int o = 0; o < n_out; ++o) {
+      const int t = tok_list ? tok_list[o] : o;
+      /* routed experts: the K sorted rows that belong to token t */
+      for (int s = 0; s < K; ++s) {
+        const int32_t p = inv[(int64_t)t * K + s];
+        int e = 0;
+        while (!(offsets[e] <= p && p < offsets[e + 1])) ++e; /* owner of row p */
+        const int tok = perm[p] / K;                          /* == t */
+        ffn_row(x + (int64_t)tok * d, wg + (int64_t)e * I * d, wu + (int64_t)e * I * d,
+                wd + (int64_t)e * d * I, d, I, h, y + (int64_t)s * d);
+      }
+      double g = 1.0;
+      if (S > 0) {
+        ffn_row(x + (int64_t)t * d, sg, su, sd, d, S, h, sh);
+        if (c->shared_gate) g = sigmoid64(dot_bf16(x + (int64_t)t * d, wsg, d));
+      }
+      if (gate_o) gate_o[t] = g;
+      for (int cidx = 0; cidx < d; ++cidx) {
+        double acc = 0.0;
+        for (int s = 0; s < K; ++s) acc += w[(int64_t)t * K + s] * y[(int64_t)s * d + cidx];
+        if (S > 0) acc += g * sh[cidx];
+        if (out_f64) out_f64[(int64_t)o * d + cidx] = acc;
+        if (out_bf16) out_bf16[(int64_t)o * d + cidx] = f64_to_bf16(acc);
+      }
+    }
+    free(h); free(y); free(sh);
+  }
+  if (ids_o) memcpy(ids_o, ids, sizeof(int32_t) * n);
+  if (w_o) memcpy(w_o, w, sizeof(double) * n);
+  if (counts_o) memcpy(counts_o, counts, sizeof(int32_t) * E);
+  if (offsets_o) memcpy(offsets_o, offsets, sizeof(int32_t) * (E + 1));
+  if (perm_o) memcpy(perm_o, perm, sizeof(int32_t) * n);
+  if (inv_o) memcpy(inv_o, inv, sizeof(int32_t) * n);
+  if (n_active_o) *n_active_o = n_active;
+done:
+  free(ids); free(w); free(counts); free(offsets); free(perm); free(inv);
+  return rc;
+}
+
+/* The same forward with every sum carried in fp32 instead of fp64: used only
+ * by a cross-precision test that guards the fp64 code against a typo. */
+static float dot_bf16_f32(const uint16_t *a, const uint16_t *b, int64_t n) {
+  float s = 0.0f;
+  for (int64_t j = 0; j < n; ++j) s += (float)bf16_to_f64(a[j]) * (float)bf16_to_f64(b[j]);
+  return s;
+}
+
+int32_t oracle_ffn_row_f32(const uint16_t *xrow, const uint16_t *wg, const uint16_t *wu,
+                           const uint16_t *wd, int32_t d, int32_t I, float *y) {
+  float *h = (float *)malloc(sizeof(float) * I);
+  for (int i = 0; i < I; ++i) {
+    float g = dot_bf16_f32(xrow, wg + (int64_t)i * d, d);
+    float u = dot_bf16_f32(xrow, wu + (int64_t)i * d, d);
+    h[i] = g / (1.0f + expf(-g)) * u;
+  }
+  for (int cidx = 0; cidx < d; ++cidx) {
+    float s = 0.0f;
+    for (int i = 0; i < I; ++i) s += h[i] * (float)bf16_to_f64(wd[(int64_t)cidx * I + i]);
+    y[cidx] = s;
+  }
+  free(h);
+  return 0;
+}
+
+int32_t oracle_ffn_row_f64(const uint16_t *xrow, const uint16_t *wg, const uint16_t *wu,
+                           const uint16_t *wd, int32_t d, int32_t I, double *y) {
+  double *h = (double *)malloc(sizeof(double) * I);
+  ffn_row(xrow, wg, wu, wd, d, I, h, y);
+  free(h);
+  return 0;
+}
+
+/* bf16 rounding of a double array, exposed for the rounding-floor check */
+void oracle_round_bf16(const double *v, int64_t n, uint16_t *out) {
+  for (int64_t i = 0; i < n; ++i) out[i] = f64_to_bf16(v[i]);
+}
