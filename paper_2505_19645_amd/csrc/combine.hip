@@ -1,0 +1,45 @@
+// Weighted scatter-combine: out[t,:] = sum_s w[t,s] * y[inv[t*K+s],:] + g_t * ys[t,:]
+// summed in slot order s = 0..K-1, then the shared expert, in fp32, and rounded
+// once to bf16.  One thread produces four adjacent output features.
+#include "common.h"
+
+__global__ __launch_bounds__(256) void combine_kernel(
+    const float *__restrict__ y, const float *__restrict__ ys, const float *__restrict__ w,
+    const float *__restrict__ gate, const int32_t *__restrict__ inv, int T, int K, int d,
+    int has_shared, uint16_t *__restrict__ out, float *__restrict__ out_f32) {
+  const int t = blockIdx.x;
+  const int c = (blockIdx.y * 256 + threadIdx.x) * 4;
+  if (c >= d) return;  // d is a multiple of 8, so a thread's four features are all valid
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < K; ++s) {
+    const int p = inv[(size_t)t * K + s];
+    const float ws = w[(size_t)t * K + s];
+    const f32x4 v = *reinterpret_cast<const f32x4 *>(y + (size_t)p * d + c);
+    acc[0] = fmaf(ws, v[0], acc[0]);
+    acc[1] = fmaf(ws, v[1], acc[1]);
+    acc[2] = fmaf(ws, v[2], acc[2]);
+    acc[3] = fmaf(ws, v[3], acc[3]);
+  }
+  if (has_shared) {
+    const float g = gate[t];
+    const f32x4 v = *reinterpret_cast<const f32x4 *>(ys + (size_t)t * d + c);
+    acc[0] = fmaf(g, v[0], acc[0]);
+    acc[1] = fmaf(g, v[1], acc[1]);
+    acc[2] = fmaf(g, v[2], acc[2]);
+    acc[3] = fmaf(g, v[3], acc[3]);
+  }
+  u32x2 o;
+  o[0] = f32_to_bf16_bits(acc[0]) | (f32_to_bf16_bits(acc[1]) << 16);
+  o[1] = f32_to_bf16_bits(acc[2]) | (f32_to_bf16_bits(acc[3]) << 16);
+  *reinterpret_cast<u32x2 *>(out + (size_t)t * d + c) = o;
+  if (out_f32) *reinterpret_cast<f32x4 *>(out_f32 + (size_t)t * d + c) = acc;
+}
+
+hipError_t launch_combine(const float *y, const float *ys, const float *w, const float *gate,
+                          const int32_t *inv, int T, int K, int d, int has_shared, uint16_t *out,
+                          float *out_f32, hipStream_t s) {
+  dim3 grid(T, (d / 4 + 255) / 256);
+  hipLaunchKernelGGL(combine_kernel, grid, dim3(256), 0, s, y, ys, w, gate, inv, T, K, d, has_shared,
+                     out, out_f32);
+  return hipGetLastError();
+}

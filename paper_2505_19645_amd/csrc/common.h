@@ -1,0 +1,70 @@
+// Internal helpers shared by the HIP kernels of libmoesd (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/moesd.h"
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+
+#define MOESD_WAVE 64
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+// round to nearest even; finite inputs
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
+__device__ __forceinline__ u32x4 ld16(const uint16_t *p) { return *reinterpret_cast<const u32x4 *>(p); }
+
+// streaming 16-byte load: the weights are read exactly once, keep them out of the caches' way
+__device__ __forceinline__ u32x4 ld16_stream(const uint16_t *p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+}
+
+__device__ __forceinline__ f32x4 mfma16(u32x4 a, u32x4 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+                                                 __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+__device__ __forceinline__ float silu_f32(float z) { return z / (1.0f + expf(-z)); }
+
+// ---- launch descriptors (host fills, passed by value) ------------------------
+
+struct ExpertArgs {
+  // routed experts
+  const uint16_t *w_gate, *w_up, *w_down;  // [E,I,d] [E,I,d] [E,d,I]
+  // shared expert
+  const uint16_t *ws_gate, *ws_up, *ws_down;  // [S,d] [S,d] [d,S]
+  const uint16_t *x;                          // [T,d]
+  uint16_t *h;                                // [T*K, I] bf16
+  uint16_t *hs;                               // [T, S]   bf16
+  float *y;                                   // [T*K, d] f32
+  float *ys;                                  // [T, d]   f32
+  const int32_t *offsets;                     // [E+1]
+  const int32_t *perm;                        // [T*K]
+  int32_t d, E, K, I, S, T;
+};
+
+// host-side launch entry points, one per source file
+hipError_t launch_router_logits(const uint16_t *x, const uint16_t *w_router, const float *bias,
+                                const uint16_t *w_shared_gate, int T, int d, int E, double *logits,
+                                hipStream_t s);
+hipError_t launch_topk(const double *logits, int T, int E, int K, int score_func, int renorm,
+                       float scale, int has_shared_gate, int32_t *ids, float *w, float *gate,
+                       hipStream_t s);
+hipError_t launch_permute(const int32_t *ids, int64_t n, int E, int32_t *counts, int32_t *offsets,
+                          int32_t *perm, int32_t *inv, int32_t *n_active, hipStream_t s);
+hipError_t launch_gate_up(const ExpertArgs &a, hipStream_t s);
+hipError_t launch_down(const ExpertArgs &a, hipStream_t s);
+hipError_t launch_combine(const float *y, const float *ys, const float *w, const float *gate,
+                          const int32_t *inv, int T, int K, int d, int has_shared, uint16_t *out,
+                          float *out_f32, hipStream_t s);

@@ -1,0 +1,231 @@
+// Host side of libmoesd: argument checks, workspace carving, launch order.
+#include <atomic>
+#include <cstring>
+
+#include "common.h"
+
+namespace {
+
+std::atomic<int32_t> g_last_hip_error{0};
+
+int32_t hip_fail(hipError_t e) {
+  g_last_hip_error.store((int32_t)e);
+  return MOESD_HIP_ERROR;
+}
+
+inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+int32_t check_desc(const moesd_layer_desc *c) {
+  if (!c) return MOESD_INVALID_ARG;
+  if (c->E < 1 || c->top_k < 1 || c->top_k > c->E) return MOESD_INVALID_ARG;
+  if (c->d < 8 || c->d % 8 || c->inter < 8 || c->inter % 8) return MOESD_INVALID_ARG;
+  if (c->shared_inter < 0 || c->shared_inter % 8) return MOESD_INVALID_ARG;
+  if (c->E > MOESD_MAX_E || c->top_k > MOESD_MAX_K) return MOESD_UNSUPPORTED;
+  if (c->score_func != MOESD_SCORE_SOFTMAX && c->score_func != MOESD_SCORE_SIGMOID)
+    return MOESD_UNSUPPORTED;
+  if ((c->renormalize | 1) != 1 || (c->shared_gate | 1) != 1) return MOESD_UNSUPPORTED;
+  return MOESD_OK;
+}
+
+int32_t check_T(const moesd_layer_desc *c, int32_t T) {
+  if (T < 0) return MOESD_INVALID_ARG;
+  if ((int64_t)T * c->top_k >= ((int64_t)1 << 31)) return MOESD_INVALID_ARG;
+  return MOESD_OK;
+}
+
+// Workspace pieces, in order.  Every piece starts on a 256-byte boundary.
+struct Workspace {
+  double *logits;  // [T, E+1] fp64 router logits (+ shared-gate logit)
+  int32_t *ids;    // [T, K]
+  float *w;        // [T, K]
+  int32_t *counts, *offsets, *perm, *inv, *n_active;
+  float *gate;     // [T]
+  uint16_t *h;     // [T*K, I] bf16
+  uint16_t *hs;    // [T, S]   bf16
+  float *y;        // [T*K, d] f32
+  float *ys;       // [T, d]   f32
+  size_t bytes;
+};
+
+Workspace carve(const moesd_layer_desc *c, int64_t T, char *base) {
+  Workspace ws;
+  size_t off = 0;
+  auto take = [&](size_t n) {
+    char *p = base ? base + off : nullptr;
+    off += align256(n ? n : 1);
+    return p;
+  };
+  const int64_t K = c->top_k, E = c->E, d = c->d, I = c->inter, S = c->shared_inter;
+  ws.logits = (double *)take(sizeof(double) * T * (E + 1));
+  ws.ids = (int32_t *)take(sizeof(int32_t) * T * K);
+  ws.w = (float *)take(sizeof(float) * T * K);
+  ws.counts = (int32_t *)take(sizeof(int32_t) * E);
+  ws.offsets = (int32_t *)take(sizeof(int32_t) * (E + 1));
+  ws.perm = (int32_t *)take(sizeof(int32_t) * T * K);
+  ws.inv = (int32_t *)take(sizeof(int32_t) * T * K);
+  ws.n_active = (int32_t *)take(sizeof(int32_t));
+  ws.gate = (float *)take(sizeof(float) * T);
+  ws.h = (uint16_t *)take(sizeof(uint16_t) * T * K * I);
+  ws.hs = (uint16_t *)take(sizeof(uint16_t) * T * S);
+  ws.y = (float *)take(sizeof(float) * T * K * d);
+  ws.ys = (float *)take(sizeof(float) * T * d);
+  ws.bytes = off;
+  return ws;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *moesd_status_string(int32_t status) {
+  switch (status) {
+    case MOESD_OK: return "ok";
+    case MOESD_INVALID_ARG: return "invalid argument";
+    case MOESD_UNSUPPORTED: return "unsupported configuration";
+    case MOESD_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case MOESD_HIP_ERROR: return "HIP error (see moesd_last_hip_error)";
+    default: return "unknown status";
+  }
+}
+
+int32_t moesd_last_hip_error(void) { return g_last_hip_error.load(); }
+
+size_t moesd_workspace_bytes(const moesd_layer_desc *desc, int32_t T_max) {
+  if (check_desc(desc) != MOESD_OK || check_T(desc, T_max) != MOESD_OK) return 0;
+  return carve(desc, T_max, nullptr).bytes;
+}
+
+int32_t moesd_route(const moesd_layer_desc *desc, const void *x, const void *w_router,
+                    const float *router_bias, int32_t T, int32_t *topk_ids, float *topk_w,
+                    void *workspace, size_t workspace_bytes, void *stream) {
+  int32_t st = check_desc(desc);
+  if (st) return st;
+  if ((st = check_T(desc, T))) return st;
+  if (T == 0) return MOESD_OK;
+  if (!x || !w_router || !topk_ids || !topk_w || !workspace) return MOESD_INVALID_ARG;
+  if (((uintptr_t)workspace & 255) != 0) return MOESD_INVALID_ARG;
+  Workspace ws = carve(desc, T, (char *)workspace);
+  if (workspace_bytes < ws.bytes) return MOESD_WORKSPACE_TOO_SMALL;
+  hipStream_t s = (hipStream_t)stream;
+  hipError_t e = launch_router_logits((const uint16_t *)x, (const uint16_t *)w_router, router_bias,
+                                      nullptr, T, desc->d, desc->E, ws.logits, s);
+  if (e != hipSuccess) return hip_fail(e);
+  e = launch_topk(ws.logits, T, desc->E, desc->top_k, desc->score_func, desc->renormalize,
+                  desc->routed_scale, 0, topk_ids, topk_w, nullptr, s);
+  if (e != hipSuccess) return hip_fail(e);
+  return MOESD_OK;
+}
+
+int32_t moesd_permute(int32_t E, int32_t K, int32_t T, const int32_t *topk_ids, int32_t *counts,
+                      int32_t *offsets, int32_t *perm, int32_t *inv_perm, int32_t *n_active,
+                      void *stream) {
+  if (E < 1 || K < 1 || K > E || T < 0) return MOESD_INVALID_ARG;
+  if ((int64_t)T * K >= ((int64_t)1 << 31)) return MOESD_INVALID_ARG;
+  if (E > MOESD_MAX_E || K > MOESD_MAX_K) return MOESD_UNSUPPORTED;
+  if (!counts || !offsets || !n_active) return MOESD_INVALID_ARG;
+  if (T > 0 && (!topk_ids || !perm || !inv_perm)) return MOESD_INVALID_ARG;
+  hipError_t e = launch_permute(topk_ids, (int64_t)T * K, E, counts, offsets, perm, inv_perm,
+                                n_active, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e);
+  return MOESD_OK;
+}
+
+int32_t moesd_moe_forward_staged(const moesd_layer_desc *desc, const moesd_weights *wt,
+                                 const void *x, int32_t T, void *out, float *out_f32,
+                                 void *workspace, size_t workspace_bytes, int32_t *topk_ids,
+                                 float *topk_w, int32_t *counts, int32_t *offsets, int32_t *perm,
+                                 int32_t *inv_perm, int32_t *n_active, void *stream,
+                                 void *const *events) {
+  int32_t st = check_desc(desc);
+  if (st) return st;
+  if ((st = check_T(desc, T))) return st;
+  if (!wt) return MOESD_INVALID_ARG;
+  const bool has_shared = desc->shared_inter > 0;
+  if (!wt->w_router || !wt->w_gate || !wt->w_up || !wt->w_down) return MOESD_INVALID_ARG;
+  if (has_shared && (!wt->ws_gate || !wt->ws_up || !wt->ws_down)) return MOESD_INVALID_ARG;
+  if (has_shared && desc->shared_gate && !wt->w_shared_gate) return MOESD_INVALID_ARG;
+  hipStream_t s = (hipStream_t)stream;
+  hipError_t e;
+  if (T == 0) {
+    // nothing to compute; keep the counting outputs well defined if asked for
+    if (counts && offsets && n_active) {
+      e = launch_permute(nullptr, 0, desc->E, counts, offsets, nullptr, nullptr, n_active, s);
+      if (e != hipSuccess) return hip_fail(e);
+    }
+    return MOESD_OK;
+  }
+  if (!x || !out || !workspace) return MOESD_INVALID_ARG;
+  if (((uintptr_t)workspace & 255) != 0) return MOESD_INVALID_ARG;
+  Workspace ws = carve(desc, T, (char *)workspace);
+  if (workspace_bytes < ws.bytes) return MOESD_WORKSPACE_TOO_SMALL;
+
+  int32_t *ids = topk_ids ? topk_ids : ws.ids;
+  float *w = topk_w ? topk_w : ws.w;
+  int32_t *cnt = counts ? counts : ws.counts;
+  int32_t *off = offsets ? offsets : ws.offsets;
+  int32_t *pm = perm ? perm : ws.perm;
+  int32_t *iv = inv_perm ? inv_perm : ws.inv;
+  int32_t *na = n_active ? n_active : ws.n_active;
+  const bool gated = has_shared && desc->shared_gate;
+
+#define MOESD_EVENT(i)                                             \
+  if (events) {                                                    \
+    e = hipEventRecord((hipEvent_t)events[i], s);                  \
+    if (e != hipSuccess) return hip_fail(e);                       \
+  }
+#define MOESD_TRY(call)                                            \
+  e = (call);                                                      \
+  if (e != hipSuccess) return hip_fail(e);
+
+  MOESD_EVENT(0)
+  MOESD_TRY(launch_router_logits((const uint16_t *)x, (const uint16_t *)wt->w_router,
+                                 wt->router_bias, gated ? (const uint16_t *)wt->w_shared_gate : nullptr,
+                                 T, desc->d, desc->E, ws.logits, s))
+  MOESD_TRY(launch_topk(ws.logits, T, desc->E, desc->top_k, desc->score_func, desc->renormalize,
+                        desc->routed_scale, gated ? 1 : 0, ids, w, ws.gate, s))
+  MOESD_TRY(launch_permute(ids, (int64_t)T * desc->top_k, desc->E, cnt, off, pm, iv, na, s))
+  MOESD_EVENT(1)
+
+  ExpertArgs a;
+  a.w_gate = (const uint16_t *)wt->w_gate;
+  a.w_up = (const uint16_t *)wt->w_up;
+  a.w_down = (const uint16_t *)wt->w_down;
+  a.ws_gate = (const uint16_t *)wt->ws_gate;
+  a.ws_up = (const uint16_t *)wt->ws_up;
+  a.ws_down = (const uint16_t *)wt->ws_down;
+  a.x = (const uint16_t *)x;
+  a.h = ws.h;
+  a.hs = ws.hs;
+  a.y = ws.y;
+  a.ys = ws.ys;
+  a.offsets = off;
+  a.perm = pm;
+  a.d = desc->d;
+  a.E = desc->E;
+  a.K = desc->top_k;
+  a.I = desc->inter;
+  a.S = desc->shared_inter;
+  a.T = T;
+  MOESD_TRY(launch_gate_up(a, s))
+  MOESD_EVENT(2)
+  MOESD_TRY(launch_down(a, s))
+  MOESD_EVENT(3)
+  MOESD_TRY(launch_combine(ws.y, ws.ys, w, ws.gate, iv, T, desc->top_k, desc->d, has_shared ? 1 : 0,
+                           (uint16_t *)out, out_f32, s))
+  MOESD_EVENT(4)
+#undef MOESD_EVENT
+#undef MOESD_TRY
+  return MOESD_OK;
+}
+
+int32_t moesd_moe_forward(const moesd_layer_desc *desc, const moesd_weights *weights, const void *x,
+                          int32_t T, void *out, float *out_f32, void *workspace,
+                          size_t workspace_bytes, int32_t *topk_ids, float *topk_w, int32_t *counts,
+                          int32_t *offsets, int32_t *perm, int32_t *inv_perm, int32_t *n_active,
+                          void *stream) {
+  return moesd_moe_forward_staged(desc, weights, x, T, out, out_f32, workspace, workspace_bytes,
+                                  topk_ids, topk_w, counts, offsets, perm, inv_perm, n_active,
+                                  stream, nullptr);
+}
+
+}  // extern "C"

@@ -1,0 +1,130 @@
+// Token-to-expert permutation: a stable counting sort of the T*K flat slots by
+// expert id, done by one workgroup with per-wave LDS histograms.
+//
+// counts[e] > 0 is the activation indicator X_e of the paper's Sec. 3.2 and
+// n_active = sum_e X_e is its N.  Every step is integer work whose result does
+// not depend on scheduling: a wave walks its contiguous segment in order, lanes
+// that hold the same expert find each other with ballots, and only the lowest of
+// them touches that wave's private histogram row, so ranks are deterministic.
+#include "common.h"
+
+#define PERM_WAVES 16
+#define PERM_THREADS (PERM_WAVES * 64)
+
+// mask of the lanes (among `valid`) whose value equals this lane's
+__device__ __forceinline__ unsigned long long match_lanes(int v, int nbits, unsigned long long valid) {
+  unsigned long long m = valid;
+  for (int b = 0; b < nbits; ++b) {
+    const bool bit = (v >> b) & 1;
+    const unsigned long long bal = __ballot(bit);
+    m &= bit ? bal : ~bal;
+  }
+  return m;
+}
+
+__global__ __launch_bounds__(PERM_THREADS) void permute_kernel(
+    const int32_t *__restrict__ ids, int64_t n, int E, int nbits, int32_t *__restrict__ counts,
+    int32_t *__restrict__ offsets, int32_t *__restrict__ perm, int32_t *__restrict__ inv,
+    int32_t *__restrict__ n_active) {
+  extern __shared__ int32_t smem[];
+  int32_t *hist = smem;                     // [PERM_WAVES][E]
+  int32_t *scan = smem + PERM_WAVES * E;    // [PERM_THREADS] scratch for the scan over experts
+  __shared__ int32_t wave_tot[PERM_WAVES];
+  __shared__ int32_t active_tot;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // contiguous segment per wave, a whole number of 64-slot steps
+  int64_t seg = (n + PERM_WAVES - 1) / PERM_WAVES;
+  seg = (seg + 63) / 64 * 64;
+  const int64_t beg = (int64_t)wave * seg;
+  const int64_t end = beg + seg < n ? beg + seg : n;
+
+  for (int i = tid; i < PERM_WAVES * E; i += PERM_THREADS) hist[i] = 0;
+  if (tid == 0) active_tot = 0;
+  __syncthreads();
+
+  // pass 1: per-wave histogram
+  int32_t *myhist = hist + wave * E;
+  for (int64_t f0 = beg; f0 < end; f0 += 64) {
+    const int64_t f = f0 + lane;
+    const bool ok = f < end;
+    const int e = ok ? min(max(ids[f], 0), E - 1) : 0;  // out-of-range ids are the caller's bug; stay in bounds
+    const unsigned long long valid = __ballot(ok);
+    const unsigned long long peers = match_lanes(e, nbits, valid);
+    if (ok && (peers & ((1ull << lane) - 1ull)) == 0ull) atomicAdd(&myhist[e], __popcll(peers));
+  }
+  __syncthreads();
+
+  // per expert: total, and each wave's starting rank inside the expert
+  int total = 0;
+  for (int e = tid; e < E; e += PERM_THREADS) {  // E <= PERM_THREADS: at most one pass
+    int run = 0;
+    for (int w = 0; w < PERM_WAVES; ++w) {
+      const int c = hist[w * E + e];
+      hist[w * E + e] = run;
+      run += c;
+    }
+    total = run;
+    counts[e] = total;
+  }
+  // exclusive scan of the totals over experts (tid == expert index)
+  int v = (tid < E) ? total : 0;
+  int incl = v;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int o = __shfl_up(incl, off, 64);
+    if (lane >= off) incl += o;
+  }
+  if (lane == 63) wave_tot[wave] = incl;
+  const unsigned long long act = __ballot(tid < E && total > 0);
+  if (lane == 0 && act) atomicAdd(&active_tot, __popcll(act));
+  __syncthreads();
+  int wbase = 0;
+  for (int w = 0; w < wave; ++w) wbase += wave_tot[w];
+  const int excl = wbase + incl - v;
+  if (tid < E) {
+    offsets[tid] = excl;
+    scan[tid] = excl;
+  }
+  if (tid == 0) {
+    offsets[E] = (int32_t)n;
+    *n_active = active_tot;
+  }
+  __syncthreads();
+  for (int i = tid; i < PERM_WAVES * E; i += PERM_THREADS) hist[i] += scan[i % E];
+  __syncthreads();
+
+  // pass 2: same walk; the group leader reserves the group's rows
+  for (int64_t f0 = beg; f0 < end; f0 += 64) {
+    const int64_t f = f0 + lane;
+    const bool ok = f < end;
+    const int e = ok ? min(max(ids[f], 0), E - 1) : 0;  // out-of-range ids are the caller's bug; stay in bounds
+    const unsigned long long valid = __ballot(ok);
+    const unsigned long long peers = match_lanes(e, nbits, valid);
+    const unsigned long long below = peers & ((1ull << lane) - 1ull);
+    int base = 0;
+    if (ok && below == 0ull) base = atomicAdd(&myhist[e], __popcll(peers));
+    const int leader = ok ? __ffsll((long long)peers) - 1 : 0;
+    base = __shfl(base, leader, 64);
+    if (ok) {
+      const int p = base + __popcll(below);
+      perm[p] = (int32_t)f;
+      inv[f] = p;
+    }
+  }
+}
+
+hipError_t launch_permute(const int32_t *ids, int64_t n, int E, int32_t *counts, int32_t *offsets,
+                          int32_t *perm, int32_t *inv, int32_t *n_active, hipStream_t s) {
+  int nbits = 1;
+  while ((1 << nbits) < E) ++nbits;
+  const size_t smem = sizeof(int32_t) * ((size_t)PERM_WAVES * E + PERM_THREADS);
+  if (smem > 48 * 1024) {  // above the default dynamic-LDS limit (E > 704); gfx950 has 160 KB per CU
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(permute_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(permute_kernel, dim3(1), dim3(PERM_THREADS), smem, s, ids, n, E, nbits, counts,
+                     offsets, perm, inv, n_active);
+  return hipGetLastError();
+}
