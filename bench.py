@@ -1,0 +1,281 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE FFN layer forward over a verification batch of
+T = B*(gamma+1) tokens on one MI355X.
+
+A step is one pass of the whole hot path (route, permute, grouped gate/up +
+SwiGLU, grouped down, shared expert, combine) over one batch of synthetic
+tokens, with the weights already resident in HBM.  The default workload is the
+Qwen1.5-MoE-A2.7B-shaped layer at B=16, gamma=3 (T=64).  Weights are kept cold by
+rotating over several replicas of the layer, as consecutive layers of a real
+model would be.
+
+Prints ONE JSON line on stdout; progress goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X HBM3E
+MFMA_BF16_PEAK_TF = 2500.0  # MI355X dense bf16
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def layer_bytes(shape, n_active, T):
+    """Algorithmic HBM bytes of one layer call: every activated weight once, plus
+    the tokens in and out.  Intermediates are not counted."""
+    w = n_active * shape.expert_bytes + shape.shared_bytes + shape.router_bytes
+    return w + 2 * T * shape.d * 2
+
+
+def gate_up_bytes(shape, n_active, T):
+    """Algorithmic bytes of the gate/up kernel: the gate and up matrices of the
+    activated experts and of the shared expert once, tokens in, activations out."""
+    w = (n_active * 2 * shape.d * shape.inter + 2 * shape.d * shape.shared_inter) * 2
+    act = T * shape.d * 2 + (T * shape.top_k * shape.inter + T * shape.shared_inter) * 2
+    return w + act
+
+
+def down_bytes(shape, n_active, T):
+    w = (n_active * shape.d * shape.inter + shape.d * shape.shared_inter) * 2
+    act = (T * shape.top_k * shape.inter + T * shape.shared_inter) * 2 \
+        + (T * shape.top_k * shape.d + (T * shape.d if shape.shared_inter else 0)) * 4
+    return w + act
+
+
+def layer_flops(shape, T):
+    return 6 * T * shape.top_k * shape.d * shape.inter + 6 * T * shape.d * shape.shared_inter \
+        + 2 * T * shape.E * shape.d
+
+
+class Runner:
+    """Device-resident replicas of one layer plus per-T buffers."""
+
+    def __init__(self, shape, host_w, n_rep):
+        import torch
+        import paper_2505_19645_amd as moesd
+        self.torch, self.moesd, self.shape = torch, moesd, shape
+        self.desc = moesd.make_desc(shape)
+        import numpy as np
+        dev = "cuda:0"
+        base = {}
+        for k, v in host_w.items():
+            if v is None:
+                base[k] = None
+            elif k == "router_bias":
+                base[k] = torch.from_numpy(v.astype(np.float32)).to(dev)
+            else:
+                base[k] = torch.from_numpy(np.ascontiguousarray(v).view(np.int16)).to(dev)
+        self.reps = [base]
+        for _ in range(1, n_rep):
+            self.reps.append({k: (None if v is None else v.clone()) for k, v in base.items()})
+        self.wstructs = [moesd.make_weights(r) for r in self.reps]
+        self.stream = torch.cuda.current_stream().cuda_stream
+
+    def prepare(self, x_np):
+        torch, moesd, s = self.torch, self.moesd, self.shape
+        import numpy as np
+        T = x_np.shape[0]
+        self.T = T
+        self.x = torch.from_numpy(np.ascontiguousarray(x_np).view(np.int16)).to("cuda:0")
+        self.ws = torch.empty(moesd.moesd_workspace_bytes(self.desc, T), dtype=torch.uint8, device="cuda:0")
+        self.out = torch.empty((T, s.d), dtype=torch.int16, device="cuda:0")
+        self.n_active = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+        self.counts = torch.zeros(s.E, dtype=torch.int32, device="cuda:0")
+
+    def step(self, i, events=None):
+        self.moesd.moesd_moe_forward(self.desc, self.wstructs[i % len(self.wstructs)], self.x, self.T,
+                                     self.out, self.ws, counts=self.counts, n_active=self.n_active,
+                                     stream=self.stream, events=events)
+
+    def time_steps(self, steps, warmup):
+        """-> mean ms per step over exactly `steps` steps (events on our stream)."""
+        from paper_2505_19645_amd.hiputil import Event
+        torch = self.torch
+        for i in range(warmup):
+            self.step(i)
+        torch.cuda.synchronize()
+        e0, e1 = Event(), Event()
+        e0.record(self.stream)
+        for i in range(steps):
+            self.step(warmup + i)
+        e1.record(self.stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_ms(e1) / steps
+
+    def time_stages(self, steps, warmup):
+        """Same steps again with events at the stage boundaries of every forward.
+        -> dict of mean ms: route_permute, gate_up, down, combine, total."""
+        from paper_2505_19645_amd.hiputil import Event
+        torch = self.torch
+        evs = [[Event() for _ in range(5)] for _ in range(steps)]
+        for i in range(warmup):
+            self.step(i)
+        torch.cuda.synchronize()
+        for i in range(steps):
+            self.step(warmup + i, events=[e.handle for e in evs[i]])
+        torch.cuda.synchronize()
+        names = ["route_permute", "gate_up", "down", "combine"]
+        acc = {n: 0.0 for n in names}
+        tot = 0.0
+        for row in evs:
+            for j, n in enumerate(names):
+                acc[n] += row[j].elapsed_ms(row[j + 1])
+            tot += row[0].elapsed_ms(row[4])
+        out = {n: acc[n] / steps for n in names}
+        out["total"] = tot / steps
+        return out
+
+
+def pick_replicas(shape, T, budget_gb=24.0):
+    import paper_2505_19645_amd as moesd
+    n_exp = moesd.moesd_expected_active_experts(shape.E, shape.top_k, T)
+    active = n_exp * shape.expert_bytes + shape.shared_bytes
+    full = shape.E * shape.expert_bytes + shape.shared_bytes
+    want = int(math.ceil(1.5e9 / max(active, 1.0))) + 1     # >= 1.5 GB of other weights between visits
+    cap = max(2, int(budget_gb * 1e9 // full))
+    return max(2, min(want, cap, 12))
+
+
+SHORT_CURVE = [(1, 0), (2, 0), (4, 0), (8, 0), (16, 0), (8, 3), (16, 3), (32, 3), (64, 3), (128, 4)]
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", default="qwen1.5-moe-a2.7b")
+    ap.add_argument("--B", type=int, default=16)
+    ap.add_argument("--gamma", type=int, default=3)
+    ap.add_argument("--skew", type=float, default=0.0, help="std of the per-expert logit bias")
+    ap.add_argument("--curve", choices=["none", "short", "full"], default="short")
+    ap.add_argument("--curve-steps", type=int, default=30)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--replicas", type=int, default=0)
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU; the layer is not sharded across GPUs "
+            "(expert parallelism is described in DESIGN.md only). Use --gpus 1.")
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2505_19645_amd as moesd
+    from paper_2505_19645_amd import synth
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible; the HIP path has no CPU fallback")
+        sys.exit(3)
+    moesd.lib()
+    shape = synth.PRESETS[args.config]
+    T = args.B * (args.gamma + 1)
+    log(f"[bench] {shape.name}: d={shape.d} E={shape.E} K={shape.top_k} I={shape.inter} "
+        f"S={shape.shared_inter}; B={args.B} gamma={args.gamma} T={T} on {torch.cuda.get_device_name(0)}")
+
+    t0 = time.time()
+    host_w = synth.make_layer(shape, skew_std=args.skew, threads=min(16, os.cpu_count() or 1))
+    log(f"[bench] generated weights on host in {time.time() - t0:.1f}s")
+    curve_pts = {"none": [], "short": SHORT_CURVE, "full": synth.sweep_points(shape.name)}[args.curve]
+    if shape.name == "mixtral-8x7b" and args.curve == "short":
+        curve_pts = [(t, 0) for t in (1, 4, 16, 64, 256)]
+    t_min = min([T] + [b * (g + 1) for b, g in curve_pts])
+    n_rep = args.replicas or pick_replicas(shape, t_min)
+    run = Runner(shape, host_w, n_rep)
+    log(f"[bench] {n_rep} weight replicas resident ({n_rep * (shape.E * shape.expert_bytes + shape.shared_bytes) / 1e9:.1f} GB)")
+
+    # ---- headline point -------------------------------------------------------
+    x = synth.make_tokens(shape, T, point=100 * args.B + args.gamma)
+    run.prepare(x)
+    ms = run.time_steps(args.steps, args.warmup)
+    n_active = int(run.n_active.item())
+    counts = run.counts.cpu().numpy()
+    log(f"[bench] T={T}: {ms * 1e3:.1f} us/layer, n_active={n_active}, max m_e={counts.max()}")
+    st = run.time_stages(args.steps, args.warmup)
+    log("[bench] stages (us): " + ", ".join(f"{k}={v * 1e3:.1f}" for k, v in st.items()))
+
+    lb = layer_bytes(shape, n_active, T)
+    gub = gate_up_bytes(shape, n_active, T)
+    dnb = down_bytes(shape, n_active, T)
+    fl = layer_flops(shape, T)
+    hbm_time = lb / (HBM_PEAK_GBS * 1e9)
+    mfma_time = fl / (MFMA_BF16_PEAK_TF * 1e12)
+    achieved = gub / (st["gate_up"] * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "gate_up_stream_kernel", "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": None, "algorithmic_bytes": gub,
+                "avg_launch_us": round(st["gate_up"] * 1e3, 2)}
+    stages = {k: round(v * 1e3, 2) for k, v in st.items()}
+    stages["down_GBps"] = round(dnb / (st["down"] * 1e-3) / 1e9, 1)
+    layer = {"bytes": lb, "flops": fl, "hbm_roofline_us": round(hbm_time * 1e6, 2),
+             "mfma_roofline_us": round(mfma_time * 1e6, 2),
+             "achieved_GBps": round(lb / (ms * 1e-3) / 1e9, 1),
+             "hbm_frac": round(lb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+             "n_active": n_active,
+             "n_active_model": round(moesd.moesd_expected_active_experts(shape.E, shape.top_k, T), 2)}
+
+    # ---- curve: layer time vs T against the activated-expert model ---------------
+    curve = []
+    for (b, g) in curve_pts:
+        t = b * (g + 1)
+        xs = synth.make_tokens(shape, t, point=100 * b + g)
+        run.prepare(xs)
+        m = run.time_steps(args.curve_steps, max(5, args.curve_steps // 3))
+        na = int(run.n_active.item())
+        byt = layer_bytes(shape, na, t)
+        roof = max(byt / (HBM_PEAK_GBS * 1e9), layer_flops(shape, t) / (MFMA_BF16_PEAK_TF * 1e12))
+        curve.append({"B": b, "gamma": g, "T": t, "us": round(m * 1e3, 2), "n_active": na,
+                      "N_model": round(moesd.moesd_expected_active_experts(shape.E, shape.top_k, t), 2),
+                      "Texp_model": round(moesd.moesd_expected_tokens_per_expert(shape.E, shape.top_k, t), 2),
+                      "roofline_us": round(roof * 1e6, 2), "roofline_frac": round(roof / (m * 1e-3), 4)})
+        log(f"[bench] curve B={b} gamma={g} T={t}: {m * 1e3:.1f} us, n_active={na}, "
+            f"roofline {roof * 1e6:.1f} us ({roof / (m * 1e-3):.2f})")
+    # layer-level target efficiency t(B, gamma=0) / t(B, gamma) where both were measured
+    by = {(c["B"], c["gamma"]): c["us"] for c in curve}
+    for c in curve:
+        if c["gamma"] > 0 and (c["B"], 0) in by:
+            c["target_efficiency"] = round(by[(c["B"], 0)] / c["us"], 4)
+
+    # ---- CPU baseline: the oracle as it stands, one forward of the same batch ----
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import moe as oracle
+        oracle.lib()
+        cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)))
+        log(f"[bench] oracle forward on the host ({cores} threads) ...")
+        t0 = time.time()
+        ref = oracle.moe_forward(shape, host_w, x)
+        dt = time.time() - t0
+        cpu = {"value": round(dt * 1e6, 1), "unit": "us/layer", "cores": cores, "kind": "oracle",
+               "sample": f"one full forward of the same batch (T={T}, all tokens), fp64 plain C + OpenMP"}
+        log(f"[bench] oracle: {dt:.2f}s per layer; n_active={ref['n_active']}")
+        assert ref["n_active"] == n_active
+
+    result = {
+        "metric": "MoE-layer us at T=B*(gamma+1)", "value": round(ms * 1e3, 2), "unit": "us/layer",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 5),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{shape.name}-shaped MoE layer, B={args.B}, gamma={args.gamma}, T={T}",
+                   "d": shape.d, "E": shape.E, "top_k": shape.top_k, "inter": shape.inter,
+                   "shared_inter": shape.shared_inter, "skew_std": args.skew,
+                   "weight_replicas": n_rep, "cold_weights": True},
+        "roofline": roofline, "cpu_baseline": cpu, "layer": layer, "stages_us": stages, "curve": curve,
+    }
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

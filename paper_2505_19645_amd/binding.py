@@ -45,6 +45,9 @@ def lib():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} not built: run python -m paper_2505_19645_amd.build")
+        # PyTorch ships its own HIP runtime; load it first so the library binds to
+        # that one copy (two runtimes in a process would not share streams)
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         L.moesd_expected_active_experts.restype = C.c_double
         L.moesd_expected_active_experts.argtypes = [C.c_int32, C.c_int32, C.c_int64]
