@@ -39,19 +39,27 @@ __device__ __forceinline__ float silu_f32(float z) { return z / (1.0f + expf(-z)
 
 // ---- launch descriptors (host fills, passed by value) ------------------------
 
-struct ExpertArgs {
+// Plan written by the permutation kernel for the expert kernels (int32 words):
+//   [0] n_small: experts with 1..16 rows      [1] n_big: (expert, 64-row block) entries
+//   [PLAN_HDR .. PLAN_HDR+E)  ids of the small experts, ascending
+//   then n_big pairs (expert id, block index), ascending by expert then block
+#define PLAN_HDR 2
+
+struct StreamArgs {
   // routed experts
-  const uint16_t *w_gate, *w_up, *w_down;  // [E,I,d] [E,I,d] [E,d,I]
+  const uint16_t *w_gate, *w_up, *w_down;     // [E,I,d] [E,I,d] [E,d,I]
   // shared expert
   const uint16_t *ws_gate, *ws_up, *ws_down;  // [S,d] [S,d] [d,S]
   const uint16_t *x;                          // [T,d]
   uint16_t *h;                                // [T*K, I] bf16
   uint16_t *hs;                               // [T, S]   bf16
   float *y;                                   // [T*K, d] f32
-  float *ys;                                  // [T, d]   f32
+  float *ys;                                  // [parts, T, d] f32: partial sums over k-parts of S
   const int32_t *offsets;                     // [E+1]
-  const int32_t *perm;                        // [T*K]
+  const int32_t *row_token;                   // [T*K] sorted row -> token
+  const int32_t *plan;
   int32_t d, E, K, I, S, T;
+  int32_t part_k;                             // k-part length of the shared down projection
 };
 
 // host-side launch entry points, one per source file
@@ -61,10 +69,12 @@ hipError_t launch_router_logits(const uint16_t *x, const uint16_t *w_router, con
 hipError_t launch_topk(const double *logits, int T, int E, int K, int score_func, int renorm,
                        float scale, int has_shared_gate, int32_t *ids, float *w, float *gate,
                        hipStream_t s);
-hipError_t launch_permute(const int32_t *ids, int64_t n, int E, int32_t *counts, int32_t *offsets,
-                          int32_t *perm, int32_t *inv, int32_t *n_active, hipStream_t s);
-hipError_t launch_gate_up(const ExpertArgs &a, hipStream_t s);
-hipError_t launch_down(const ExpertArgs &a, hipStream_t s);
-hipError_t launch_combine(const float *y, const float *ys, const float *w, const float *gate,
-                          const int32_t *inv, int T, int K, int d, int has_shared, uint16_t *out,
+// row_token / plan may be NULL (standalone permutation)
+hipError_t launch_permute(const int32_t *ids, int64_t n, int E, int K, int32_t *counts,
+                          int32_t *offsets, int32_t *perm, int32_t *inv, int32_t *n_active,
+                          int32_t *row_token, int32_t *plan, hipStream_t s);
+hipError_t launch_gate_up(const StreamArgs &a, hipStream_t s);
+hipError_t launch_down(const StreamArgs &a, hipStream_t s);
+hipError_t launch_combine(const float *y, const float *ys, int n_parts, const float *w,
+                          const float *gate, const int32_t *inv, int T, int K, int d, uint16_t *out,
                           float *out_f32, hipStream_t s);

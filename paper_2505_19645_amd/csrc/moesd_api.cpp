@@ -39,13 +39,24 @@ struct Workspace {
   int32_t *ids;    // [T, K]
   float *w;        // [T, K]
   int32_t *counts, *offsets, *perm, *inv, *n_active;
+  int32_t *row_token;  // [T*K] sorted row -> token
+  int32_t *plan;       // work lists for the expert kernels (see common.h)
   float *gate;     // [T]
   uint16_t *h;     // [T*K, I] bf16
   uint16_t *hs;    // [T, S]   bf16
   float *y;        // [T*K, d] f32
-  float *ys;       // [T, d]   f32
+  float *ys;       // [parts, T, d] f32
+  int32_t part_k, parts;
   size_t bytes;
 };
+
+// The shared expert's down projection is cut along its intermediate dimension
+// into parts about as long as a routed expert's, so that every tile of the down
+// kernel costs the same; the combine adds the parts.
+inline int32_t shared_part_k(const moesd_layer_desc *c) {
+  const int32_t pk = (c->inter + 255) / 256 * 256;
+  return pk;
+}
 
 Workspace carve(const moesd_layer_desc *c, int64_t T, char *base) {
   Workspace ws;
@@ -64,11 +75,15 @@ Workspace carve(const moesd_layer_desc *c, int64_t T, char *base) {
   ws.perm = (int32_t *)take(sizeof(int32_t) * T * K);
   ws.inv = (int32_t *)take(sizeof(int32_t) * T * K);
   ws.n_active = (int32_t *)take(sizeof(int32_t));
+  ws.row_token = (int32_t *)take(sizeof(int32_t) * T * K);
+  ws.plan = (int32_t *)take(sizeof(int32_t) * (PLAN_HDR + E + 2 * (E + T * K / 64 + 2)));
+  ws.part_k = shared_part_k(c);
+  ws.parts = S > 0 ? (int32_t)((S + ws.part_k - 1) / ws.part_k) : 0;
   ws.gate = (float *)take(sizeof(float) * T);
   ws.h = (uint16_t *)take(sizeof(uint16_t) * T * K * I);
   ws.hs = (uint16_t *)take(sizeof(uint16_t) * T * S);
   ws.y = (float *)take(sizeof(float) * T * K * d);
-  ws.ys = (float *)take(sizeof(float) * T * d);
+  ws.ys = (float *)take(sizeof(float) * ws.parts * T * d);
   ws.bytes = off;
   return ws;
 }
@@ -124,8 +139,8 @@ int32_t moesd_permute(int32_t E, int32_t K, int32_t T, const int32_t *topk_ids, 
   if (E > MOESD_MAX_E || K > MOESD_MAX_K) return MOESD_UNSUPPORTED;
   if (!counts || !offsets || !n_active) return MOESD_INVALID_ARG;
   if (T > 0 && (!topk_ids || !perm || !inv_perm)) return MOESD_INVALID_ARG;
-  hipError_t e = launch_permute(topk_ids, (int64_t)T * K, E, counts, offsets, perm, inv_perm,
-                                n_active, (hipStream_t)stream);
+  hipError_t e = launch_permute(topk_ids, (int64_t)T * K, E, K, counts, offsets, perm, inv_perm,
+                                n_active, nullptr, nullptr, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e);
   return MOESD_OK;
 }
@@ -149,7 +164,8 @@ int32_t moesd_moe_forward_staged(const moesd_layer_desc *desc, const moesd_weigh
   if (T == 0) {
     // nothing to compute; keep the counting outputs well defined if asked for
     if (counts && offsets && n_active) {
-      e = launch_permute(nullptr, 0, desc->E, counts, offsets, nullptr, nullptr, n_active, s);
+      e = launch_permute(nullptr, 0, desc->E, desc->top_k, counts, offsets, nullptr, nullptr,
+                         n_active, nullptr, nullptr, s);
       if (e != hipSuccess) return hip_fail(e);
     }
     return MOESD_OK;
@@ -183,10 +199,11 @@ int32_t moesd_moe_forward_staged(const moesd_layer_desc *desc, const moesd_weigh
                                  T, desc->d, desc->E, ws.logits, s))
   MOESD_TRY(launch_topk(ws.logits, T, desc->E, desc->top_k, desc->score_func, desc->renormalize,
                         desc->routed_scale, gated ? 1 : 0, ids, w, ws.gate, s))
-  MOESD_TRY(launch_permute(ids, (int64_t)T * desc->top_k, desc->E, cnt, off, pm, iv, na, s))
+  MOESD_TRY(launch_permute(ids, (int64_t)T * desc->top_k, desc->E, desc->top_k, cnt, off, pm, iv, na,
+                           ws.row_token, ws.plan, s))
   MOESD_EVENT(1)
 
-  ExpertArgs a;
+  StreamArgs a;
   a.w_gate = (const uint16_t *)wt->w_gate;
   a.w_up = (const uint16_t *)wt->w_up;
   a.w_down = (const uint16_t *)wt->w_down;
@@ -199,7 +216,9 @@ int32_t moesd_moe_forward_staged(const moesd_layer_desc *desc, const moesd_weigh
   a.y = ws.y;
   a.ys = ws.ys;
   a.offsets = off;
-  a.perm = pm;
+  a.row_token = ws.row_token;
+  a.plan = ws.plan;
+  a.part_k = ws.part_k;
   a.d = desc->d;
   a.E = desc->E;
   a.K = desc->top_k;
@@ -210,7 +229,7 @@ int32_t moesd_moe_forward_staged(const moesd_layer_desc *desc, const moesd_weigh
   MOESD_EVENT(2)
   MOESD_TRY(launch_down(a, s))
   MOESD_EVENT(3)
-  MOESD_TRY(launch_combine(ws.y, ws.ys, w, ws.gate, iv, T, desc->top_k, desc->d, has_shared ? 1 : 0,
+  MOESD_TRY(launch_combine(ws.y, ws.ys, ws.parts, w, ws.gate, iv, T, desc->top_k, desc->d,
                            (uint16_t *)out, out_f32, s))
   MOESD_EVENT(4)
 #undef MOESD_EVENT

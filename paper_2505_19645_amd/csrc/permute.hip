@@ -23,13 +23,14 @@ __device__ __forceinline__ unsigned long long match_lanes(int v, int nbits, unsi
 }
 
 __global__ __launch_bounds__(PERM_THREADS) void permute_kernel(
-    const int32_t *__restrict__ ids, int64_t n, int E, int nbits, int32_t *__restrict__ counts,
-    int32_t *__restrict__ offsets, int32_t *__restrict__ perm, int32_t *__restrict__ inv,
-    int32_t *__restrict__ n_active) {
+    const int32_t *__restrict__ ids, int64_t n, int E, int K, int nbits,
+    int32_t *__restrict__ counts, int32_t *__restrict__ offsets, int32_t *__restrict__ perm,
+    int32_t *__restrict__ inv, int32_t *__restrict__ n_active, int32_t *__restrict__ row_token,
+    int32_t *__restrict__ plan) {
   extern __shared__ int32_t smem[];
   int32_t *hist = smem;                     // [PERM_WAVES][E]
   int32_t *scan = smem + PERM_WAVES * E;    // [PERM_THREADS] scratch for the scan over experts
-  __shared__ int32_t wave_tot[PERM_WAVES];
+  __shared__ int32_t wave_tot[3][PERM_WAVES];
   __shared__ int32_t active_tot;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -67,28 +68,63 @@ __global__ __launch_bounds__(PERM_THREADS) void permute_kernel(
     total = run;
     counts[e] = total;
   }
-  // exclusive scan of the totals over experts (tid == expert index)
-  int v = (tid < E) ? total : 0;
-  int incl = v;
+  // exclusive scans over experts (tid == expert index): the totals give the
+  // offsets; the other two place each expert in the expert kernels' work lists
+  // (1..16 rows: one entry in the "small" list; more: one entry per 64-row block)
+  const int v = (tid < E) ? total : 0;
+  const int v_small = (v >= 1 && v <= 16) ? 1 : 0;
+  const int v_big = (v > 16) ? (v + 63) / 64 : 0;
+  int incl = v, incl_s = v_small, incl_b = v_big;
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) {
     const int o = __shfl_up(incl, off, 64);
-    if (lane >= off) incl += o;
+    const int os = __shfl_up(incl_s, off, 64);
+    const int ob = __shfl_up(incl_b, off, 64);
+    if (lane >= off) {
+      incl += o;
+      incl_s += os;
+      incl_b += ob;
+    }
   }
-  if (lane == 63) wave_tot[wave] = incl;
+  if (lane == 63) {
+    wave_tot[0][wave] = incl;
+    wave_tot[1][wave] = incl_s;
+    wave_tot[2][wave] = incl_b;
+  }
   const unsigned long long act = __ballot(tid < E && total > 0);
   if (lane == 0 && act) atomicAdd(&active_tot, __popcll(act));
   __syncthreads();
-  int wbase = 0;
-  for (int w = 0; w < wave; ++w) wbase += wave_tot[w];
+  int wbase = 0, wbase_s = 0, wbase_b = 0;
+  for (int w = 0; w < wave; ++w) {
+    wbase += wave_tot[0][w];
+    wbase_s += wave_tot[1][w];
+    wbase_b += wave_tot[2][w];
+  }
   const int excl = wbase + incl - v;
   if (tid < E) {
     offsets[tid] = excl;
     scan[tid] = excl;
+    if (plan) {
+      if (v_small) plan[PLAN_HDR + wbase_s + incl_s - 1] = tid;
+      const int pos = wbase_b + incl_b - v_big;
+      for (int b = 0; b < v_big; ++b) {
+        plan[PLAN_HDR + E + 2 * (pos + b)] = tid;
+        plan[PLAN_HDR + E + 2 * (pos + b) + 1] = b;
+      }
+    }
   }
   if (tid == 0) {
     offsets[E] = (int32_t)n;
     *n_active = active_tot;
+    if (plan) {
+      int ns = 0, nb = 0;
+      for (int w = 0; w < PERM_WAVES; ++w) {
+        ns += wave_tot[1][w];
+        nb += wave_tot[2][w];
+      }
+      plan[0] = ns;
+      plan[1] = nb;
+    }
   }
   __syncthreads();
   for (int i = tid; i < PERM_WAVES * E; i += PERM_THREADS) hist[i] += scan[i % E];
@@ -110,12 +146,14 @@ __global__ __launch_bounds__(PERM_THREADS) void permute_kernel(
       const int p = base + __popcll(below);
       perm[p] = (int32_t)f;
       inv[f] = p;
+      if (row_token) row_token[p] = (int32_t)(f / K);
     }
   }
 }
 
-hipError_t launch_permute(const int32_t *ids, int64_t n, int E, int32_t *counts, int32_t *offsets,
-                          int32_t *perm, int32_t *inv, int32_t *n_active, hipStream_t s) {
+hipError_t launch_permute(const int32_t *ids, int64_t n, int E, int K, int32_t *counts,
+                          int32_t *offsets, int32_t *perm, int32_t *inv, int32_t *n_active,
+                          int32_t *row_token, int32_t *plan, hipStream_t s) {
   int nbits = 1;
   while ((1 << nbits) < E) ++nbits;
   const size_t smem = sizeof(int32_t) * ((size_t)PERM_WAVES * E + PERM_THREADS);
@@ -124,7 +162,7 @@ hipError_t launch_permute(const int32_t *ids, int64_t n, int E, int32_t *counts,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(permute_kernel, dim3(1), dim3(PERM_THREADS), smem, s, ids, n, E, nbits, counts,
-                     offsets, perm, inv, n_active);
+  hipLaunchKernelGGL(permute_kernel, dim3(1), dim3(PERM_THREADS), smem, s, ids, n, E, K, nbits,
+                     counts, offsets, perm, inv, n_active, row_token, plan);
   return hipGetLastError();
 }
