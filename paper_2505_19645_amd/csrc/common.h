@@ -73,6 +73,11 @@ hipError_t launch_topk(const double *logits, int T, int E, int K, int score_func
 hipError_t launch_permute(const int32_t *ids, int64_t n, int E, int K, int32_t *counts,
                           int32_t *offsets, int32_t *perm, int32_t *inv, int32_t *n_active,
                           int32_t *row_token, int32_t *plan, hipStream_t s);
+// top-K and permutation in one launch; only for E <= 256 and few tokens
+hipError_t launch_topk_permute(const double *logits, int T, int E, int K, int score_func, int renorm,
+                               float scale, int has_shared_gate, int32_t *ids, float *w, float *gate,
+                               int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv,
+                               int32_t *n_active, int32_t *row_token, int32_t *plan, hipStream_t s);
 hipError_t launch_gate_up(const StreamArgs &a, hipStream_t s);
 hipError_t launch_down(const StreamArgs &a, hipStream_t s);
 hipError_t launch_combine(const float *y, const float *ys, int n_parts, const float *w,

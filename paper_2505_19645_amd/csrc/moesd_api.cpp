@@ -197,10 +197,16 @@ int32_t moesd_moe_forward_staged(const moesd_layer_desc *desc, const moesd_weigh
   MOESD_TRY(launch_router_logits((const uint16_t *)x, (const uint16_t *)wt->w_router,
                                  wt->router_bias, gated ? (const uint16_t *)wt->w_shared_gate : nullptr,
                                  T, desc->d, desc->E, ws.logits, s))
-  MOESD_TRY(launch_topk(ws.logits, T, desc->E, desc->top_k, desc->score_func, desc->renormalize,
-                        desc->routed_scale, gated ? 1 : 0, ids, w, ws.gate, s))
-  MOESD_TRY(launch_permute(ids, (int64_t)T * desc->top_k, desc->E, desc->top_k, cnt, off, pm, iv, na,
-                           ws.row_token, ws.plan, s))
+  if (T <= 32 && desc->E <= 256) {
+    MOESD_TRY(launch_topk_permute(ws.logits, T, desc->E, desc->top_k, desc->score_func,
+                                  desc->renormalize, desc->routed_scale, gated ? 1 : 0, ids, w, ws.gate,
+                                  cnt, off, pm, iv, na, ws.row_token, ws.plan, s))
+  } else {
+    MOESD_TRY(launch_topk(ws.logits, T, desc->E, desc->top_k, desc->score_func, desc->renormalize,
+                          desc->routed_scale, gated ? 1 : 0, ids, w, ws.gate, s))
+    MOESD_TRY(launch_permute(ids, (int64_t)T * desc->top_k, desc->E, desc->top_k, cnt, off, pm, iv, na,
+                             ws.row_token, ws.plan, s))
+  }
   MOESD_EVENT(1)
 
   StreamArgs a;

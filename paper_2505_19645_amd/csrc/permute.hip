@@ -7,6 +7,7 @@
 // that hold the same expert find each other with ballots, and only the lowest of
 // them touches that wave's private histogram row, so ranks are deterministic.
 #include "common.h"
+#include "route_device.h"
 
 #define PERM_WAVES 16
 #define PERM_THREADS (PERM_WAVES * 64)
@@ -22,12 +23,11 @@ __device__ __forceinline__ unsigned long long match_lanes(int v, int nbits, unsi
   return m;
 }
 
-__global__ __launch_bounds__(PERM_THREADS) void permute_kernel(
-    const int32_t *__restrict__ ids, int64_t n, int E, int K, int nbits,
-    int32_t *__restrict__ counts, int32_t *__restrict__ offsets, int32_t *__restrict__ perm,
-    int32_t *__restrict__ inv, int32_t *__restrict__ n_active, int32_t *__restrict__ row_token,
-    int32_t *__restrict__ plan) {
-  extern __shared__ int32_t smem[];
+__device__ __forceinline__ void permute_body(
+    const int32_t *ids, int64_t n, int E, int K, int nbits, int32_t *__restrict__ counts,
+    int32_t *__restrict__ offsets, int32_t *__restrict__ perm, int32_t *__restrict__ inv,
+    int32_t *__restrict__ n_active, int32_t *__restrict__ row_token, int32_t *__restrict__ plan,
+    int32_t *smem) {
   int32_t *hist = smem;                     // [PERM_WAVES][E]
   int32_t *scan = smem + PERM_WAVES * E;    // [PERM_THREADS] scratch for the scan over experts
   __shared__ int32_t wave_tot[3][PERM_WAVES];
@@ -151,6 +151,34 @@ __global__ __launch_bounds__(PERM_THREADS) void permute_kernel(
   }
 }
 
+__global__ __launch_bounds__(PERM_THREADS) void permute_kernel(
+    const int32_t *__restrict__ ids, int64_t n, int E, int K, int nbits,
+    int32_t *__restrict__ counts, int32_t *__restrict__ offsets, int32_t *__restrict__ perm,
+    int32_t *__restrict__ inv, int32_t *__restrict__ n_active, int32_t *__restrict__ row_token,
+    int32_t *__restrict__ plan) {
+  extern __shared__ int32_t smem[];
+  permute_body(ids, n, E, K, nbits, counts, offsets, perm, inv, n_active, row_token, plan, smem);
+}
+
+// Few tokens: the same workgroup first picks every token's top-K (wave w takes
+// tokens w, w+16, ...) and then sorts, which saves a kernel launch.
+template <int SLOTS>
+__global__ __launch_bounds__(PERM_THREADS) void topk_permute_kernel(
+    const double *__restrict__ logits, int T, int E, int Etot, int K, int score_func, int renorm,
+    float scale, int32_t *ids, float *__restrict__ w, float *__restrict__ gate, int nbits,
+    int32_t *__restrict__ counts, int32_t *__restrict__ offsets, int32_t *__restrict__ perm,
+    int32_t *__restrict__ inv, int32_t *__restrict__ n_active, int32_t *__restrict__ row_token,
+    int32_t *__restrict__ plan) {
+  extern __shared__ int32_t smem[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int t = wave; t < T; t += PERM_WAVES)
+    topk_token<SLOTS>(logits, t, lane, E, Etot, K, score_func, renorm, scale, ids, w, gate);
+  __threadfence_block();
+  __syncthreads();
+  permute_body(ids, (int64_t)T * K, E, K, nbits, counts, offsets, perm, inv, n_active, row_token, plan,
+               smem);
+}
+
 hipError_t launch_permute(const int32_t *ids, int64_t n, int E, int K, int32_t *counts,
                           int32_t *offsets, int32_t *perm, int32_t *inv, int32_t *n_active,
                           int32_t *row_token, int32_t *plan, hipStream_t s) {
@@ -164,5 +192,27 @@ hipError_t launch_permute(const int32_t *ids, int64_t n, int E, int K, int32_t *
   }
   hipLaunchKernelGGL(permute_kernel, dim3(1), dim3(PERM_THREADS), smem, s, ids, n, E, K, nbits,
                      counts, offsets, perm, inv, n_active, row_token, plan);
+  return hipGetLastError();
+}
+
+hipError_t launch_topk_permute(const double *logits, int T, int E, int K, int score_func, int renorm,
+                               float scale, int has_shared_gate, int32_t *ids, float *w, float *gate,
+                               int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv,
+                               int32_t *n_active, int32_t *row_token, int32_t *plan, hipStream_t s) {
+  const int Etot = E + (has_shared_gate ? 1 : 0);
+  int nbits = 1;
+  while ((1 << nbits) < E) ++nbits;
+  const size_t smem = sizeof(int32_t) * ((size_t)PERM_WAVES * E + PERM_THREADS);
+  if (E <= 64) {
+    hipLaunchKernelGGL(topk_permute_kernel<1>, dim3(1), dim3(PERM_THREADS), smem, s, logits, T, E, Etot,
+                       K, score_func, renorm, scale, ids, w, gate, nbits, counts, offsets, perm, inv,
+                       n_active, row_token, plan);
+  } else if (E <= 256) {
+    hipLaunchKernelGGL(topk_permute_kernel<4>, dim3(1), dim3(PERM_THREADS), smem, s, logits, T, E, Etot,
+                       K, score_func, renorm, scale, ids, w, gate, nbits, counts, offsets, perm, inv,
+                       n_active, row_token, plan);
+  } else {
+    return hipErrorInvalidValue;  // callers use the two-kernel path for wider routers
+  }
   return hipGetLastError();
 }
