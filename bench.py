@@ -164,6 +164,8 @@ def main():
     ap.add_argument("--curve-steps", type=int, default=30)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--replicas", type=int, default=0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (known traffic) for scaling rocprofv3 --pmc byte counters")
     args = ap.parse_args()
 
     if args.gpus != 1:
@@ -196,6 +198,14 @@ def main():
     run = Runner(shape, host_w, n_rep)
     log(f"[bench] {n_rep} weight replicas resident ({n_rep * (shape.E * shape.expert_bytes + shape.shared_bytes) / 1e9:.1f} GB)")
 
+    if args.calibrate_copy:
+        src = torch.ones(1 << 29, dtype=torch.int16, device="cuda:0")   # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     # ---- headline point -------------------------------------------------------
     x = synth.make_tokens(shape, T, point=100 * args.B + args.gamma)
     run.prepare(x)
@@ -213,9 +223,17 @@ def main():
     hbm_time = lb / (HBM_PEAK_GBS * 1e9)
     mfma_time = fl / (MFMA_BF16_PEAK_TF * 1e12)
     achieved = gub / (st["gate_up"] * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "gate_up_stream_kernel", "achieved": round(achieved, 1),
+    traffic = None
+    try:  # HBM bytes per launch measured earlier with rocprofv3 --pmc on this same command
+        with open(os.path.join(ROOT, "paper_2505_19645_amd", "measured_traffic.json")) as f:
+            tr = json.load(f).get(f"{shape.name}/B{args.B}/g{args.gamma}/skew{args.skew}")
+        if tr:
+            traffic = tr["gate_up"]
+    except OSError:
+        pass
+    roofline = {"bound": "hbm", "kernel": "expert_stream_kernel<gate_up>", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": None, "algorithmic_bytes": gub,
+                "traffic": traffic, "algorithmic_bytes": gub,
                 "avg_launch_us": round(st["gate_up"] * 1e3, 2)}
     stages = {k: round(v * 1e3, 2) for k, v in st.items()}
     stages["down_GBps"] = round(dnb / (st["down"] * 1e-3) / 1e9, 1)
