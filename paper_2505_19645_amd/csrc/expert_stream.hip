@@ -5,31 +5,32 @@
 // Sec. 3.2 shows that sparser models stay in this regime for longer).  These
 // kernels are therefore built around the weight stream, not around the MFMA:
 //
-//  * One persistent workgroup per compute unit.  All tiles of a launch are laid
-//    on one line, weighted by their cost, and every workgroup takes an equal,
-//    contiguous share of that line.  A workgroup therefore reads long
-//    contiguous runs of weight rows and all workgroups finish together.
-//  * A tile is 32 weight rows (16 of w_gate + the same 16 of w_up, or 32 rows of
-//    w_down) against one block of token rows of one expert: up to 16 rows
-//    ("small" tile) or up to 64 rows ("big" tile).
-//  * The contraction dimension is cut into 256-element blocks.  A block is
-//    fetched with global_load_lds_dwordx4 into 24 KB ring slots: every wave
-//    instruction moves two 512-byte row pieces, contiguous in HBM, straight
-//    into LDS without touching a register; the weights carry the non-temporal
-//    hint (each byte is read exactly once).  A small tile's block fills one
-//    slot (16 KB of weights + 8 KB of tokens), a big tile's block two (the
-//    second holds token rows 16..63).  Every slot is exactly six loads per
-//    wave, so the hand-written s_waitcnt counts are compile-time constants.
-//  * Loads are issued and awaited by hand (s_waitcnt vmcnt, one s_barrier per
-//    slot): the compiler sees no vector memory load in the loop, so it cannot
-//    serialise the prefetch, which runs four slots ahead across tile borders.
+//  * One persistent workgroup (4 waves) per compute unit.
+//  * Two tile shapes, so that the token rows never cost more than half the
+//    weight bytes that travel with them:
+//      small: an expert (or token block) with 1..16 rows.  32 weight rows (16 of
+//             w_gate + the same 16 of w_up, or 32 rows of w_down), contraction
+//             blocks of 256 elements; a block is one 24 KB slot: 16 KB of
+//             weights + 8 KB of tokens.
+//      wide:  17..64 rows.  128 weight rows (64 + 64, or 128 of w_down),
+//             contraction blocks of 128 elements; a block is two slots: 32 KB
+//             of weights + 16 KB of tokens.
+//    Experts with more than 64 rows are cut into 64-row blocks.
+//  * Every slot is exactly six global_load_lds_dwordx4 per wave, each moving
+//    1 KB (two 512-byte or four 256-byte row pieces, contiguous in HBM) straight
+//    into LDS; the weights carry the non-temporal hint (each byte is read once).
+//    So the hand-written s_waitcnt counts are compile-time constants.  Loads run
+//    four slots ahead in a ring of six, across tile borders; the compiler sees no
+//    vector memory load in the loop and cannot serialise the prefetch.
+//  * Work split: wide tiles are dealt round-robin, then every workgroup gets a
+//    contiguous run of small tiles sized so that all finish together.
 //  * MFMA operands come from LDS.  The 16-byte pieces of a row are stored
-//    XOR-swizzled by (row & 7), which keeps the operand reads free of bank
-//    conflicts while the DMA writes stay linear.
+//    XOR-swizzled by (row & 7): operand reads are free of bank conflicts while
+//    the DMA writes stay linear.
 //  * Small tiles: the four waves split the eight 32-element MFMA steps of a
 //    block and add their partial 16x16 tiles through LDS in a fixed order.
-//    Big tiles: wave w owns token rows 16w..16w+15 and needs no reduction.
-//    Either way results do not depend on scheduling.
+//    Wide tiles: wave w owns weight rows 16w..16w+15 of each half against all
+//    four token tiles; no reduction.  Results never depend on scheduling.
 //
 // MFMA operand use (v_mfma_f32_16x16x32_bf16): lane l = 16*q + r supplies 8
 // consecutive contraction elements (piece 4*s + q of step s) of weight row r
@@ -37,10 +38,7 @@
 // 4*q .. 4*q+3.
 #include "common.h"
 
-#define KB 256             // contraction elements per block
-#define ROW_BYTES 512      // KB * 2
-#define A_BYTES 16384      // 2 operand halves x 16 rows x 512 B
-#define SLOT_BYTES 24576   // A_BYTES + 16 token rows
+#define SLOT_BYTES 24576   // one ring slot
 #define RING 6             // slots in the ring
 #define AHEAD 4            // slots in flight
 #define LW 6               // loads per wave per slot
@@ -48,17 +46,29 @@
 #define SMALL_M 16
 #define BIG_TB 64
 #define STREAM_LDS_BYTES (RING * SLOT_BYTES + RED_BYTES)
+// small tiles
+#define KB 256             // contraction elements per block
+#define ROW_BYTES 512
+#define A_BYTES 16384      // 2 halves x 16 rows x 512 B
+// wide tiles
+#define KBW 128
+#define ROWW_BYTES 256
+#define WIDE_B_OFF 8192    // second slot: weight rows 96..127, then the 64 token rows
 
 enum { MODE_GATE_UP = 0, MODE_DOWN = 1 };
 
 // ---- hand-issued memory operations --------------------------------------------
+// lds_base is wave-uniform by construction; readfirstlane makes that explicit so the
+// operand always lands in a scalar register
 __device__ __forceinline__ void dma16(const void *g, uint32_t lds_base) {
+  const uint32_t b = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_base);
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-               :: "v"(g), "s"(lds_base) : "memory");
+               :: "v"(g), "s"(b) : "memory");
 }
 __device__ __forceinline__ void dma16_stream(const void *g, uint32_t lds_base) {
+  const uint32_t b = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_base);
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off nt"
-               :: "v"(g), "s"(lds_base) : "memory");
+               :: "v"(g), "s"(b) : "memory");
 }
 template <int N>
 __device__ __forceinline__ void wait_vm() {
@@ -69,42 +79,22 @@ __device__ __forceinline__ void wg_barrier() {
 }
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
-// The lookup tables are separate __restrict__ kernel parameters so that the
-// compiler can prove them unclobbered and read them through the scalar unit: a
-// vector load here would make it wait for the whole prefetch queue.
+// Read one int32 of a lookup table through the scalar unit (read-only use of the
+// scalar cache; the tables were written by an earlier kernel).  Spelled out by
+// hand because a compiler-chosen vector load would count in vmcnt and make the
+// compiler wait for the whole prefetch queue; the result is wave-uniform.
+__device__ __forceinline__ int sload(const int32_t *p, int idx) {
+  int v;
+  const int off = uni(idx) * 4;
+  asm volatile("s_load_dword %0, %1, %2\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(p), "s"(off) : "memory");
+  return v;
+}
+
 struct Tables {
   const int32_t *__restrict__ plan;
   const int32_t *__restrict__ offsets;
   const int32_t *__restrict__ row_token;
 };
-
-// ---- the tile line ----------------------------------------------------------------
-// segment 0: shared expert, segment 1: big routed entries, segment 2: small routed
-struct Line {
-  int n[3];      // tiles per segment
-  int cost[3];   // cost per tile, in quarter slot-times
-  int tiles_r;   // row tiles per routed expert
-  int tiles_s;   // row tiles of the shared expert
-  int parts;     // k-parts of the shared down projection (1 for gate/up)
-  bool shared_big;
-};
-
-__device__ __forceinline__ long line_cost(const Line &L) {
-  return (long)L.n[0] * L.cost[0] + (long)L.n[1] * L.cost[1] + (long)L.n[2] * L.cost[2];
-}
-
-// first tile whose start cost is >= x
-__device__ __forceinline__ int tile_at(const Line &L, long x) {
-  int base = 0;
-#pragma unroll
-  for (int s = 0; s < 3; ++s) {
-    const long span = (long)L.n[s] * L.cost[s];
-    if (x <= span) return base + (L.cost[s] ? (int)((x + L.cost[s] - 1) / L.cost[s]) : 0);
-    x -= span;
-    base += L.n[s];
-  }
-  return base;
-}
 
 // One (group, token block): everything that is constant over its row tiles.
 struct Entry {
@@ -115,29 +105,17 @@ struct Entry {
   long b_stride;
   bool use_map;             // token rows go through row_token
   int row0, m;              // first token row, number of token rows (1..64)
-  int klen, nkb;
-  bool big;
+  int klen, nkb;            // contraction length, blocks (of KB or KBW)
   void *out;
   int out_n;
   int tiles;                // row tiles in this entry
-  int first_tile;           // line index of its row tile 0
+  int first;                // id (in its class) of this entry's row tile 0
 };
 
 template <int MODE>
-__device__ __forceinline__ Entry load_entry(const StreamArgs &a, const Tables &tb_, const Line &L, int tile) {
-  Entry en;
-  if (tile < L.n[0]) {  // shared expert
-    const int per = L.tiles_s;
-    const int blk = tile / per;           // gate/up: token block; down: (token block, part)
-    const int part = (MODE == MODE_DOWN) ? blk % L.parts : 0;
-    const int tbk = (MODE == MODE_DOWN) ? blk / L.parts : blk;
-    const int rows = L.shared_big ? BIG_TB : SMALL_M;
-    en.big = L.shared_big;
+__device__ __forceinline__ void fill_group(Entry &en, const StreamArgs &a, bool shared, int e, int part) {
+  if (shared) {
     en.use_map = false;
-    en.row0 = tbk * rows;
-    en.m = min(a.T - en.row0, rows);
-    en.tiles = per;
-    en.first_tile = blk * per;
     if (MODE == MODE_GATE_UP) {
       en.a0 = a.ws_gate;
       en.a1 = a.ws_up;
@@ -151,7 +129,7 @@ __device__ __forceinline__ Entry load_entry(const StreamArgs &a, const Tables &t
     } else {
       const int k0 = part * a.part_k;
       en.a0 = a.ws_down + k0;
-      en.a1 = en.a0 + (size_t)16 * a.S;
+      en.a1 = en.a0;
       en.a_stride = a.S;
       en.n_rows = a.d;
       en.b = a.hs + k0;
@@ -161,25 +139,6 @@ __device__ __forceinline__ Entry load_entry(const StreamArgs &a, const Tables &t
       en.out_n = a.d;
     }
   } else {
-    int j = tile - L.n[0];
-    int e, tbk = 0;
-    en.big = j < L.n[1];
-    if (en.big) {
-      const int entry = j / L.tiles_r;
-      e = tb_.plan[PLAN_HDR + a.E + 2 * entry];
-      tbk = tb_.plan[PLAN_HDR + a.E + 2 * entry + 1];
-      en.first_tile = L.n[0] + entry * L.tiles_r;
-    } else {
-      j -= L.n[1];
-      const int entry = j / L.tiles_r;
-      e = tb_.plan[PLAN_HDR + entry];
-      en.first_tile = L.n[0] + L.n[1] + entry * L.tiles_r;
-    }
-    const int beg = tb_.offsets[e], end = tb_.offsets[e + 1];
-    const int rows = en.big ? BIG_TB : SMALL_M;
-    en.row0 = beg + tbk * rows;
-    en.m = min(end - en.row0, rows);
-    en.tiles = L.tiles_r;
     if (MODE == MODE_GATE_UP) {
       en.a0 = a.w_gate + (size_t)e * a.I * a.d;
       en.a1 = a.w_up + (size_t)e * a.I * a.d;
@@ -193,7 +152,7 @@ __device__ __forceinline__ Entry load_entry(const StreamArgs &a, const Tables &t
       en.out_n = a.I;
     } else {
       en.a0 = a.w_down + (size_t)e * a.d * a.I;
-      en.a1 = en.a0 + (size_t)16 * a.I;
+      en.a1 = en.a0;
       en.a_stride = a.I;
       en.n_rows = a.d;
       en.b = a.h;
@@ -204,73 +163,162 @@ __device__ __forceinline__ Entry load_entry(const StreamArgs &a, const Tables &t
       en.out_n = a.d;
     }
   }
-  en.nkb = (en.klen + KB - 1) / KB;
+}
+
+// The tiles of one class (wide or small) that a workgroup processes: ids
+// id0, id0 + stride, ...  The class's tile ids run over [shared expert's tiles]
+// [routed entries x row tiles].
+struct ClassCfg {
+  int n_mine, id0, stride;
+  int n_sh;    // shared-expert tiles at the head of the class
+  int per_s;   // row tiles per shared entry
+  int per_r;   // row tiles per routed entry
+  int parts;   // k-parts of the shared down projection (1 for gate/up)
+};
+
+// entry that owns tile `id` of the class
+template <int MODE, bool WIDE>
+__device__ __forceinline__ Entry load_entry(const StreamArgs &a, const Tables &tb_, const ClassCfg &c,
+                                            int id) {
+  Entry en;
+  constexpr int rows = WIDE ? BIG_TB : SMALL_M;
+  if (id < c.n_sh) {
+    const int per = c.per_s;
+    const int blk = id / per;  // gate/up: token block; down: (token block, part)
+    const int part = (MODE == MODE_DOWN) ? blk % c.parts : 0;
+    const int tbk = (MODE == MODE_DOWN) ? blk / c.parts : blk;
+    en.row0 = tbk * rows;
+    en.m = min(a.T - en.row0, rows);
+    en.tiles = per;
+    en.first = blk * per;
+    fill_group<MODE>(en, a, true, 0, part);
+  } else {
+    const int per = c.per_r;
+    const int entry = (id - c.n_sh) / per;
+    int e, tbk = 0;
+    if (WIDE) {
+      e = sload(tb_.plan, PLAN_HDR + a.E + 2 * entry);
+      tbk = sload(tb_.plan, PLAN_HDR + a.E + 2 * entry + 1);
+    } else {
+      e = sload(tb_.plan, PLAN_HDR + entry);
+    }
+    const int beg = sload(tb_.offsets, e), end = sload(tb_.offsets, e + 1);
+    en.row0 = beg + tbk * rows;
+    en.m = min(end - en.row0, rows);
+    en.tiles = per;
+    en.first = c.n_sh + entry * per;
+    fill_group<MODE>(en, a, false, e, 0);
+  }
+  en.nkb = WIDE ? (en.klen + KBW - 1) / KBW : (en.klen + KB - 1) / KB;
   return en;
 }
 
-// rows per tile in the weight matrix: gate/up 16 (of each matrix), down 32
-template <int MODE>
-__device__ __forceinline__ int tile_i0(int rt) { return MODE == MODE_GATE_UP ? rt * 16 : rt * 32; }
+// first weight row of row tile rt
+template <int MODE, bool WIDE>
+__device__ __forceinline__ int tile_i0(int rt) {
+  if (MODE == MODE_GATE_UP) return WIDE ? rt * 64 : rt * 16;
+  return WIDE ? rt * 128 : rt * 32;
+}
 
 // Per-lane source pointers of the DMA instructions this wave issues.
+//   small: a[0..3] weights, b[0..1] tokens
+//   wide:  a[0..5] first slot, a[6..7] second slot, b[0..3] tokens
+template <bool WIDE>
 struct LoadPtrs {
-  const uint16_t *a[4];  // weight rows of the current tile
-  const uint16_t *b[8];  // token rows: [0,1] first slot, [2..7] second slot of a big block
+  const uint16_t *a[WIDE ? 8 : 4];
+  const uint16_t *b[WIDE ? 4 : 2];
 };
 
-template <int MODE>
-__device__ __forceinline__ void setup_b(LoadPtrs &lp, const Entry &en,
+template <int MODE, bool WIDE>
+__device__ __forceinline__ void setup_b(LoadPtrs<WIDE> &lp, const Entry &en,
                                         const int32_t *__restrict__ row_token, int wave, int lane) {
-  const int half = lane >> 5, slot = lane & 31;
+  if (!WIDE) {
+    const int half = lane >> 5, pos = lane & 31;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    if (i >= 2 && !en.big) break;
-    // instruction -> token row pair: first slot pairs 2w, 2w+1 (rows 0..15);
-    // second slot pairs 8 + 6w + (i-2) (rows 16..63)
-    const int pair = (i < 2) ? wave * 2 + i : 8 + wave * 6 + (i - 2);
-    const int ra = min(2 * pair, en.m - 1), rb = min(2 * pair + 1, en.m - 1);
-    int ta = en.row0 + ra, tb = en.row0 + rb;
-    if (en.use_map) {
-      ta = row_token[ta];
-      tb = row_token[tb];
+    for (int i = 0; i < 2; ++i) {
+      const int pair = wave * 2 + i;  // token rows 2*pair, 2*pair+1
+      int ta = en.row0 + min(2 * pair, en.m - 1), tb = en.row0 + min(2 * pair + 1, en.m - 1);
+      if (en.use_map) {
+        ta = sload(row_token, ta);
+        tb = sload(row_token, tb);
+      }
+      const int tok = half ? tb : ta;
+      const int r = 2 * pair + half;
+      lp.b[i] = en.b + (size_t)tok * en.b_stride + ((pos ^ (r & 7)) << 3);
     }
-    const int tok = half ? tb : ta;
-    const int r = 2 * pair + half;
-    lp.b[i] = en.b + (size_t)tok * en.b_stride + ((slot ^ (r & 7)) << 3);
-  }
-}
-
-template <int MODE>
-__device__ __forceinline__ void setup_a(LoadPtrs &lp, const Entry &en, int rt, int wave, int lane) {
-  const int half = lane >> 5, slot = lane & 31;
-  const int i0 = tile_i0<MODE>(rt);
-  // valid rows in each 16-row half of this tile (at least 1 after clamping)
-  const int rv0 = min(16, en.n_rows - i0);
-  const int rv1 = (MODE == MODE_GATE_UP) ? rv0 : max(1, min(16, en.n_rows - i0 - 16));
-  const bool second_ok = (MODE == MODE_GATE_UP) || (en.n_rows - i0 > 16);
+  } else {
+    const int sub = lane >> 4, pos = lane & 15;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int j = wave * 4 + i;  // 0..15: half = j >> 3, row pair = j & 7
-    const int r = 2 * (j & 7) + half;
-    const uint16_t *base = ((j >> 3) && second_ok) ? en.a1 : en.a0;
-    const int rv = (j >> 3) ? rv1 : rv0;
-    lp.a[i] = base + (size_t)(i0 + min(r, rv - 1)) * en.a_stride + ((slot ^ (r & 7)) << 3);
+    for (int i = 0; i < 4; ++i) {
+      const int jb = wave * 4 + i;  // token rows 4*jb .. 4*jb+3
+      int t0 = en.row0 + min(4 * jb, en.m - 1), t1 = en.row0 + min(4 * jb + 1, en.m - 1);
+      int t2 = en.row0 + min(4 * jb + 2, en.m - 1), t3 = en.row0 + min(4 * jb + 3, en.m - 1);
+      if (en.use_map) {
+        t0 = sload(row_token, t0);
+        t1 = sload(row_token, t1);
+        t2 = sload(row_token, t2);
+        t3 = sload(row_token, t3);
+      }
+      const int tok = sub == 0 ? t0 : (sub == 1 ? t1 : (sub == 2 ? t2 : t3));
+      const int r = 4 * jb + sub;
+      lp.b[i] = en.b + (size_t)tok * en.b_stride + ((pos ^ (r & 7)) << 3);
+    }
   }
 }
 
-// Issue one slot: exactly LW loads per wave.  second = second slot of a big block.
-__device__ __forceinline__ void issue_slot(const LoadPtrs &lp, int klen, int kb, bool second,
+template <int MODE, bool WIDE>
+__device__ __forceinline__ void setup_a(LoadPtrs<WIDE> &lp, const Entry &en, int rt, int wave, int lane) {
+  const int i0 = tile_i0<MODE, WIDE>(rt);
+  if (!WIDE) {
+    const int half = lane >> 5, pos = lane & 31;
+    // valid rows in each 16-row half of this tile (at least 1 after clamping)
+    const int rv0 = min(16, en.n_rows - i0);
+    const int rv1 = (MODE == MODE_GATE_UP) ? rv0 : max(1, min(16, en.n_rows - i0 - 16));
+    const int off1 = (MODE == MODE_GATE_UP) ? 0 : ((en.n_rows - i0 > 16) ? 16 : 0);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int j = wave * 4 + i;  // 0..15: half = j >> 3, row pair = j & 7
+      const int r = 2 * (j & 7) + half;
+      const uint16_t *base = (j >> 3) ? en.a1 : en.a0;
+      const int row = (j >> 3) ? i0 + off1 + min(r, rv1 - 1) : i0 + min(r, rv0 - 1);
+      lp.a[i] = base + (size_t)row * en.a_stride + ((pos ^ (r & 7)) << 3);
+    }
+  } else {
+    const int sub = lane >> 4, pos = lane & 15;
+    const int span = (MODE == MODE_GATE_UP) ? 64 : 128;
+    const int rv = min(span, en.n_rows - i0);  // valid rows of each matrix in this tile
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int j = (i < 6) ? wave * 6 + i : 24 + wave * 2 + (i - 6);  // rows 4j .. 4j+3 of 128
+      const int r = 4 * j + sub;
+      const uint16_t *base;
+      int row;
+      if (MODE == MODE_GATE_UP) {
+        base = (r >> 6) ? en.a1 : en.a0;
+        row = i0 + min(r & 63, rv - 1);
+      } else {
+        base = en.a0;
+        row = i0 + min(r, rv - 1);
+      }
+      lp.a[i] = base + (size_t)row * en.a_stride + ((pos ^ (r & 7)) << 3);
+    }
+  }
+}
+
+// Issue one slot: exactly LW loads per wave.  Pieces past the end of a row are
+// pulled back inside it; their products are masked in the MFMA loop.
+template <bool WIDE>
+__device__ __forceinline__ void issue_slot(const LoadPtrs<WIDE> &lp, int klen, int kb, bool second,
                                            uint32_t slot_base, int wave, int lane) {
-  const int k0 = kb * KB;
-  const bool full = k0 + KB <= klen;
-  // pieces past the end of a row are pulled back inside it; their products are masked
-  const int sl = lane & 31, half = lane >> 5;
-  auto koff = [&](int r) -> int {
-    if (full) return k0;
-    const int piece = sl ^ (r & 7);
-    return min(k0 + piece * 8, klen - 8) - piece * 8;
-  };
-  if (!second) {
+  if (!WIDE) {
+    const int k0 = kb * KB;
+    const bool full = k0 + KB <= klen;
+    const int pos = lane & 31, half = lane >> 5;
+    auto koff = [&](int r) __attribute__((always_inline)) -> int {
+      if (full) return k0;
+      const int piece = pos ^ (r & 7);
+      return min(k0 + piece * 8, klen - 8) - piece * 8;
+    };
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int j = wave * 4 + i;
@@ -282,109 +330,110 @@ __device__ __forceinline__ void issue_slot(const LoadPtrs &lp, int klen, int kb,
       dma16(lp.b[i] + koff(2 * pair + half), slot_base + A_BYTES + (uint32_t)pair * 1024u);
     }
   } else {
+    const int k0 = kb * KBW;
+    const bool full = k0 + KBW <= klen;
+    const int pos = lane & 15, sub = lane >> 4;
+    auto koff = [&](int r) __attribute__((always_inline)) -> int {
+      if (full) return k0;
+      const int piece = pos ^ (r & 7);
+      return min(k0 + piece * 8, klen - 8) - piece * 8;
+    };
+    if (!second) {
 #pragma unroll
-    for (int i = 0; i < 6; ++i) {
-      const int q2 = wave * 6 + i;  // token rows 16 + 2*q2, +1
-      dma16(lp.b[2 + i] + koff(2 * (8 + q2) + half), slot_base + (uint32_t)q2 * 1024u);
+      for (int i = 0; i < 6; ++i) {
+        const int j = wave * 6 + i;  // weight rows 4j..4j+3 (0..95)
+        dma16_stream(lp.a[i] + koff(4 * j + sub), slot_base + (uint32_t)j * 1024u);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int j = 24 + wave * 2 + i;  // weight rows 96..127
+        dma16_stream(lp.a[6 + i] + koff(4 * j + sub), slot_base + (uint32_t)(j - 24) * 1024u);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int jb = wave * 4 + i;  // token rows 4jb..4jb+3
+        dma16(lp.b[i] + koff(4 * jb + sub), slot_base + WIDE_B_OFF + (uint32_t)jb * 1024u);
+      }
     }
   }
 }
 
 template <int MODE>
-__global__ __launch_bounds__(256) void expert_stream_kernel(StreamArgs a,
-                                                            const int32_t *__restrict__ plan,
-                                                            const int32_t *__restrict__ offsets,
-                                                            const int32_t *__restrict__ row_token) {
-  extern __shared__ __attribute__((aligned(1024))) char smem[];
-  const Tables tb_{plan, offsets, row_token};
+__device__ __forceinline__ void store_out(void *out, int out_n, size_t orow, int i, int second_off,
+                                          float s0, float s1) {
+  // s0/s1: the two operand halves' results for one (token row, feature); second_off is
+  // the feature distance between the halves in the down projection
+  if (MODE == MODE_GATE_UP) {
+    if (i < out_n)
+      reinterpret_cast<uint16_t *>(out)[orow * out_n + i] = (uint16_t)f32_to_bf16_bits(silu_f32(s0) * s1);
+  } else {
+    float *y = reinterpret_cast<float *>(out);
+    if (i < out_n) y[orow * out_n + i] = s0;
+    if (i + second_off < out_n) y[orow * out_n + i + second_off] = s1;
+  }
+}
+
+// All tiles of one class for this workgroup: the software pipeline.
+template <int MODE, bool WIDE>
+__device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_, const ClassCfg &c,
+                                          char *smem) {
+  if (c.n_mine <= 0) return;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = uni(tid >> 6);
   const int r16 = lane & 15, q = lane >> 4;
   const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
   float *red = reinterpret_cast<float *>(smem + RING * SLOT_BYTES);
-
-  // ---- the line and this workgroup's share of it --------------------------------
-  Line L;
-  {
-    const int n_small = plan[0], n_big = plan[1];
-    const bool has_shared = a.S > 0;
-    L.shared_big = a.T > SMALL_M;
-    L.parts = (MODE == MODE_DOWN && has_shared) ? (a.S + a.part_k - 1) / a.part_k : 1;
-    L.tiles_r = (MODE == MODE_GATE_UP) ? (a.I + 15) / 16 : (a.d + 31) / 32;
-    L.tiles_s = (MODE == MODE_GATE_UP) ? (a.S + 15) / 16 : (a.d + 31) / 32;
-    const int n_tb = L.shared_big ? (a.T + BIG_TB - 1) / BIG_TB : 1;
-    const int nkb_r = ((MODE == MODE_GATE_UP ? a.d : a.I) + KB - 1) / KB;
-    const int nkb_s = ((MODE == MODE_GATE_UP ? a.d : min(a.part_k, a.S)) + KB - 1) / KB;
-    L.n[0] = has_shared ? L.tiles_s * L.parts * n_tb : 0;
-    L.n[1] = n_big * L.tiles_r;
-    L.n[2] = n_small * L.tiles_r;
-    // measured: a big block (two slots, four times the token bytes) takes about
-    // 2.25 small-block times in gate/up and 2.75 in down
-    const int big_q = (MODE == MODE_GATE_UP) ? 9 : 11;
-    L.cost[0] = (L.shared_big ? big_q : 4) * nkb_s;
-    L.cost[1] = big_q * nkb_r;
-    L.cost[2] = 4 * nkb_r;
-  }
-  const long C = line_cost(L);
-  const int G = gridDim.x, b = blockIdx.x;
-  const int t_begin = tile_at(L, C * b / G);
-  const int t_end = tile_at(L, C * (b + 1) / G);
-  if (t_begin >= t_end) return;
+  constexpr int NACC = WIDE ? 4 : 1;
 
   // ---- load cursor -------------------------------------------------------------------
-  int l_tile = t_begin, l_kb = 0, l_slot = 0;
+  int l_i = 0, l_kb = 0, l_slot = 0;
   bool l_second = false;
-  Entry len = load_entry<MODE>(a, tb_, L, l_tile);
-  LoadPtrs lp;
-  setup_b<MODE>(lp, len, tb_.row_token, wave, lane);
-  setup_a<MODE>(lp, len, l_tile - len.first_tile, wave, lane);
+  Entry len = load_entry<MODE, WIDE>(a, tb_, c, c.id0);
+  LoadPtrs<WIDE> lp;
+  setup_b<MODE, WIDE>(lp, len, tb_.row_token, wave, lane);
+  setup_a<MODE, WIDE>(lp, len, c.id0 - len.first, wave, lane);
   bool l_live = true;
 
-  auto advance_load = [&]() {
-    issue_slot(lp, len.klen, l_kb, l_second, lds0 + (uint32_t)(l_slot % RING) * SLOT_BYTES, wave, lane);
+  auto advance_load = [&]() __attribute__((always_inline)) {
+    issue_slot<WIDE>(lp, len.klen, l_kb, l_second, lds0 + (uint32_t)(l_slot % RING) * SLOT_BYTES, wave, lane);
     ++l_slot;
-    if (len.big && !l_second) {
+    if (WIDE && !l_second) {
       l_second = true;
       return;
     }
     l_second = false;
     if (++l_kb == len.nkb) {
       l_kb = 0;
-      if (++l_tile == t_end) {
+      if (++l_i == c.n_mine) {
         l_live = false;
         return;
       }
-      if (l_tile - len.first_tile == len.tiles) {
-        len = load_entry<MODE>(a, tb_, L, l_tile);
-        setup_b<MODE>(lp, len, tb_.row_token, wave, lane);
+      const int id = c.id0 + l_i * c.stride;
+      if (id - len.first >= len.tiles || id < len.first) {
+        len = load_entry<MODE, WIDE>(a, tb_, c, id);
+        setup_b<MODE, WIDE>(lp, len, tb_.row_token, wave, lane);
       }
-      setup_a<MODE>(lp, len, l_tile - len.first_tile, wave, lane);
+      setup_a<MODE, WIDE>(lp, len, id - len.first, wave, lane);
     }
   };
 
   // ---- compute cursor -----------------------------------------------------------------
-  int c_tile = t_begin, c_kb = 0, c_slot = 0;
+  int c_i = 0, c_kb = 0, c_slot = 0;
   bool c_second = false;
-  Entry cen = load_entry<MODE>(a, tb_, L, c_tile);
-  f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+  Entry cen = load_entry<MODE, WIDE>(a, tb_, c, c.id0);
+  f32x4 acc0[NACC], acc1[NACC];
+#pragma unroll
+  for (int nt = 0; nt < NACC; ++nt) {
+    acc0[nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    acc1[nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  }
   // a finished small tile whose partial sums wait in `red` for the next barrier
   bool pend = false;
   int pend_m = 0, pend_row0 = 0, pend_i0 = 0, pend_n = 0;
   void *pend_out = nullptr;
 
-  auto store_out = [&](void *out, int out_n, size_t orow, int i0, int fi, float s0, float s1) {
-    if (MODE == MODE_GATE_UP) {
-      const int i = i0 + fi;
-      if (i < out_n)
-        reinterpret_cast<uint16_t *>(out)[orow * out_n + i] = (uint16_t)f32_to_bf16_bits(silu_f32(s0) * s1);
-    } else {
-      float *y = reinterpret_cast<float *>(out);
-      const int i = i0 + fi;
-      if (i < out_n) y[orow * out_n + i] = s0;
-      if (i + 16 < out_n) y[orow * out_n + i + 16] = s1;
-    }
-  };
-  auto flush_pending = [&]() {  // after a barrier: add the four waves' partial tiles
+  auto flush_pending = [&]() __attribute__((always_inline)) {  // after a barrier: add the waves' partial tiles
     const int l2 = tid & 63, rr = tid >> 6;
     const int j = l2 & 15, fi = 4 * (l2 >> 4) + rr;
     float s0 = 0.f, s1 = 0.f;
@@ -393,7 +442,7 @@ __global__ __launch_bounds__(256) void expert_stream_kernel(StreamArgs a,
       s0 += red[(w * 2 + 0) * 256 + tid];
       s1 += red[(w * 2 + 1) * 256 + tid];
     }
-    if (j < pend_m) store_out(pend_out, pend_n, (size_t)(pend_row0 + j), pend_i0, fi, s0, s1);
+    if (j < pend_m) store_out<MODE>(pend_out, pend_n, (size_t)(pend_row0 + j), pend_i0 + fi, 16, s0, s1);
     pend = false;
   };
 
@@ -405,12 +454,12 @@ __global__ __launch_bounds__(256) void expert_stream_kernel(StreamArgs a,
     else wait_vm<0>();
     wg_barrier();
     if (l_live) advance_load();
-    if (pend) flush_pending();
+    if (!WIDE && pend) flush_pending();
 
     const char *sb = smem + (size_t)(c_slot % RING) * SLOT_BYTES;
-    const int kbase = c_kb * KB;
     bool tile_done = false;
-    if (!cen.big) {
+    if (!WIDE) {
+      const int kbase = c_kb * KB;
       // waves split the 8 steps
       if (kbase + KB <= cen.klen) {  // whole block: no masks, reads issued back to back
         u32x4 fa0[2], fa1[2], fb[2];
@@ -424,8 +473,8 @@ __global__ __launch_bounds__(256) void expert_stream_kernel(StreamArgs a,
         }
 #pragma unroll
         for (int ss = 0; ss < 2; ++ss) {
-          acc0 = mfma16(fa0[ss], fb[ss], acc0);
-          acc1 = mfma16(fa1[ss], fb[ss], acc1);
+          acc0[0] = mfma16(fa0[ss], fb[ss], acc0[0]);
+          acc1[0] = mfma16(fa1[ss], fb[ss], acc1[0]);
         }
       } else {
 #pragma unroll
@@ -438,49 +487,64 @@ __global__ __launch_bounds__(256) void expert_stream_kernel(StreamArgs a,
             const u32x4 fa1 = *reinterpret_cast<const u32x4 *>(sb + 8192 + off);
             u32x4 fb = *reinterpret_cast<const u32x4 *>(sb + A_BYTES + off);
             if (kbase + piece * 8 >= cen.klen) fb = (u32x4){0u, 0u, 0u, 0u};  // ragged last step
-            acc0 = mfma16(fa0, fb, acc0);
-            acc1 = mfma16(fa1, fb, acc1);
+            acc0[0] = mfma16(fa0, fb, acc0[0]);
+            acc1[0] = mfma16(fa1, fb, acc1[0]);
           }
         }
       }
       tile_done = (c_kb == cen.nkb - 1);
       ++c_kb;
     } else if (c_second) {
-      // wave w owns token rows 16w..16w+15; weights sit in the previous slot
+      // wave w: weight rows 16w..16w+15 of each half; weights 0..95 sit in the previous slot
+      const int kbase = c_kb * KBW;
       const char *sa = smem + (size_t)((c_slot + RING - 1) % RING) * SLOT_BYTES;
-      const char *sbt = (wave == 0) ? sa + A_BYTES : sb + (size_t)(wave - 1) * 16 * ROW_BYTES;
-      if (wave * 16 < cen.m) {
-        if (kbase + KB <= cen.klen) {  // whole block: two groups of four steps, reads ahead of the MFMAs
+      const char *pa0 = sa + (size_t)(16 * wave) * ROWW_BYTES;
+      const char *pa1 = (wave < 2) ? sa + (size_t)(64 + 16 * wave) * ROWW_BYTES
+                                   : sb + (size_t)(16 * wave - 32) * ROWW_BYTES;
+      const char *pb = sb + WIDE_B_OFF;
+      const int ntc = (cen.m + 15) >> 4;
+      if (kbase + KBW <= cen.klen) {
+        // whole block: all reads are unconditional and issued ahead of the MFMAs; token
+        // tiles beyond the block's rows multiply stale LDS rows into accumulators
+        // that are never stored
+        u32x4 fa0[4], fa1[4];
 #pragma unroll
-          for (int g4 = 0; g4 < 2; ++g4) {
-            u32x4 fa0[4], fa1[4], fb[4];
+        for (int s = 0; s < 4; ++s) {
+          const int off = r16 * ROWW_BYTES + (((4 * s + q) ^ (r16 & 7)) << 4);
+          fa0[s] = *reinterpret_cast<const u32x4 *>(pa0 + off);
+          fa1[s] = *reinterpret_cast<const u32x4 *>(pa1 + off);
+        }
 #pragma unroll
-            for (int s4 = 0; s4 < 4; ++s4) {
-              const int piece = 4 * (g4 * 4 + s4) + q;
-              const int off = r16 * ROW_BYTES + ((piece ^ (r16 & 7)) << 4);
-              fa0[s4] = *reinterpret_cast<const u32x4 *>(sa + off);
-              fa1[s4] = *reinterpret_cast<const u32x4 *>(sa + 8192 + off);
-              fb[s4] = *reinterpret_cast<const u32x4 *>(sbt + off);
-            }
+        for (int nt = 0; nt < NACC; ++nt) {
+          u32x4 fb[4];
 #pragma unroll
-            for (int s4 = 0; s4 < 4; ++s4) {
-              acc0 = mfma16(fa0[s4], fb[s4], acc0);
-              acc1 = mfma16(fa1[s4], fb[s4], acc1);
-            }
+          for (int s = 0; s < 4; ++s) {
+            const int off = r16 * ROWW_BYTES + (((4 * s + q) ^ (r16 & 7)) << 4);
+            fb[s] = *reinterpret_cast<const u32x4 *>(pb + nt * 16 * ROWW_BYTES + off);
           }
-        } else {
 #pragma unroll
-          for (int s = 0; s < 8; ++s) {
-            if (kbase + s * 32 < cen.klen) {
-              const int piece = 4 * s + q;
-              const int off = r16 * ROW_BYTES + ((piece ^ (r16 & 7)) << 4);
-              const u32x4 fa0 = *reinterpret_cast<const u32x4 *>(sa + off);
-              const u32x4 fa1 = *reinterpret_cast<const u32x4 *>(sa + 8192 + off);
-              u32x4 fb = *reinterpret_cast<const u32x4 *>(sbt + off);
-              if (kbase + piece * 8 >= cen.klen) fb = (u32x4){0u, 0u, 0u, 0u};
-              acc0 = mfma16(fa0, fb, acc0);
-              acc1 = mfma16(fa1, fb, acc1);
-            }
+          for (int s = 0; s < 4; ++s) {
+            acc0[nt] = mfma16(fa0[s], fb[s], acc0[nt]);
+            acc1[nt] = mfma16(fa1[s], fb[s], acc1[nt]);
+          }
+        }
+      } else {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          if (kbase + s * 32 < cen.klen) {
+            const int piece = 4 * s + q;
+            const int off = r16 * ROWW_BYTES + ((piece ^ (r16 & 7)) << 4);
+            const u32x4 fa0 = *reinterpret_cast<const u32x4 *>(pa0 + off);
+            const u32x4 fa1 = *reinterpret_cast<const u32x4 *>(pa1 + off);
+            const bool dead = kbase + piece * 8 >= cen.klen;
+#pragma unroll
+            for (int nt = 0; nt < NACC; ++nt)
+              if (nt < ntc) {
+                u32x4 fb = *reinterpret_cast<const u32x4 *>(pb + nt * 16 * ROWW_BYTES + off);
+                if (dead) fb = (u32x4){0u, 0u, 0u, 0u};
+                acc0[nt] = mfma16(fa0, fb, acc0[nt]);
+                acc1[nt] = mfma16(fa1, fb, acc1[nt]);
+              }
           }
         }
       }
@@ -488,27 +552,38 @@ __global__ __launch_bounds__(256) void expert_stream_kernel(StreamArgs a,
       ++c_kb;
       c_second = false;
     } else {
-      c_second = true;  // first half of a big block: nothing to compute yet
+      c_second = true;  // first slot of a wide block: nothing to compute yet
     }
     ++c_slot;
 
     if (tile_done) {
-      const int rt = c_tile - cen.first_tile;
-      const int i0 = tile_i0<MODE>(rt);
-      if (cen.big) {
-        // straight from the accumulators: token row 16*wave + r16, features 4q..4q+3
-        const int j = wave * 16 + r16;
-        if (j < cen.m) {
+      const int id = c.id0 + c_i * c.stride;
+      const int i0 = tile_i0<MODE, WIDE>(id - cen.first);
+      if (WIDE) {
+        // straight from the accumulators: token row 16*nt + r16, features 16*wave + 4q + rr
+        const int ntc = (cen.m + 15) >> 4;
 #pragma unroll
-          for (int rr = 0; rr < 4; ++rr)
-            store_out(cen.out, cen.out_n, (size_t)(cen.row0 + j), i0, 4 * q + rr, acc0[rr], acc1[rr]);
+        for (int nt = 0; nt < NACC; ++nt)
+          if (nt < ntc) {
+            const int j = nt * 16 + r16;
+            if (j < cen.m) {
+#pragma unroll
+              for (int rr = 0; rr < 4; ++rr)
+                store_out<MODE>(cen.out, cen.out_n, (size_t)(cen.row0 + j), i0 + 16 * wave + 4 * q + rr, 64,
+                                acc0[nt][rr], acc1[nt][rr]);
+            }
+          }
+#pragma unroll
+        for (int nt = 0; nt < NACC; ++nt) {
+          acc0[nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+          acc1[nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
         }
       } else {
         if (cen.nkb == 1) wg_barrier();  // the previous tile's sums may still be read from `red`
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
-          red[(wave * 2 + 0) * 256 + rr * 64 + lane] = acc0[rr];
-          red[(wave * 2 + 1) * 256 + rr * 64 + lane] = acc1[rr];
+          red[(wave * 2 + 0) * 256 + rr * 64 + lane] = acc0[0][rr];
+          red[(wave * 2 + 1) * 256 + rr * 64 + lane] = acc1[0][rr];
         }
         pend = true;
         pend_m = cen.m;
@@ -516,18 +591,79 @@ __global__ __launch_bounds__(256) void expert_stream_kernel(StreamArgs a,
         pend_i0 = i0;
         pend_n = cen.out_n;
         pend_out = cen.out;
+        acc0[0] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        acc1[0] = (f32x4){0.f, 0.f, 0.f, 0.f};
       }
-      acc0 = (f32x4){0.f, 0.f, 0.f, 0.f};
-      acc1 = (f32x4){0.f, 0.f, 0.f, 0.f};
       c_kb = 0;
-      if (++c_tile == t_end) break;
-      if (c_tile - cen.first_tile == cen.tiles) cen = load_entry<MODE>(a, tb_, L, c_tile);
+      if (++c_i == c.n_mine) break;
+      const int nid = c.id0 + c_i * c.stride;
+      if (nid - cen.first >= cen.tiles || nid < cen.first) cen = load_entry<MODE, WIDE>(a, tb_, c, nid);
     }
   }
-  if (pend) {
+  if (!WIDE && pend) {
     wg_barrier();
     flush_pending();
   }
+  // nothing pending, every wave done reading the ring: the next class may reuse it
+  wait_vm<0>();
+  wg_barrier();
+}
+
+template <int MODE>
+__global__ __launch_bounds__(256) void expert_stream_kernel(StreamArgs a,
+                                                            const int32_t *__restrict__ plan,
+                                                            const int32_t *__restrict__ offsets,
+                                                            const int32_t *__restrict__ row_token) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const Tables tb_{plan, offsets, row_token};
+  const int G = gridDim.x, bid = blockIdx.x;
+
+  // ---- the schedule ---------------------------------------------------------------
+  // wide tiles: [shared expert's, if it has more than 16 rows][big routed entries]
+  // small tiles: [shared expert's, if it has at most 16 rows][small routed entries]
+  const int n_small_e = sload(plan, 0), n_big_e = sload(plan, 1);
+  const bool has_shared = a.S > 0;
+  const bool shared_wide = a.T > SMALL_M;
+  const int parts = (MODE == MODE_DOWN && has_shared) ? (a.S + a.part_k - 1) / a.part_k : 1;
+  ClassCfg cw, cs;
+  cw.parts = cs.parts = parts;
+  cs.per_r = (MODE == MODE_GATE_UP) ? (a.I + 15) / 16 : (a.d + 31) / 32;
+  cs.per_s = (MODE == MODE_GATE_UP) ? (a.S + 15) / 16 : (a.d + 31) / 32;
+  cw.per_r = (MODE == MODE_GATE_UP) ? (a.I + 63) / 64 : (a.d + 127) / 128;
+  cw.per_s = (MODE == MODE_GATE_UP) ? (a.S + 63) / 64 : (a.d + 127) / 128;
+  const int n_tb = (a.T + BIG_TB - 1) / BIG_TB;
+  cw.n_sh = (has_shared && shared_wide) ? cw.per_s * parts * n_tb : 0;
+  cs.n_sh = (has_shared && !shared_wide) ? cs.per_s * parts : 0;
+  const int n_wide = cw.n_sh + n_big_e * cw.per_r;
+  const int n_small = cs.n_sh + n_small_e * cs.per_r;
+  {
+    // cost in slots: a small tile is nkb slots, a wide tile 2*nkbw (same weight bytes per slot)
+    const int kr = (MODE == MODE_GATE_UP) ? a.d : a.I;
+    const long c_small = (kr + KB - 1) / KB;
+    const long c_wide = 2 * ((kr + KBW - 1) / KBW);
+    const long C = n_wide * c_wide + n_small * c_small;  // total
+    // wide tiles round-robin; the small line is cut in proportion to what is left of
+    // each workgroup's equal share (all quantities scaled by G)
+    const int k = n_wide / G, rem = n_wide % G;
+    cw.n_mine = k + (bid < rem ? 1 : 0);
+    cw.id0 = bid;
+    cw.stride = G;
+    const long r_hi = max(0L, C - (long)(k + 1) * c_wide * G);
+    const long r_lo = max(0L, C - (long)k * c_wide * G);
+    const long p0 = (long)min(bid, rem) * r_hi + (long)max(0, bid - rem) * r_lo;
+    const long p1 = (long)min(bid + 1, rem) * r_hi + (long)max(0, bid + 1 - rem) * r_lo;
+    const long p_tot = (long)rem * r_hi + (long)(G - rem) * r_lo;
+    int sb0 = 0, sb1 = 0;
+    if (p_tot > 0) {
+      sb0 = (int)((long)n_small * p0 / p_tot);
+      sb1 = (int)((long)n_small * p1 / p_tot);
+    }
+    cs.n_mine = sb1 - sb0;
+    cs.id0 = sb0;
+    cs.stride = 1;
+  }
+  run_class<MODE, true>(a, tb_, cw, smem);
+  run_class<MODE, false>(a, tb_, cs, smem);
 }
 
 static hipError_t launch_stream(int mode, const StreamArgs &a, hipStream_t s) {
