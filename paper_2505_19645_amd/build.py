@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmoesd.so")
-SOURCES = ["moesd_api.cpp", "closed_forms.cpp", "route.hip", "permute.hip", "expert_stream.hip",
+SOURCES = ["moesd_api.cpp", "closed_forms.cpp", "route.hip", "permute.hip", "expert_stream.hip", "expert_tiled.hip",
            "combine.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",

@@ -40,10 +40,14 @@ __device__ __forceinline__ float silu_f32(float z) { return z / (1.0f + expf(-z)
 // ---- launch descriptors (host fills, passed by value) ------------------------
 
 // Plan written by the permutation kernel for the expert kernels (int32 words):
-//   [0] n_small: experts with 1..16 rows      [1] n_big: (expert, 64-row block) entries
-//   [PLAN_HDR .. PLAN_HDR+E)  ids of the small experts, ascending
-//   then n_big pairs (expert id, block index), ascending by expert then block
-#define PLAN_HDR 2
+//   [0] n_small: experts with 1..16 rows
+//   [1] n_big:   experts with 17..64 rows
+//   [2] n_large: (expert, 256-row block) entries of the experts with more than 64 rows
+//   [PLAN_HDR .. +E)        ids of the small experts, ascending
+//   [PLAN_HDR+E .. +2E)     n_big pairs (expert id, 0), ascending
+//   [PLAN_HDR+3E .. )       n_large pairs (expert id, block index), ascending by expert, block
+#define PLAN_HDR 4
+#define PLAN_WORDS(E, TK) (PLAN_HDR + 3 * (E) + 2 * ((E) + (TK) / 256 + 2))
 
 struct StreamArgs {
   // routed experts
@@ -80,6 +84,8 @@ hipError_t launch_topk_permute(const double *logits, int T, int E, int K, int sc
                                int32_t *n_active, int32_t *row_token, int32_t *plan, hipStream_t s);
 hipError_t launch_gate_up(const StreamArgs &a, hipStream_t s);
 hipError_t launch_down(const StreamArgs &a, hipStream_t s);
+hipError_t launch_gate_up_tiled(const StreamArgs &a, hipStream_t s);
+hipError_t launch_down_tiled(const StreamArgs &a, hipStream_t s);
 hipError_t launch_combine(const float *y, const float *ys, int n_parts, const float *w,
                           const float *gate, const int32_t *inv, int T, int K, int d, uint16_t *out,
                           float *out_f32, hipStream_t s);

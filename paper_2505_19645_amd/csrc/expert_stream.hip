@@ -15,7 +15,7 @@
 //      wide:  17..64 rows.  128 weight rows (64 + 64, or 128 of w_down),
 //             contraction blocks of 128 elements; a block is two slots: 32 KB
 //             of weights + 16 KB of tokens.
-//    Experts with more than 64 rows are cut into 64-row blocks.
+//    Experts with more than 64 rows belong to the MFMA-tiled kernel.
 //  * Every slot is exactly six global_load_lds_dwordx4 per wave, each moving
 //    1 KB (two 512-byte or four 256-byte row pieces, contiguous in HBM) straight
 //    into LDS; the weights carry the non-temporal hint (each byte is read once).
@@ -25,8 +25,9 @@
 //  * Work split: wide tiles are dealt round-robin, then every workgroup gets a
 //    contiguous run of small tiles sized so that all finish together.
 //  * MFMA operands come from LDS.  The 16-byte pieces of a row are stored
-//    XOR-swizzled by (row & 7): operand reads are free of bank conflicts while
-//    the DMA writes stay linear.
+//    XOR-swizzled by (row & 15): the 16 rows that one quarter-wave reads then
+//    fall into 16 different 16-byte bank groups of the 64-bank LDS, while the DMA
+//    writes stay linear.
 //  * Small tiles: the four waves split the eight 32-element MFMA steps of a
 //    block and add their partial 16x16 tiles through LDS in a fixed order.
 //    Wide tiles: wave w owns weight rows 16w..16w+15 of each half against all
@@ -244,7 +245,7 @@ __device__ __forceinline__ void setup_b(LoadPtrs<WIDE> &lp, const Entry &en,
       }
       const int tok = half ? tb : ta;
       const int r = 2 * pair + half;
-      lp.b[i] = en.b + (size_t)tok * en.b_stride + ((pos ^ (r & 7)) << 3);
+      lp.b[i] = en.b + (size_t)tok * en.b_stride + ((pos ^ (r & 15)) << 3);
     }
   } else {
     const int sub = lane >> 4, pos = lane & 15;
@@ -261,7 +262,7 @@ __device__ __forceinline__ void setup_b(LoadPtrs<WIDE> &lp, const Entry &en,
       }
       const int tok = sub == 0 ? t0 : (sub == 1 ? t1 : (sub == 2 ? t2 : t3));
       const int r = 4 * jb + sub;
-      lp.b[i] = en.b + (size_t)tok * en.b_stride + ((pos ^ (r & 7)) << 3);
+      lp.b[i] = en.b + (size_t)tok * en.b_stride + ((pos ^ (r & 15)) << 3);
     }
   }
 }
@@ -281,7 +282,7 @@ __device__ __forceinline__ void setup_a(LoadPtrs<WIDE> &lp, const Entry &en, int
       const int r = 2 * (j & 7) + half;
       const uint16_t *base = (j >> 3) ? en.a1 : en.a0;
       const int row = (j >> 3) ? i0 + off1 + min(r, rv1 - 1) : i0 + min(r, rv0 - 1);
-      lp.a[i] = base + (size_t)row * en.a_stride + ((pos ^ (r & 7)) << 3);
+      lp.a[i] = base + (size_t)row * en.a_stride + ((pos ^ (r & 15)) << 3);
     }
   } else {
     const int sub = lane >> 4, pos = lane & 15;
@@ -300,7 +301,7 @@ __device__ __forceinline__ void setup_a(LoadPtrs<WIDE> &lp, const Entry &en, int
         base = en.a0;
         row = i0 + min(r, rv - 1);
       }
-      lp.a[i] = base + (size_t)row * en.a_stride + ((pos ^ (r & 7)) << 3);
+      lp.a[i] = base + (size_t)row * en.a_stride + ((pos ^ (r & 15)) << 3);
     }
   }
 }
@@ -316,7 +317,7 @@ __device__ __forceinline__ void issue_slot(const LoadPtrs<WIDE> &lp, int klen, i
     const int pos = lane & 31, half = lane >> 5;
     auto koff = [&](int r) __attribute__((always_inline)) -> int {
       if (full) return k0;
-      const int piece = pos ^ (r & 7);
+      const int piece = pos ^ (r & 15);
       return min(k0 + piece * 8, klen - 8) - piece * 8;
     };
 #pragma unroll
@@ -335,7 +336,7 @@ __device__ __forceinline__ void issue_slot(const LoadPtrs<WIDE> &lp, int klen, i
     const int pos = lane & 15, sub = lane >> 4;
     auto koff = [&](int r) __attribute__((always_inline)) -> int {
       if (full) return k0;
-      const int piece = pos ^ (r & 7);
+      const int piece = pos ^ (r & 15);
       return min(k0 + piece * 8, klen - 8) - piece * 8;
     };
     if (!second) {
@@ -466,7 +467,7 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
 #pragma unroll
         for (int ss = 0; ss < 2; ++ss) {
           const int piece = 4 * (wave * 2 + ss) + q;
-          const int off = r16 * ROW_BYTES + ((piece ^ (r16 & 7)) << 4);
+          const int off = r16 * ROW_BYTES + ((piece ^ r16) << 4);
           fa0[ss] = *reinterpret_cast<const u32x4 *>(sb + off);
           fa1[ss] = *reinterpret_cast<const u32x4 *>(sb + 8192 + off);
           fb[ss] = *reinterpret_cast<const u32x4 *>(sb + A_BYTES + off);
@@ -482,7 +483,7 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
           const int s = wave * 2 + ss;
           if (kbase + s * 32 < cen.klen) {
             const int piece = 4 * s + q;
-            const int off = r16 * ROW_BYTES + ((piece ^ (r16 & 7)) << 4);
+            const int off = r16 * ROW_BYTES + ((piece ^ r16) << 4);
             const u32x4 fa0 = *reinterpret_cast<const u32x4 *>(sb + off);
             const u32x4 fa1 = *reinterpret_cast<const u32x4 *>(sb + 8192 + off);
             u32x4 fb = *reinterpret_cast<const u32x4 *>(sb + A_BYTES + off);
@@ -510,7 +511,7 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
         u32x4 fa0[4], fa1[4];
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-          const int off = r16 * ROWW_BYTES + (((4 * s + q) ^ (r16 & 7)) << 4);
+          const int off = r16 * ROWW_BYTES + (((4 * s + q) ^ r16) << 4);
           fa0[s] = *reinterpret_cast<const u32x4 *>(pa0 + off);
           fa1[s] = *reinterpret_cast<const u32x4 *>(pa1 + off);
         }
@@ -519,7 +520,7 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
           u32x4 fb[4];
 #pragma unroll
           for (int s = 0; s < 4; ++s) {
-            const int off = r16 * ROWW_BYTES + (((4 * s + q) ^ (r16 & 7)) << 4);
+            const int off = r16 * ROWW_BYTES + (((4 * s + q) ^ r16) << 4);
             fb[s] = *reinterpret_cast<const u32x4 *>(pb + nt * 16 * ROWW_BYTES + off);
           }
 #pragma unroll
@@ -533,7 +534,7 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
         for (int s = 0; s < 4; ++s) {
           if (kbase + s * 32 < cen.klen) {
             const int piece = 4 * s + q;
-            const int off = r16 * ROWW_BYTES + ((piece ^ (r16 & 7)) << 4);
+            const int off = r16 * ROWW_BYTES + ((piece ^ r16) << 4);
             const u32x4 fa0 = *reinterpret_cast<const u32x4 *>(pa0 + off);
             const u32x4 fa1 = *reinterpret_cast<const u32x4 *>(pa1 + off);
             const bool dead = kbase + piece * 8 >= cen.klen;
@@ -623,7 +624,8 @@ __global__ __launch_bounds__(256) void expert_stream_kernel(StreamArgs a,
   // small tiles: [shared expert's, if it has at most 16 rows][small routed entries]
   const int n_small_e = sload(plan, 0), n_big_e = sload(plan, 1);
   const bool has_shared = a.S > 0;
-  const bool shared_wide = a.T > SMALL_M;
+  const bool shared_wide = a.T > SMALL_M && a.T <= BIG_TB;   // more rows: the tiled kernel takes it
+  const bool shared_small = a.T <= SMALL_M;
   const int parts = (MODE == MODE_DOWN && has_shared) ? (a.S + a.part_k - 1) / a.part_k : 1;
   ClassCfg cw, cs;
   cw.parts = cs.parts = parts;
@@ -633,7 +635,7 @@ __global__ __launch_bounds__(256) void expert_stream_kernel(StreamArgs a,
   cw.per_s = (MODE == MODE_GATE_UP) ? (a.S + 63) / 64 : (a.d + 127) / 128;
   const int n_tb = (a.T + BIG_TB - 1) / BIG_TB;
   cw.n_sh = (has_shared && shared_wide) ? cw.per_s * parts * n_tb : 0;
-  cs.n_sh = (has_shared && !shared_wide) ? cs.per_s * parts : 0;
+  cs.n_sh = (has_shared && shared_small) ? cs.per_s * parts : 0;
   const int n_wide = cw.n_sh + n_big_e * cw.per_r;
   const int n_small = cs.n_sh + n_small_e * cs.per_r;
   {

@@ -1,0 +1,288 @@
+// Expert FFN for many rows per expert: MFMA-tiled grouped GEMM through LDS.
+//
+// Once an expert's load T_exp passes the ridge point the layer turns from
+// loading weights to computing (the k3*G(T_exp) term of the paper's Sec. 3.3
+// model).  Experts (or the shared expert) with more than 64 token rows are cut
+// into blocks of 256 rows and handled here: a workgroup computes a 256-token x
+// 256-weight-row tile (128 w_gate rows + the same 128 w_up rows with SwiGLU
+// fused, or 256 w_down rows), marching over the contraction dimension in
+// 32-element steps through a four-stage LDS ring, with v_mfma_f32_32x32x16_bf16.
+//
+//  * Four waves as 2 (row halves) x 2 (token halves); a wave owns 2 x 2 32-row
+//    tiles (gate and up rows 64wr..64wr+63, or two 64-row groups of w_down) x
+//    four 32-token tiles = 16 accumulator tiles (256 accumulator registers):
+//    8 operand reads feed 16 MFMAs, 131 flops per byte brought into LDS.
+//  * Operands go straight from global memory into the LDS ring with
+//    global_load_lds_dwordx4 (no staging registers, three steps in flight while
+//    one is multiplied); loads are issued and awaited by hand, one s_barrier per
+//    step.  Rows are 64 bytes in LDS, their four 16-byte pieces XOR-swizzled by
+//    (row >> 2) & 3: four rows share a 256-byte bank line, and the 16 rows a
+//    quarter-wave reads then fall into 16 different 16-byte bank groups, while
+//    the DMA writes stay linear.
+//  * Workgroup ids are remapped so that the token blocks of one expert that share
+//    a weight tile, and the row tiles that share a token block, run on one XCD at
+//    the same time and meet in its L2.
+//
+// MFMA operand use (32x32x16): lane l = 32*q + r supplies 8 consecutive
+// contraction elements (piece 2*s + q of step s) of weight row r as A and of
+// token row r as B; it receives, for token r, output features
+// 8*g + 4*q + c (g, c = 0..3) in accumulator register 4*g + c.
+#include "common.h"
+
+#define TBM 256  // token rows per tile
+#define TBN 256  // weight rows per tile (two halves of 128)
+#define TBK 32   // contraction elements per step
+#define T_ROW_BYTES 64
+#define T_A_BYTES (TBN * T_ROW_BYTES)  // 16 KB
+#define T_B_BYTES (TBM * T_ROW_BYTES)  // 16 KB
+#define T_STAGE_BYTES (T_A_BYTES + T_B_BYTES)
+#define T_STAGES 4
+#define T_LW 8  // loads per wave per stage
+#define TILED_LDS_BYTES (T_STAGES * T_STAGE_BYTES)
+
+enum { TMODE_GATE_UP = 0, TMODE_DOWN = 1 };
+
+__device__ __forceinline__ void t_dma16(const void *g, uint32_t lds_base) {
+  const uint32_t b = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_base);
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :: "v"(g), "s"(b) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void t_wait_vm() {
+  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+__device__ __forceinline__ void t_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+__device__ __forceinline__ f32x16 mfma32(u32x4 a, u32x4 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b),
+                                                 c, 0, 0, 0);
+}
+
+template <int MODE>
+__global__ __launch_bounds__(256) void expert_tiled_kernel(StreamArgs a, int n_shared_entries,
+                                                           int n_entries_ub, int rt_max) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wr = wave & 1, wt = wave >> 1;
+  const int r32 = lane & 31, q = lane >> 5;
+
+  // ---- which tile ---------------------------------------------------------------------
+  // consecutive linear ids = the entries (token blocks) of one row tile.  Workgroup
+  // ids are dealt to the 8 XCDs round-robin; the remap hands each XCD runs of 4
+  // consecutive linear ids (the blocks of one expert that share a weight tile), and
+  // deals those runs round-robin, so empty parts of the id space spread evenly.
+  const int n_lin = n_entries_ub * rt_max;
+  const int xcd = blockIdx.x % 8, g = blockIdx.x / 8;
+  const int lin = ((g / 4) * 8 + xcd) * 4 + (g % 4);
+  if (lin >= n_lin) return;
+  const int rt = lin / n_entries_ub;
+  const int entry = lin % n_entries_ub;
+
+  const int parts = (MODE == TMODE_DOWN && a.S > 0) ? (a.S + a.part_k - 1) / a.part_k : 1;
+  const uint16_t *A0, *A1;  // the two 64-row operand halves, row 0, at this entry's k origin
+  const uint16_t *B;
+  long a_stride, b_stride;
+  int n_rows, row0, m, klen, out_n;
+  bool use_map;
+  void *out;
+  if (entry < n_shared_entries) {
+    const int part = (MODE == TMODE_DOWN) ? entry % parts : 0;
+    const int blk = (MODE == TMODE_DOWN) ? entry / parts : entry;
+    row0 = blk * TBM;
+    m = min(a.T - row0, TBM);
+    use_map = false;
+    if (MODE == TMODE_GATE_UP) {
+      A0 = a.ws_gate; A1 = a.ws_up; a_stride = a.d; n_rows = a.S;
+      B = a.x; b_stride = a.d; klen = a.d; out = a.hs; out_n = a.S;
+    } else {
+      const int k0 = part * a.part_k;
+      A0 = a.ws_down + k0; A1 = A0 + (size_t)128 * a.S; a_stride = a.S; n_rows = a.d;
+      B = a.hs + k0; b_stride = a.S; klen = min(a.part_k, a.S - k0);
+      out = a.ys + (size_t)part * a.T * a.d; out_n = a.d;
+    }
+  } else {
+    const int le = entry - n_shared_entries;
+    if (le >= a.plan[2]) return;
+    const int base = PLAN_HDR + 3 * a.E;
+    const int e = a.plan[base + 2 * le], blk = a.plan[base + 2 * le + 1];
+    const int beg = a.offsets[e], end = a.offsets[e + 1];
+    row0 = beg + blk * TBM;
+    m = min(end - row0, TBM);
+    if (MODE == TMODE_GATE_UP) {
+      A0 = a.w_gate + (size_t)e * a.I * a.d; A1 = a.w_up + (size_t)e * a.I * a.d; a_stride = a.d;
+      n_rows = a.I; B = a.x; b_stride = a.d; use_map = true; klen = a.d; out = a.h; out_n = a.I;
+    } else {
+      A0 = a.w_down + (size_t)e * a.d * a.I; A1 = A0 + (size_t)128 * a.I; a_stride = a.I;
+      n_rows = a.d; B = a.h; b_stride = a.I; use_map = false; klen = a.I; out = a.y; out_n = a.d;
+    }
+  }
+  // first output feature of this tile; gate/up: 128 features (rows i0.. of both matrices),
+  // down: 256 features (rows i0.. and i0+128..)
+  const int i0 = (MODE == TMODE_GATE_UP) ? rt * 128 : rt * 256;
+  if (i0 >= n_rows) return;
+  const int rv0 = min(128, n_rows - i0);                                               // valid rows, first half
+  const int rv1 = (MODE == TMODE_GATE_UP) ? rv0 : max(1, min(128, n_rows - i0 - 128));  // second half
+  const bool second_ok = (MODE == TMODE_GATE_UP) || (n_rows - i0 > 128);
+
+  // ---- DMA assignment: one instruction = 16 rows x 64 bytes = 1 KB of LDS -----------------
+  // A: 256 rows = 16 instructions, 4 per wave; B: 256 rows = 16 instructions, 4 per wave.
+  // Lane l covers row 16j + (l >> 2) at LDS position (l & 3) and fetches piece
+  // pos ^ ((row >> 2) & 3) = pos ^ ((l >> 4) & 3).
+  const int sub = lane >> 2, pos = lane & 3;
+  const int mypiece = pos ^ ((sub >> 2) & 3);
+  const uint16_t *ga[4];
+  const uint16_t *gb[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = 16 * (4 * wave + i) + sub;  // 0..255
+    const int hrow = row & 127;
+    const uint16_t *base = (row >> 7) ? ((second_ok) ? A1 : A0) : A0;
+    const int rv = (row >> 7) ? rv1 : rv0;
+    ga[i] = base + (size_t)(i0 + min(hrow, rv - 1)) * a_stride;
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = 16 * (4 * wave + i) + sub;  // 0..255
+    int tr = row0 + min(row, m - 1);
+    if (use_map) tr = a.row_token[tr];
+    gb[i] = B + (size_t)tr * b_stride;
+  }
+
+  f32x16 acc[4][4];  // [weight tile: 2 of the first half, 2 of the second][token tile]
+#pragma unroll
+  for (int h = 0; h < 4; ++h)
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[h][t][v] = 0.f;
+
+  const int nkb = (klen + TBK - 1) / TBK;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
+  // exactly T_LW loads per wave; a piece past the end of the rows is pulled back inside
+  // (its products are masked below)
+  auto issue = [&](int kb) __attribute__((always_inline)) {
+    const int k = min(kb * TBK + mypiece * 8, klen - 8);
+    const uint32_t sbase = lds0 + (uint32_t)(kb % T_STAGES) * T_STAGE_BYTES;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) t_dma16(ga[i] + k, sbase + (uint32_t)(4 * wave + i) * 1024u);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) t_dma16(gb[i] + k, sbase + T_A_BYTES + (uint32_t)(4 * wave + i) * 1024u);
+  };
+
+  for (int i = 0; i < T_STAGES - 1 && i < nkb; ++i) issue(i);
+  const int key = (r32 >> 2) & 3;
+  for (int kb = 0; kb < nkb; ++kb) {
+    // stage kb has landed when at most the two younger stages' loads are pending
+    const int younger = min(nkb - 1 - kb, T_STAGES - 2);
+    if (younger == 2) t_wait_vm<2 * T_LW>();
+    else if (younger == 1) t_wait_vm<T_LW>();
+    else t_wait_vm<0>();
+    t_barrier();  // everyone's part of stage kb is in LDS; everyone is done reading stage kb-1
+    if (kb + T_STAGES - 1 < nkb) issue(kb + T_STAGES - 1);  // into the slot of stage kb-1
+    const char *s = smem + (kb % T_STAGES) * T_STAGE_BYTES;
+    // rows of this wave's weight tiles (64wr.. of each half) and token tiles (128wt..)
+    const char *pa = s + (64 * wr + r32) * T_ROW_BYTES;
+    const char *pb = s + T_A_BYTES + (128 * wt + r32) * T_ROW_BYTES;
+    const int kbase = kb * TBK;
+    const bool full = kbase + TBK <= klen;
+#pragma unroll
+    for (int st = 0; st < 2; ++st) {
+      const int off = ((2 * st + q) ^ key) << 4;
+      u32x4 fa[4], fb[4];
+#pragma unroll
+      for (int h = 0; h < 4; ++h)
+        fa[h] = *reinterpret_cast<const u32x4 *>(pa + ((h >> 1) * 128 + (h & 1) * 32) * T_ROW_BYTES + off);
+#pragma unroll
+      for (int t = 0; t < 4; ++t) fb[t] = *reinterpret_cast<const u32x4 *>(pb + t * 32 * T_ROW_BYTES + off);
+      if (!full && kbase + (2 * st + q) * 8 >= klen) {  // ragged last step: drop pieces past the end
+#pragma unroll
+        for (int t = 0; t < 4; ++t) fb[t] = (u32x4){0u, 0u, 0u, 0u};
+      }
+#pragma unroll
+      for (int h = 0; h < 4; ++h)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) acc[h][t] = mfma32(fa[h], fb[t], acc[h][t]);
+    }
+  }
+
+  // ---- epilogue: lane holds, for token (128wt + 32t + r32), features 8g + 4q + c ------------
+  // weight tile h: half (h >> 1), rows 64wr + 32(h & 1) .. +31 of that half
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int j = 128 * wt + 32 * t + r32;
+    if (j < m) {
+      const size_t orow = (size_t)(row0 + j);
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int f = 64 * wr + 32 * hh + 8 * g + 4 * q;  // feature inside the 128 of a half
+          if (MODE == TMODE_GATE_UP) {
+            const int i = i0 + f;
+            if (i < out_n) {
+              uint32_t hb[4];
+#pragma unroll
+              for (int c = 0; c < 4; ++c)
+                hb[c] = f32_to_bf16_bits(silu_f32(acc[hh][t][4 * g + c]) * acc[2 + hh][t][4 * g + c]);
+              u32x2 o;
+              o[0] = hb[0] | (hb[1] << 16);
+              o[1] = hb[2] | (hb[3] << 16);
+              *reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(out) + orow * out_n + i) = o;
+            }
+          } else {
+            float *y = reinterpret_cast<float *>(out);
+#pragma unroll
+            for (int h2 = 0; h2 < 2; ++h2) {
+              const int i = i0 + 128 * h2 + f;
+              if (i < out_n) {
+                const f32x16 &v = acc[2 * h2 + hh][t];
+                f32x4 o = {v[4 * g], v[4 * g + 1], v[4 * g + 2], v[4 * g + 3]};
+                *reinterpret_cast<f32x4 *>(y + orow * out_n + i) = o;
+              }
+            }
+          }
+        }
+    }
+  }
+}
+
+static hipError_t launch_tiled(int mode, const StreamArgs &a, hipStream_t s) {
+  static bool attr_set[2] = {false, false};
+  const void *fn = mode == TMODE_GATE_UP ? reinterpret_cast<const void *>(expert_tiled_kernel<TMODE_GATE_UP>)
+                                         : reinterpret_cast<const void *>(expert_tiled_kernel<TMODE_DOWN>);
+  if (!attr_set[mode]) {
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, TILED_LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_set[mode] = true;
+  }
+  const int parts = (mode == TMODE_DOWN && a.S > 0) ? (a.S + a.part_k - 1) / a.part_k : 1;
+  const int n_shared = (a.S > 0 && a.T > 64) ? ((a.T + TBM - 1) / TBM) * parts : 0;
+  // experts with more than 64 rows: at most T*K/65 of them, each with ceil(m/256) blocks
+  const long tk = (long)a.T * a.K;
+  long n_large_ub = tk / 65;
+  if (n_large_ub > a.E) n_large_ub = a.E;
+  n_large_ub += tk / TBM;
+  const int n_entries = n_shared + (int)n_large_ub;
+  if (n_entries == 0) return hipSuccess;
+  int rt_max;
+  if (mode == TMODE_GATE_UP) {
+    const int nmax = a.I > a.S ? a.I : a.S;
+    rt_max = (nmax + 127) / 128;
+  } else {
+    rt_max = (a.d + 255) / 256;
+  }
+  const long n_lin = (long)n_entries * rt_max;
+  const long grid = ((n_lin + 31) / 32) * 32;
+  if (mode == TMODE_GATE_UP)
+    hipLaunchKernelGGL(expert_tiled_kernel<TMODE_GATE_UP>, dim3((unsigned)grid), dim3(256), TILED_LDS_BYTES, s, a,
+                       n_shared, n_entries, rt_max);
+  else
+    hipLaunchKernelGGL(expert_tiled_kernel<TMODE_DOWN>, dim3((unsigned)grid), dim3(256), TILED_LDS_BYTES, s, a,
+                       n_shared, n_entries, rt_max);
+  return hipGetLastError();
+}
+
+hipError_t launch_gate_up_tiled(const StreamArgs &a, hipStream_t s) { return launch_tiled(TMODE_GATE_UP, a, s); }
+hipError_t launch_down_tiled(const StreamArgs &a, hipStream_t s) { return launch_tiled(TMODE_DOWN, a, s); }

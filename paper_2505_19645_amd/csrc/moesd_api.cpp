@@ -76,7 +76,7 @@ Workspace carve(const moesd_layer_desc *c, int64_t T, char *base) {
   ws.inv = (int32_t *)take(sizeof(int32_t) * T * K);
   ws.n_active = (int32_t *)take(sizeof(int32_t));
   ws.row_token = (int32_t *)take(sizeof(int32_t) * T * K);
-  ws.plan = (int32_t *)take(sizeof(int32_t) * (PLAN_HDR + E + 2 * (E + T * K / 64 + 2)));
+  ws.plan = (int32_t *)take(sizeof(int32_t) * PLAN_WORDS(E, T * K));
   ws.part_k = shared_part_k(c);
   ws.parts = S > 0 ? (int32_t)((S + ws.part_k - 1) / ws.part_k) : 0;
   ws.gate = (float *)take(sizeof(float) * T);
@@ -231,9 +231,12 @@ int32_t moesd_moe_forward_staged(const moesd_layer_desc *desc, const moesd_weigh
   a.I = desc->inter;
   a.S = desc->shared_inter;
   a.T = T;
+  // experts with at most 64 rows stream; the others (possible only if T > 64) are tiled
   MOESD_TRY(launch_gate_up(a, s))
+  if (T > 64) MOESD_TRY(launch_gate_up_tiled(a, s))
   MOESD_EVENT(2)
   MOESD_TRY(launch_down(a, s))
+  if (T > 64) MOESD_TRY(launch_down_tiled(a, s))
   MOESD_EVENT(3)
   MOESD_TRY(launch_combine(ws.y, ws.ys, ws.parts, w, ws.gate, iv, T, desc->top_k, desc->d,
                            (uint16_t *)out, out_f32, s))

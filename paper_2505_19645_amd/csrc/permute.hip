@@ -30,7 +30,7 @@ __device__ __forceinline__ void permute_body(
     int32_t *smem) {
   int32_t *hist = smem;                     // [PERM_WAVES][E]
   int32_t *scan = smem + PERM_WAVES * E;    // [PERM_THREADS] scratch for the scan over experts
-  __shared__ int32_t wave_tot[3][PERM_WAVES];
+  __shared__ int32_t wave_tot[4][PERM_WAVES];
   __shared__ int32_t active_tot;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -69,36 +69,41 @@ __device__ __forceinline__ void permute_body(
     counts[e] = total;
   }
   // exclusive scans over experts (tid == expert index): the totals give the
-  // offsets; the other two place each expert in the expert kernels' work lists
-  // (1..16 rows: one entry in the "small" list; more: one entry per 64-row block)
+  // offsets; the others place each expert in the expert kernels' work lists
+  // (1..16 rows: "small"; 17..64: "big"; more: one "large" entry per 256-row block)
   const int v = (tid < E) ? total : 0;
   const int v_small = (v >= 1 && v <= 16) ? 1 : 0;
-  const int v_big = (v > 16) ? (v + 63) / 64 : 0;
-  int incl = v, incl_s = v_small, incl_b = v_big;
+  const int v_big = (v > 16 && v <= 64) ? 1 : 0;
+  const int v_large = (v > 64) ? (v + 255) / 256 : 0;
+  int incl = v, incl_s = v_small, incl_b = v_big, incl_l = v_large;
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) {
     const int o = __shfl_up(incl, off, 64);
     const int os = __shfl_up(incl_s, off, 64);
     const int ob = __shfl_up(incl_b, off, 64);
+    const int ol = __shfl_up(incl_l, off, 64);
     if (lane >= off) {
       incl += o;
       incl_s += os;
       incl_b += ob;
+      incl_l += ol;
     }
   }
   if (lane == 63) {
     wave_tot[0][wave] = incl;
     wave_tot[1][wave] = incl_s;
     wave_tot[2][wave] = incl_b;
+    wave_tot[3][wave] = incl_l;
   }
   const unsigned long long act = __ballot(tid < E && total > 0);
   if (lane == 0 && act) atomicAdd(&active_tot, __popcll(act));
   __syncthreads();
-  int wbase = 0, wbase_s = 0, wbase_b = 0;
+  int wbase = 0, wbase_s = 0, wbase_b = 0, wbase_l = 0;
   for (int w = 0; w < wave; ++w) {
     wbase += wave_tot[0][w];
     wbase_s += wave_tot[1][w];
     wbase_b += wave_tot[2][w];
+    wbase_l += wave_tot[3][w];
   }
   const int excl = wbase + incl - v;
   if (tid < E) {
@@ -106,10 +111,14 @@ __device__ __forceinline__ void permute_body(
     scan[tid] = excl;
     if (plan) {
       if (v_small) plan[PLAN_HDR + wbase_s + incl_s - 1] = tid;
-      const int pos = wbase_b + incl_b - v_big;
-      for (int b = 0; b < v_big; ++b) {
-        plan[PLAN_HDR + E + 2 * (pos + b)] = tid;
-        plan[PLAN_HDR + E + 2 * (pos + b) + 1] = b;
+      if (v_big) {
+        plan[PLAN_HDR + E + 2 * (wbase_b + incl_b - 1)] = tid;
+        plan[PLAN_HDR + E + 2 * (wbase_b + incl_b - 1) + 1] = 0;
+      }
+      const int pos = wbase_l + incl_l - v_large;
+      for (int b = 0; b < v_large; ++b) {
+        plan[PLAN_HDR + 3 * E + 2 * (pos + b)] = tid;
+        plan[PLAN_HDR + 3 * E + 2 * (pos + b) + 1] = b;
       }
     }
   }
@@ -117,13 +126,15 @@ __device__ __forceinline__ void permute_body(
     offsets[E] = (int32_t)n;
     *n_active = active_tot;
     if (plan) {
-      int ns = 0, nb = 0;
+      int ns = 0, nb = 0, nl = 0;
       for (int w = 0; w < PERM_WAVES; ++w) {
         ns += wave_tot[1][w];
         nb += wave_tot[2][w];
+        nl += wave_tot[3][w];
       }
       plan[0] = ns;
       plan[1] = nb;
+      plan[2] = nl;
     }
   }
   __syncthreads();

@@ -65,6 +65,19 @@ def test_variants(gpu, oracle, shape):
     run_case(gpu, oracle, shape, 23)
 
 
+@pytest.mark.parametrize("shape,T", [
+    (LayerShape("rows-gt-64", d=256, E=4, top_k=2, inter=192, shared_inter=96, shared_gate=1, seed=31), 300),
+    (LayerShape("rows-gt-256", d=128, E=2, top_k=1, inter=136, seed=32), 700),
+    (LayerShape("tiled-tails", d=264, E=3, top_k=2, inter=72, shared_inter=40, seed=33), 130),
+    (LayerShape("mixed-classes", d=256, E=16, top_k=2, inter=128, shared_inter=64, shared_gate=1, seed=34), 200),
+])
+def test_many_rows_per_expert(gpu, oracle, shape, T):
+    # experts above 64 rows go through the MFMA-tiled kernel; the skewed case mixes all three classes
+    skew = 2.0 if shape.name == "mixed-classes" else 0.0
+    got, ref = run_case(gpu, oracle, shape, T, skew=skew)
+    assert got["counts"].max() > 64
+
+
 def test_skewed_routing_and_bias(gpu, oracle):
     shape = LayerShape("skew", d=256, E=64, top_k=8, inter=128, shared_inter=256, shared_gate=1, seed=16)
     got, ref = run_case(gpu, oracle, shape, 48, skew=1.5)
