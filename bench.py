@@ -164,6 +164,8 @@ def main():
     ap.add_argument("--curve-steps", type=int, default=30)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--replicas", type=int, default=0)
+    ap.add_argument("--no-mfma-point", action="store_true",
+                    help="skip the extra compute-bound point (Mixtral-8x7B-shaped layer, T=4096)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (known traffic) for scaling rocprofv3 --pmc byte counters")
     args = ap.parse_args()
@@ -266,6 +268,60 @@ def main():
         if c["gamma"] > 0 and (c["B"], 0) in by:
             c["target_efficiency"] = round(by[(c["B"], 0)] / c["us"], 4)
 
+    # ---- the paper's forward-time model over the measured curve (Sec. 3.3, Appendix C.2) ----
+    model_fit = None
+    if len(curve) >= 6:
+        from paper_2505_19645_amd import sdmodel
+        k2_min_us = shape.expert_bytes / (HBM_PEAK_GBS * 1e9) * 1e6
+        model_fit = sdmodel.fit_layer_curve([c["T"] for c in curve], [c["n_active"] for c in curve],
+                                            [c["us"] for c in curve], shape.E, shape.top_k, k2_min_us,
+                                            MFMA_BF16_PEAK_TF * 1e12 / (HBM_PEAK_GBS * 1e9))
+        log(f"[bench] model t = c0 + c2*N + c3*G(Texp): c0={model_fit['c0_us']:.1f} us, "
+            f"c2={model_fit['c2_us_per_expert']:.2f} us/expert ({model_fit['c2_over_k2_min']:.2f} x k2_min), "
+            f"c3={model_fit['c3_us']:.2f}, mean rel err {model_fit['mean_rel_err']:.3f}")
+
+    # ---- compute-bound point: Mixtral-8x7B-shaped layer at T = 4096 (MFMA roofline) ----
+    mfma = None
+    if not args.no_mfma_point:
+        mshape = synth.PRESETS["mixtral-8x7b"]
+        mT = 4096
+        del run
+        torch.cuda.empty_cache()
+        g = torch.Generator(device="cuda:0")
+        g.manual_seed(3000)
+
+        def rnd(*dims, std):
+            return (torch.randn(*dims, device="cuda:0", generator=g, dtype=torch.float32) * std) \
+                .to(torch.bfloat16).view(torch.int16)
+        r = synth.make_router(mshape)
+        dw = {"w_router": torch.from_numpy(r["w_router"].view(np.int16)).to("cuda:0"), "router_bias": None,
+              "w_gate": rnd(mshape.E, mshape.inter, mshape.d, std=mshape.d ** -0.5),
+              "w_up": rnd(mshape.E, mshape.inter, mshape.d, std=mshape.d ** -0.5),
+              "w_down": rnd(mshape.E, mshape.d, mshape.inter, std=mshape.inter ** -0.5),
+              "ws_gate": None, "ws_up": None, "ws_down": None, "w_shared_gate": None}
+        mrun = Runner.__new__(Runner)
+        mrun.torch, mrun.moesd, mrun.shape = torch, moesd, mshape
+        mrun.desc = moesd.make_desc(mshape)
+        mrun.reps = [dw]
+        mrun.wstructs = [moesd.make_weights(dw)]
+        mrun.stream = torch.cuda.current_stream().cuda_stream
+        mrun.prepare(synth.make_tokens(mshape, mT, point=mT))
+        mms = mrun.time_steps(10, 3)
+        mst = mrun.time_stages(10, 3)
+        mfl = layer_flops(mshape, mT)
+        gu_fl = 4 * mT * mshape.top_k * mshape.d * mshape.inter
+        mfma = {"workload": f"{mshape.name}-shaped MoE layer, T={mT} (router from the seeded generator, "
+                            "expert weights drawn on the device: timing only)",
+                "us_per_layer": round(mms * 1e3, 1), "layer_TFLOPs": round(mfl / (mms * 1e-3) / 1e12, 1),
+                "layer_frac_of_peak": round(mfl / (mms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TF, 4),
+                "gate_up_us": round(mst["gate_up"] * 1e3, 1),
+                "gate_up_TFLOPs": round(gu_fl / (mst["gate_up"] * 1e-3) / 1e12, 1),
+                "gate_up_frac_of_peak": round(gu_fl / (mst["gate_up"] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TF, 4),
+                "peak_TFLOPs": MFMA_BF16_PEAK_TF, "n_active": int(mrun.n_active.item()),
+                "max_rows_per_expert": int(mrun.counts.max().item())}
+        log(f"[bench] MFMA point: {mfma['us_per_layer']} us/layer, {mfma['layer_TFLOPs']} TFLOP/s "
+            f"({mfma['layer_frac_of_peak']:.2%} of bf16 peak); gate/up kernel {mfma['gate_up_TFLOPs']} TFLOP/s")
+
     # ---- CPU baseline: the oracle as it stands, one forward of the same batch ----
     cpu = None
     if not args.no_cpu_baseline:
@@ -291,6 +347,7 @@ def main():
                    "shared_inter": shape.shared_inter, "skew_std": args.skew,
                    "weight_replicas": n_rep, "cold_weights": True},
         "roofline": roofline, "cpu_baseline": cpu, "layer": layer, "stages_us": stages, "curve": curve,
+        "model_fit": model_fit, "mfma_point": mfma,
     }
     print(json.dumps(result), flush=True)
 

@@ -41,13 +41,15 @@ __device__ __forceinline__ float silu_f32(float z) { return z / (1.0f + expf(-z)
 
 // Plan written by the permutation kernel for the expert kernels (int32 words):
 //   [0] n_small: experts with 1..16 rows
-//   [1] n_big:   experts with 17..64 rows
-//   [2] n_large: (expert, 256-row block) entries of the experts with more than 64 rows
+//   [1] n_big:   (expert, 64-row block) entries of the experts with 17..128 rows
+//   [2] n_large: (expert, 256-row block) entries of the experts with more than 128 rows
 //   [PLAN_HDR .. +E)        ids of the small experts, ascending
-//   [PLAN_HDR+E .. +2E)     n_big pairs (expert id, 0), ascending
-//   [PLAN_HDR+3E .. )       n_large pairs (expert id, block index), ascending by expert, block
+//   [PLAN_HDR+E .. +4E)     n_big pairs (expert id, block index), ascending by expert, block
+//   [PLAN_HDR+5E .. )       n_large pairs (expert id, block index), ascending by expert, block
 #define PLAN_HDR 4
-#define PLAN_WORDS(E, TK) (PLAN_HDR + 3 * (E) + 2 * ((E) + (TK) / 256 + 2))
+#define PLAN_BIG_MAX_ROWS 128
+#define PLAN_LARGE_OFF(E) (PLAN_HDR + 5 * (E))
+#define PLAN_WORDS(E, TK) (PLAN_LARGE_OFF(E) + 2 * ((E) + (TK) / 256 + 2))
 
 struct StreamArgs {
   // routed experts

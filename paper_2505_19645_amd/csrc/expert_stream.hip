@@ -15,7 +15,8 @@
 //      wide:  17..64 rows.  128 weight rows (64 + 64, or 128 of w_down),
 //             contraction blocks of 128 elements; a block is two slots: 32 KB
 //             of weights + 16 KB of tokens.
-//    Experts with more than 64 rows belong to the MFMA-tiled kernel.
+//    Experts with 65..128 rows run as two wide blocks (their weights stream twice);
+//    beyond that they belong to the MFMA-tiled kernel.
 //  * Every slot is exactly six global_load_lds_dwordx4 per wave, each moving
 //    1 KB (two 512-byte or four 256-byte row pieces, contiguous in HBM) straight
 //    into LDS; the weights carry the non-temporal hint (each byte is read once).
@@ -624,7 +625,7 @@ __global__ __launch_bounds__(256) void expert_stream_kernel(StreamArgs a,
   // small tiles: [shared expert's, if it has at most 16 rows][small routed entries]
   const int n_small_e = sload(plan, 0), n_big_e = sload(plan, 1);
   const bool has_shared = a.S > 0;
-  const bool shared_wide = a.T > SMALL_M && a.T <= BIG_TB;   // more rows: the tiled kernel takes it
+  const bool shared_wide = a.T > SMALL_M && a.T <= PLAN_BIG_MAX_ROWS;   // more rows: the tiled kernel takes it
   const bool shared_small = a.T <= SMALL_M;
   const int parts = (MODE == MODE_DOWN && has_shared) ? (a.S + a.part_k - 1) / a.part_k : 1;
   ClassCfg cw, cs;

@@ -2,7 +2,7 @@
 //
 // Once an expert's load T_exp passes the ridge point the layer turns from
 // loading weights to computing (the k3*G(T_exp) term of the paper's Sec. 3.3
-// model).  Experts (or the shared expert) with more than 64 token rows are cut
+// model).  Experts (or the shared expert) with more than 128 token rows are cut
 // into blocks of 256 rows and handled here: a workgroup computes a 256-token x
 // 256-weight-row tile (128 w_gate rows + the same 128 w_up rows with SwiGLU
 // fused, or 256 w_down rows), marching over the contraction dimension in
@@ -62,23 +62,32 @@ __device__ __forceinline__ f32x16 mfma32(u32x4 a, u32x4 b, f32x16 c) {
 
 template <int MODE>
 __global__ __launch_bounds__(256) void expert_tiled_kernel(StreamArgs a, int n_shared_entries,
-                                                           int n_entries_ub, int rt_max) {
+                                                           int rt_shared, int rt_routed) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave & 1, wt = wave >> 1;
   const int r32 = lane & 31, q = lane >> 5;
 
   // ---- which tile ---------------------------------------------------------------------
-  // consecutive linear ids = the entries (token blocks) of one row tile.  Workgroup
-  // ids are dealt to the 8 XCDs round-robin; the remap hands each XCD runs of 4
-  // consecutive linear ids (the blocks of one expert that share a weight tile), and
-  // deals those runs round-robin, so empty parts of the id space spread evenly.
-  const int n_lin = n_entries_ub * rt_max;
+  // The tiles with work are numbered densely: first the shared expert's (row tile major,
+  // its token blocks adjacent), then the routed experts' (row tile major over the actual
+  // number of large entries, blocks of one expert adjacent).  Workgroup ids are dealt to
+  // the 8 XCDs round-robin; the remap hands each XCD runs of 4 consecutive tile numbers
+  // (blocks that share a weight tile) and deals those runs round-robin.
   const int xcd = blockIdx.x % 8, g = blockIdx.x / 8;
   const int lin = ((g / 4) * 8 + xcd) * 4 + (g % 4);
-  if (lin >= n_lin) return;
-  const int rt = lin / n_entries_ub;
-  const int entry = lin % n_entries_ub;
+  const int n_large = a.plan[2];
+  const int n_sh_tiles = n_shared_entries * rt_shared;
+  int rt, entry;
+  if (lin < n_sh_tiles) {
+    rt = lin / n_shared_entries;
+    entry = lin % n_shared_entries;
+  } else {
+    const int lr = lin - n_sh_tiles;
+    if (n_large == 0 || lr >= n_large * rt_routed) return;
+    rt = lr / n_large;
+    entry = n_shared_entries + lr % n_large;
+  }
 
   const int parts = (MODE == TMODE_DOWN && a.S > 0) ? (a.S + a.part_k - 1) / a.part_k : 1;
   const uint16_t *A0, *A1;  // the two 64-row operand halves, row 0, at this entry's k origin
@@ -104,8 +113,7 @@ __global__ __launch_bounds__(256) void expert_tiled_kernel(StreamArgs a, int n_s
     }
   } else {
     const int le = entry - n_shared_entries;
-    if (le >= a.plan[2]) return;
-    const int base = PLAN_HDR + 3 * a.E;
+    const int base = PLAN_LARGE_OFF(a.E);
     const int e = a.plan[base + 2 * le], blk = a.plan[base + 2 * le + 1];
     const int beg = a.offsets[e], end = a.offsets[e + 1];
     row0 = beg + blk * TBM;
@@ -258,29 +266,28 @@ static hipError_t launch_tiled(int mode, const StreamArgs &a, hipStream_t s) {
     attr_set[mode] = true;
   }
   const int parts = (mode == TMODE_DOWN && a.S > 0) ? (a.S + a.part_k - 1) / a.part_k : 1;
-  const int n_shared = (a.S > 0 && a.T > 64) ? ((a.T + TBM - 1) / TBM) * parts : 0;
-  // experts with more than 64 rows: at most T*K/65 of them, each with ceil(m/256) blocks
+  const int n_shared = (a.S > 0 && a.T > PLAN_BIG_MAX_ROWS) ? ((a.T + TBM - 1) / TBM) * parts : 0;
+  // experts with more than 128 rows: at most T*K/129 of them, each with ceil(m/256) blocks
   const long tk = (long)a.T * a.K;
-  long n_large_ub = tk / 65;
+  long n_large_ub = tk / (PLAN_BIG_MAX_ROWS + 1);
   if (n_large_ub > a.E) n_large_ub = a.E;
   n_large_ub += tk / TBM;
-  const int n_entries = n_shared + (int)n_large_ub;
-  if (n_entries == 0) return hipSuccess;
-  int rt_max;
+  if (n_shared + n_large_ub == 0) return hipSuccess;
+  int rt_s, rt_r;
   if (mode == TMODE_GATE_UP) {
-    const int nmax = a.I > a.S ? a.I : a.S;
-    rt_max = (nmax + 127) / 128;
+    rt_s = (a.S + 127) / 128;
+    rt_r = (a.I + 127) / 128;
   } else {
-    rt_max = (a.d + 255) / 256;
+    rt_s = rt_r = (a.d + 255) / 256;
   }
-  const long n_lin = (long)n_entries * rt_max;
+  const long n_lin = (long)n_shared * rt_s + n_large_ub * rt_r;
   const long grid = ((n_lin + 31) / 32) * 32;
   if (mode == TMODE_GATE_UP)
     hipLaunchKernelGGL(expert_tiled_kernel<TMODE_GATE_UP>, dim3((unsigned)grid), dim3(256), TILED_LDS_BYTES, s, a,
-                       n_shared, n_entries, rt_max);
+                       n_shared, rt_s, rt_r);
   else
     hipLaunchKernelGGL(expert_tiled_kernel<TMODE_DOWN>, dim3((unsigned)grid), dim3(256), TILED_LDS_BYTES, s, a,
-                       n_shared, n_entries, rt_max);
+                       n_shared, rt_s, rt_r);
   return hipGetLastError();
 }
 

@@ -231,12 +231,12 @@ int32_t moesd_moe_forward_staged(const moesd_layer_desc *desc, const moesd_weigh
   a.I = desc->inter;
   a.S = desc->shared_inter;
   a.T = T;
-  // experts with at most 64 rows stream; the others (possible only if T > 64) are tiled
+  // experts with at most 128 rows stream; the others (possible only if T > 128) are tiled
   MOESD_TRY(launch_gate_up(a, s))
-  if (T > 64) MOESD_TRY(launch_gate_up_tiled(a, s))
+  if (T > PLAN_BIG_MAX_ROWS) { MOESD_TRY(launch_gate_up_tiled(a, s)) }
   MOESD_EVENT(2)
   MOESD_TRY(launch_down(a, s))
-  if (T > 64) MOESD_TRY(launch_down_tiled(a, s))
+  if (T > PLAN_BIG_MAX_ROWS) { MOESD_TRY(launch_down_tiled(a, s)) }
   MOESD_EVENT(3)
   MOESD_TRY(launch_combine(ws.y, ws.ys, ws.parts, w, ws.gate, iv, T, desc->top_k, desc->d,
                            (uint16_t *)out, out_f32, s))

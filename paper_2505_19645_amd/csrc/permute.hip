@@ -70,11 +70,12 @@ __device__ __forceinline__ void permute_body(
   }
   // exclusive scans over experts (tid == expert index): the totals give the
   // offsets; the others place each expert in the expert kernels' work lists
-  // (1..16 rows: "small"; 17..64: "big"; more: one "large" entry per 256-row block)
+  // (1..16 rows: "small"; 17..128: one "big" entry per 64-row block; more: one
+  // "large" entry per 256-row block)
   const int v = (tid < E) ? total : 0;
   const int v_small = (v >= 1 && v <= 16) ? 1 : 0;
-  const int v_big = (v > 16 && v <= 64) ? 1 : 0;
-  const int v_large = (v > 64) ? (v + 255) / 256 : 0;
+  const int v_big = (v > 16 && v <= PLAN_BIG_MAX_ROWS) ? (v + 63) / 64 : 0;
+  const int v_large = (v > PLAN_BIG_MAX_ROWS) ? (v + 255) / 256 : 0;
   int incl = v, incl_s = v_small, incl_b = v_big, incl_l = v_large;
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) {
@@ -111,14 +112,15 @@ __device__ __forceinline__ void permute_body(
     scan[tid] = excl;
     if (plan) {
       if (v_small) plan[PLAN_HDR + wbase_s + incl_s - 1] = tid;
-      if (v_big) {
-        plan[PLAN_HDR + E + 2 * (wbase_b + incl_b - 1)] = tid;
-        plan[PLAN_HDR + E + 2 * (wbase_b + incl_b - 1) + 1] = 0;
+      const int posb = wbase_b + incl_b - v_big;
+      for (int b = 0; b < v_big; ++b) {
+        plan[PLAN_HDR + E + 2 * (posb + b)] = tid;
+        plan[PLAN_HDR + E + 2 * (posb + b) + 1] = b;
       }
       const int pos = wbase_l + incl_l - v_large;
       for (int b = 0; b < v_large; ++b) {
-        plan[PLAN_HDR + 3 * E + 2 * (pos + b)] = tid;
-        plan[PLAN_HDR + 3 * E + 2 * (pos + b) + 1] = b;
+        plan[PLAN_LARGE_OFF(E) + 2 * (pos + b)] = tid;
+        plan[PLAN_LARGE_OFF(E) + 2 * (pos + b) + 1] = b;
       }
     }
   }
