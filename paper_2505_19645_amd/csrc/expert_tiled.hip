@@ -8,10 +8,10 @@
 // fused, or 256 w_down rows), marching over the contraction dimension in
 // 32-element steps through a four-stage LDS ring, with v_mfma_f32_32x32x16_bf16.
 //
-//  * Four waves as 2 (row halves) x 2 (token halves); a wave owns 2 x 2 32-row
-//    tiles (gate and up rows 64wr..64wr+63, or two 64-row groups of w_down) x
-//    four 32-token tiles = 16 accumulator tiles (256 accumulator registers):
-//    8 operand reads feed 16 MFMAs, 131 flops per byte brought into LDS.
+//  * Eight waves (two per SIMD, so one multiplies while the other waits for LDS)
+//    as 2 (row halves) x 4 (token quarters); a wave owns 2 x 2 32-row tiles (gate
+//    and up rows 64wr..64wr+63, or two 64-row groups of w_down) x two 32-token
+//    tiles = 8 accumulator tiles; 131 flops per byte brought into LDS.
 //  * Operands go straight from global memory into the LDS ring with
 //    global_load_lds_dwordx4 (no staging registers, three steps in flight while
 //    one is multiplied); loads are issued and awaited by hand, one s_barrier per
@@ -19,9 +19,8 @@
 //    (row >> 2) & 3: four rows share a 256-byte bank line, and the 16 rows a
 //    quarter-wave reads then fall into 16 different 16-byte bank groups, while
 //    the DMA writes stay linear.
-//  * Workgroup ids are remapped so that the token blocks of one expert that share
-//    a weight tile, and the row tiles that share a token block, run on one XCD at
-//    the same time and meet in its L2.
+//  * Workgroup ids are remapped so that runs of 4 consecutive tiles (the token blocks
+//    of one expert that share a weight tile) land on the same XCD and meet in its L2.
 //
 // MFMA operand use (32x32x16): lane l = 32*q + r supplies 8 consecutive
 // contraction elements (piece 2*s + q of step s) of weight row r as A and of
@@ -37,7 +36,8 @@
 #define T_B_BYTES (TBM * T_ROW_BYTES)  // 16 KB
 #define T_STAGE_BYTES (T_A_BYTES + T_B_BYTES)
 #define T_STAGES 4
-#define T_LW 8  // loads per wave per stage
+#define T_LW 4  // loads per wave per stage
+#define T_THREADS 512
 #define TILED_LDS_BYTES (T_STAGES * T_STAGE_BYTES)
 
 enum { TMODE_GATE_UP = 0, TMODE_DOWN = 1 };
@@ -61,11 +61,11 @@ __device__ __forceinline__ f32x16 mfma32(u32x4 a, u32x4 b, f32x16 c) {
 }
 
 template <int MODE>
-__global__ __launch_bounds__(256) void expert_tiled_kernel(StreamArgs a, int n_shared_entries,
+__global__ __launch_bounds__(T_THREADS) void expert_tiled_kernel(StreamArgs a, int n_shared_entries,
                                                            int rt_shared, int rt_routed) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wr = wave & 1, wt = wave >> 1;
+  const int wr = wave & 1, wt = wave >> 1;  // wt: 0..3
   const int r32 = lane & 31, q = lane >> 5;
 
   // ---- which tile ---------------------------------------------------------------------
@@ -135,34 +135,34 @@ __global__ __launch_bounds__(256) void expert_tiled_kernel(StreamArgs a, int n_s
   const bool second_ok = (MODE == TMODE_GATE_UP) || (n_rows - i0 > 128);
 
   // ---- DMA assignment: one instruction = 16 rows x 64 bytes = 1 KB of LDS -----------------
-  // A: 256 rows = 16 instructions, 4 per wave; B: 256 rows = 16 instructions, 4 per wave.
+  // A: 256 rows = 16 instructions, 2 per wave; B: 256 rows = 16 instructions, 2 per wave.
   // Lane l covers row 16j + (l >> 2) at LDS position (l & 3) and fetches piece
   // pos ^ ((row >> 2) & 3) = pos ^ ((l >> 4) & 3).
   const int sub = lane >> 2, pos = lane & 3;
   const int mypiece = pos ^ ((sub >> 2) & 3);
-  const uint16_t *ga[4];
-  const uint16_t *gb[4];
+  const uint16_t *ga[2];
+  const uint16_t *gb[2];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int row = 16 * (4 * wave + i) + sub;  // 0..255
+  for (int i = 0; i < 2; ++i) {
+    const int row = 16 * (2 * wave + i) + sub;  // 0..255
     const int hrow = row & 127;
     const uint16_t *base = (row >> 7) ? ((second_ok) ? A1 : A0) : A0;
     const int rv = (row >> 7) ? rv1 : rv0;
     ga[i] = base + (size_t)(i0 + min(hrow, rv - 1)) * a_stride;
   }
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int row = 16 * (4 * wave + i) + sub;  // 0..255
+  for (int i = 0; i < 2; ++i) {
+    const int row = 16 * (2 * wave + i) + sub;  // 0..255
     int tr = row0 + min(row, m - 1);
     if (use_map) tr = a.row_token[tr];
     gb[i] = B + (size_t)tr * b_stride;
   }
 
-  f32x16 acc[4][4];  // [weight tile: 2 of the first half, 2 of the second][token tile]
+  f32x16 acc[4][2];  // [weight tile: 2 of the first half, 2 of the second][token tile]
 #pragma unroll
   for (int h = 0; h < 4; ++h)
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
+    for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[h][t][v] = 0.f;
 
@@ -174,9 +174,9 @@ __global__ __launch_bounds__(256) void expert_tiled_kernel(StreamArgs a, int n_s
     const int k = min(kb * TBK + mypiece * 8, klen - 8);
     const uint32_t sbase = lds0 + (uint32_t)(kb % T_STAGES) * T_STAGE_BYTES;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) t_dma16(ga[i] + k, sbase + (uint32_t)(4 * wave + i) * 1024u);
+    for (int i = 0; i < 2; ++i) t_dma16(ga[i] + k, sbase + (uint32_t)(2 * wave + i) * 1024u);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) t_dma16(gb[i] + k, sbase + T_A_BYTES + (uint32_t)(4 * wave + i) * 1024u);
+    for (int i = 0; i < 2; ++i) t_dma16(gb[i] + k, sbase + T_A_BYTES + (uint32_t)(2 * wave + i) * 1024u);
   };
 
   for (int i = 0; i < T_STAGES - 1 && i < nkb; ++i) issue(i);
@@ -192,34 +192,34 @@ __global__ __launch_bounds__(256) void expert_tiled_kernel(StreamArgs a, int n_s
     const char *s = smem + (kb % T_STAGES) * T_STAGE_BYTES;
     // rows of this wave's weight tiles (64wr.. of each half) and token tiles (128wt..)
     const char *pa = s + (64 * wr + r32) * T_ROW_BYTES;
-    const char *pb = s + T_A_BYTES + (128 * wt + r32) * T_ROW_BYTES;
+    const char *pb = s + T_A_BYTES + (64 * wt + r32) * T_ROW_BYTES;
     const int kbase = kb * TBK;
     const bool full = kbase + TBK <= klen;
 #pragma unroll
     for (int st = 0; st < 2; ++st) {
       const int off = ((2 * st + q) ^ key) << 4;
-      u32x4 fa[4], fb[4];
+      u32x4 fa[4], fb[2];
 #pragma unroll
       for (int h = 0; h < 4; ++h)
         fa[h] = *reinterpret_cast<const u32x4 *>(pa + ((h >> 1) * 128 + (h & 1) * 32) * T_ROW_BYTES + off);
 #pragma unroll
-      for (int t = 0; t < 4; ++t) fb[t] = *reinterpret_cast<const u32x4 *>(pb + t * 32 * T_ROW_BYTES + off);
+      for (int t = 0; t < 2; ++t) fb[t] = *reinterpret_cast<const u32x4 *>(pb + t * 32 * T_ROW_BYTES + off);
       if (!full && kbase + (2 * st + q) * 8 >= klen) {  // ragged last step: drop pieces past the end
 #pragma unroll
-        for (int t = 0; t < 4; ++t) fb[t] = (u32x4){0u, 0u, 0u, 0u};
+        for (int t = 0; t < 2; ++t) fb[t] = (u32x4){0u, 0u, 0u, 0u};
       }
 #pragma unroll
       for (int h = 0; h < 4; ++h)
 #pragma unroll
-        for (int t = 0; t < 4; ++t) acc[h][t] = mfma32(fa[h], fb[t], acc[h][t]);
+        for (int t = 0; t < 2; ++t) acc[h][t] = mfma32(fa[h], fb[t], acc[h][t]);
     }
   }
 
-  // ---- epilogue: lane holds, for token (128wt + 32t + r32), features 8g + 4q + c ------------
+  // ---- epilogue: lane holds, for token (64wt + 32t + r32), features 8g + 4q + c -------------
   // weight tile h: half (h >> 1), rows 64wr + 32(h & 1) .. +31 of that half
 #pragma unroll
-  for (int t = 0; t < 4; ++t) {
-    const int j = 128 * wt + 32 * t + r32;
+  for (int t = 0; t < 2; ++t) {
+    const int j = 64 * wt + 32 * t + r32;
     if (j < m) {
       const size_t orow = (size_t)(row0 + j);
 #pragma unroll
@@ -283,10 +283,10 @@ static hipError_t launch_tiled(int mode, const StreamArgs &a, hipStream_t s) {
   const long n_lin = (long)n_shared * rt_s + n_large_ub * rt_r;
   const long grid = ((n_lin + 31) / 32) * 32;
   if (mode == TMODE_GATE_UP)
-    hipLaunchKernelGGL(expert_tiled_kernel<TMODE_GATE_UP>, dim3((unsigned)grid), dim3(256), TILED_LDS_BYTES, s, a,
+    hipLaunchKernelGGL(expert_tiled_kernel<TMODE_GATE_UP>, dim3((unsigned)grid), dim3(T_THREADS), TILED_LDS_BYTES, s, a,
                        n_shared, rt_s, rt_r);
   else
-    hipLaunchKernelGGL(expert_tiled_kernel<TMODE_DOWN>, dim3((unsigned)grid), dim3(256), TILED_LDS_BYTES, s, a,
+    hipLaunchKernelGGL(expert_tiled_kernel<TMODE_DOWN>, dim3((unsigned)grid), dim3(T_THREADS), TILED_LDS_BYTES, s, a,
                        n_shared, rt_s, rt_r);
   return hipGetLastError();
 }
