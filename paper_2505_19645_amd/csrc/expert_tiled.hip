@@ -13,9 +13,9 @@
 //    and up rows 64wr..64wr+63, or two 64-row groups of w_down) x two 32-token
 //    tiles = 8 accumulator tiles; 131 flops per byte brought into LDS.
 //  * Operands go straight from global memory into the LDS ring with
-//    global_load_lds_dwordx4 (no staging registers, three steps in flight while
-//    one is multiplied); loads are issued and awaited by hand, one s_barrier per
-//    step.  Rows are 64 bytes in LDS, their four 16-byte pieces XOR-swizzled by
+//    global_load_lds_dwordx4 (no staging registers, up to four steps in flight);
+//    loads are issued and awaited by hand, one s_barrier per step.  The MFMA
+//    fragments are double-buffered in registers, so LDS reads run under MFMAs.  Rows are 64 bytes in LDS, their four 16-byte pieces XOR-swizzled by
 //    (row >> 2) & 3: four rows share a 256-byte bank line, and the 16 rows a
 //    quarter-wave reads then fall into 16 different 16-byte bank groups, while
 //    the DMA writes stay linear.
@@ -179,39 +179,83 @@ __global__ __launch_bounds__(T_THREADS) void expert_tiled_kernel(StreamArgs a, i
     for (int i = 0; i < 2; ++i) t_dma16(gb[i] + k, sbase + T_A_BYTES + (uint32_t)(2 * wave + i) * 1024u);
   };
 
-  for (int i = 0; i < T_STAGES - 1 && i < nkb; ++i) issue(i);
+  // Operand fragments of one 16-element half step: 4 weight tiles and 2 token tiles.
   const int key = (r32 >> 2) & 3;
-  for (int kb = 0; kb < nkb; ++kb) {
-    // stage kb has landed when at most the two younger stages' loads are pending
-    const int younger = min(nkb - 1 - kb, T_STAGES - 2);
-    if (younger == 2) t_wait_vm<2 * T_LW>();
+  const char *pa0 = smem + (64 * wr + r32) * T_ROW_BYTES;
+  const char *pb0 = smem + T_A_BYTES + (64 * wt + r32) * T_ROW_BYTES;
+  auto read_half = [&](int kb, int st, u32x4 (&fa)[4], u32x4 (&fb)[2]) __attribute__((always_inline)) {
+    const int so = (kb % T_STAGES) * T_STAGE_BYTES + (((2 * st + q) ^ key) << 4);
+#pragma unroll
+    for (int h = 0; h < 4; ++h)
+      fa[h] = *reinterpret_cast<const u32x4 *>(pa0 + so + ((h >> 1) * 128 + (h & 1) * 32) * T_ROW_BYTES);
+#pragma unroll
+    for (int t = 0; t < 2; ++t) fb[t] = *reinterpret_cast<const u32x4 *>(pb0 + so + t * 32 * T_ROW_BYTES);
+  };
+  auto mfma_half = [&](const u32x4 (&fa)[4], const u32x4 (&fb)[2]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int h = 0; h < 4; ++h)
+#pragma unroll
+      for (int t = 0; t < 2; ++t) acc[h][t] = mfma32(fa[h], fb[t], acc[h][t]);
+  };
+  // stage kb has landed (this wave's part) when at most the `younger` later stages' loads are pending
+  auto wait_stage = [&](int younger) __attribute__((always_inline)) {
+    if (younger >= 3) t_wait_vm<3 * T_LW>();
+    else if (younger == 2) t_wait_vm<2 * T_LW>();
     else if (younger == 1) t_wait_vm<T_LW>();
     else t_wait_vm<0>();
+  };
+
+  int issued = 0;  // stages whose loads have been issued
+  for (; issued < T_STAGES && issued < nkb; ++issued) issue(issued);
+  int kb = 0;
+  // Steady state, whole steps only, no branches inside: the fragments are double-buffered in
+  // registers, so the LDS reads of the next half step are in flight while the MFMAs of the
+  // current one run.  Once every wave holds both halves of stage kb in registers (the
+  // barrier), that stage's slot is free for stage kb + T_STAGES.
+  const int n_main = max(klen / TBK - T_STAGES, 0);
+  if (n_main > 0) {
+    u32x4 fa0[4], fb0[2], fa1[4], fb1[2];
+    t_wait_vm<(T_STAGES - 1) * T_LW>();
+    t_barrier();
+    read_half(0, 0, fa0, fb0);
+    read_half(0, 1, fa1, fb1);
+    for (; kb < n_main; ++kb) {
+      // (the scheduling fences keep the compiler from sinking the reads below the MFMAs)
+      mfma_half(fa0, fb0);
+      __builtin_amdgcn_sched_barrier(0);
+      t_wait_vm<2 * T_LW>();  // this wave's part of stage kb+1 has landed
+      t_barrier();            // ... and everyone's; everyone has stage kb in registers
+      issue(kb + T_STAGES);
+      read_half(kb + 1, 0, fa0, fb0);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_half(fa1, fb1);
+      __builtin_amdgcn_sched_barrier(0);
+      read_half(kb + 1, 1, fa1, fb1);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    issued = n_main + T_STAGES;
+    mfma_half(fa0, fb0);  // stage n_main, already in registers
+    mfma_half(fa1, fb1);
+    kb = n_main + 1;
+  }
+  // The last steps (and short contractions): one barrier per step, fragments read and used
+  // in place, pieces past the end of a ragged last step count as zero.
+  for (; kb < nkb; ++kb) {
+    wait_stage(issued - 1 - kb);
     t_barrier();  // everyone's part of stage kb is in LDS; everyone is done reading stage kb-1
-    if (kb + T_STAGES - 1 < nkb) issue(kb + T_STAGES - 1);  // into the slot of stage kb-1
-    const char *s = smem + (kb % T_STAGES) * T_STAGE_BYTES;
-    // rows of this wave's weight tiles (64wr.. of each half) and token tiles (128wt..)
-    const char *pa = s + (64 * wr + r32) * T_ROW_BYTES;
-    const char *pb = s + T_A_BYTES + (64 * wt + r32) * T_ROW_BYTES;
-    const int kbase = kb * TBK;
-    const bool full = kbase + TBK <= klen;
+    if (issued < nkb && issued <= kb + T_STAGES - 1) {
+      issue(issued);  // into the slot of stage kb-1 or older
+      ++issued;
+    }
 #pragma unroll
     for (int st = 0; st < 2; ++st) {
-      const int off = ((2 * st + q) ^ key) << 4;
       u32x4 fa[4], fb[2];
-#pragma unroll
-      for (int h = 0; h < 4; ++h)
-        fa[h] = *reinterpret_cast<const u32x4 *>(pa + ((h >> 1) * 128 + (h & 1) * 32) * T_ROW_BYTES + off);
-#pragma unroll
-      for (int t = 0; t < 2; ++t) fb[t] = *reinterpret_cast<const u32x4 *>(pb + t * 32 * T_ROW_BYTES + off);
-      if (!full && kbase + (2 * st + q) * 8 >= klen) {  // ragged last step: drop pieces past the end
+      read_half(kb, st, fa, fb);
+      if (kb * TBK + (2 * st + q) * 8 >= klen) {
 #pragma unroll
         for (int t = 0; t < 2; ++t) fb[t] = (u32x4){0u, 0u, 0u, 0u};
       }
-#pragma unroll
-      for (int h = 0; h < 4; ++h)
-#pragma unroll
-        for (int t = 0; t < 2; ++t) acc[h][t] = mfma32(fa[h], fb[t], acc[h][t]);
+      mfma_half(fa, fb);
     }
   }
 
