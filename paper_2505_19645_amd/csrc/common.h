@@ -35,7 +35,13 @@ __device__ __forceinline__ f32x4 mfma16(u32x4 a, u32x4 b, f32x4 c) {
                                                  __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
-__device__ __forceinline__ float silu_f32(float z) { return z / (1.0f + expf(-z)); }
+// silu(z) = z / (1 + e^-z) with the hardware exp2 and reciprocal (each about 1 ulp): a few
+// ulp of fp32 in all, far below the bf16 rounding of the activation that follows.  e^-z
+// overflows to +inf for z < -88 and the result is -0, as it should be.
+__device__ __forceinline__ float silu_f32(float z) {
+  const float e = __builtin_amdgcn_exp2f(z * -1.44269504088896340736f);
+  return z * __builtin_amdgcn_rcpf(1.0f + e);
+}
 
 // ---- launch descriptors (host fills, passed by value) ------------------------
 

@@ -6,53 +6,55 @@
 // into blocks of 256 rows and handled here: a workgroup computes a 256-token x
 // 256-weight-row tile (128 w_gate rows + the same 128 w_up rows with SwiGLU
 // fused, or 256 w_down rows), marching over the contraction dimension in
-// 32-element steps through a four-stage LDS ring, with v_mfma_f32_32x32x16_bf16.
+// 64-element stages through two LDS buffers, with v_mfma_f32_32x32x16_bf16.
 //
-//  * Eight waves (two per SIMD, so one multiplies while the other waits for LDS)
-//    as 2 (row halves) x 4 (token quarters); a wave owns 2 x 2 32-row tiles (gate
+//  * Eight waves (two per SIMD, so one multiplies while the other waits) as
+//    2 (row halves) x 4 (token quarters); a wave owns 2 x 2 32-row tiles (gate
 //    and up rows 64wr..64wr+63, or two 64-row groups of w_down) x two 32-token
 //    tiles = 8 accumulator tiles; 131 flops per byte brought into LDS.
-//  * Operands go straight from global memory into the LDS ring with
-//    global_load_lds_dwordx4 (no staging registers, up to four steps in flight);
-//    loads are issued and awaited by hand, one s_barrier per step.  The MFMA
-//    fragments are double-buffered in registers, so LDS reads run under MFMAs.  Rows are 64 bytes in LDS, their four 16-byte pieces XOR-swizzled by
-//    (row >> 2) & 3: four rows share a 256-byte bank line, and the 16 rows a
-//    quarter-wave reads then fall into 16 different 16-byte bank groups, while
-//    the DMA writes stay linear.
+//  * Operands travel global memory -> registers -> LDS: every lane fetches eight
+//    16-byte pieces of a stage (whole 128-byte lines per row) one stage ahead of
+//    the multiplication and stores them when the other buffer has been read.
+//    (Measured on this chip: the same traffic through global_load_lds tops out at
+//    about two thirds of this path's rate, and 64-byte row pieces at less again.)
+//  * Rows are 128 bytes in LDS, their eight 16-byte pieces XOR-swizzled by
+//    (row >> 1) & 7: two rows share a 256-byte bank line, so the 16 rows a
+//    quarter-wave reads, and the 2 rows x 8 pieces it writes, fall into 16
+//    different 16-byte bank groups.
+//  * The MFMA fragments of a 16-element half step are double-buffered in
+//    registers: the LDS reads of the next half step run under the MFMAs of the
+//    current one; one s_barrier per stage.
 //  * Workgroup ids are remapped so that runs of 4 consecutive tiles (the token blocks
 //    of one expert that share a weight tile) land on the same XCD and meet in its L2.
 //
 // MFMA operand use (32x32x16): lane l = 32*q + r supplies 8 consecutive
-// contraction elements (piece 2*s + q of step s) of weight row r as A and of
+// contraction elements (piece 2*s + q of half step s) of weight row r as A and of
 // token row r as B; it receives, for token r, output features
 // 8*g + 4*q + c (g, c = 0..3) in accumulator register 4*g + c.
+#include <type_traits>
+
 #include "common.h"
 
 #define TBM 256  // token rows per tile
 #define TBN 256  // weight rows per tile (two halves of 128)
-#define TBK 32   // contraction elements per step
-#define T_ROW_BYTES 64
-#define T_A_BYTES (TBN * T_ROW_BYTES)  // 16 KB
-#define T_B_BYTES (TBM * T_ROW_BYTES)  // 16 KB
+#define TBK 64   // contraction elements per stage
+#define T_ROW_BYTES 128
+#define T_A_BYTES (TBN * T_ROW_BYTES)  // 32 KB
+#define T_B_BYTES (TBM * T_ROW_BYTES)  // 32 KB
 #define T_STAGE_BYTES (T_A_BYTES + T_B_BYTES)
-#define T_STAGES 4
-#define T_LW 4  // loads per wave per stage
+#define T_LW 8  // 16-byte pieces per lane per stage
 #define T_THREADS 512
-#define TILED_LDS_BYTES (T_STAGES * T_STAGE_BYTES)
+#define TILED_LDS_BYTES (2 * T_STAGE_BYTES)
 
 enum { TMODE_GATE_UP = 0, TMODE_DOWN = 1 };
 
-__device__ __forceinline__ void t_dma16(const void *g, uint32_t lds_base) {
-  const uint32_t b = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_base);
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-               :: "v"(g), "s"(b) : "memory");
-}
-template <int N>
-__device__ __forceinline__ void t_wait_vm() {
-  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
-}
+// LDS accesses done, then the workgroup barrier; deliberately no vmcnt wait: the global
+// loads of the next stage stay in flight across it.  The lgkmcnt(0) wait is a builtin (not
+// part of the asm) so that the compiler's wait-count bookkeeping knows about it.
 __device__ __forceinline__ void t_barrier() {
-  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0xC07F);  // vmcnt and expcnt unconstrained, lgkmcnt(0)
+  asm volatile("s_barrier" ::: "memory");
 }
 
 __device__ __forceinline__ f32x16 mfma32(u32x4 a, u32x4 b, f32x16 c) {
@@ -64,7 +66,8 @@ template <int MODE>
 __global__ __launch_bounds__(T_THREADS) void expert_tiled_kernel(StreamArgs a, int n_shared_entries,
                                                            int rt_shared, int rt_routed) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wr = wave & 1, wt = wave >> 1;  // wt: 0..3
   const int r32 = lane & 31, q = lane >> 5;
 
@@ -134,29 +137,53 @@ __global__ __launch_bounds__(T_THREADS) void expert_tiled_kernel(StreamArgs a, i
   const int rv1 = (MODE == TMODE_GATE_UP) ? rv0 : max(1, min(128, n_rows - i0 - 128));  // second half
   const bool second_ok = (MODE == TMODE_GATE_UP) || (n_rows - i0 > 128);
 
-  // ---- DMA assignment: one instruction = 16 rows x 64 bytes = 1 KB of LDS -----------------
-  // A: 256 rows = 16 instructions, 2 per wave; B: 256 rows = 16 instructions, 2 per wave.
-  // Lane l covers row 16j + (l >> 2) at LDS position (l & 3) and fetches piece
-  // pos ^ ((row >> 2) & 3) = pos ^ ((l >> 4) & 3).
-  const int sub = lane >> 2, pos = lane & 3;
-  const int mypiece = pos ^ ((sub >> 2) & 3);
-  const uint16_t *ga[2];
-  const uint16_t *gb[2];
+  // ---- loader: a stage is 512 rows x 128 bytes; wave w fetches rows 64(w&3).. of the weight
+  // rows (w < 4) or of the token rows (w >= 4), instruction i rows 8i..8i+7, lane l row
+  // (l >> 3), piece (l & 7)
+  const int lrow = lane >> 3, piece = lane & 7;
+  const bool load_b = wave >= 4;
+  const int lw = wave & 3;
+  const char *wbase;    // wave-uniform: first row this wave may touch, at the k origin
+  uint32_t off[T_LW];   // this lane's rows (clamped into the valid rows), in bytes from wbase
+  if (!load_b) {
+    const bool second = lw >= 2;
+    const uint16_t *base = (second && second_ok) ? A1 : A0;
+    const int rv = second ? rv1 : rv0;
+    wbase = reinterpret_cast<const char *>(base + (size_t)i0 * a_stride);
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int row = 16 * (2 * wave + i) + sub;  // 0..255
-    const int hrow = row & 127;
-    const uint16_t *base = (row >> 7) ? ((second_ok) ? A1 : A0) : A0;
-    const int rv = (row >> 7) ? rv1 : rv0;
-    ga[i] = base + (size_t)(i0 + min(hrow, rv - 1)) * a_stride;
-  }
+    for (int i = 0; i < T_LW; ++i) {
+      const int hrow = 64 * (lw & 1) + 8 * i + lrow;
+      off[i] = (uint32_t)min(hrow, rv - 1) * (uint32_t)(a_stride * 2);
+    }
+  } else {
+    wbase = reinterpret_cast<const char *>(use_map ? B : B + (size_t)row0 * b_stride);
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int row = 16 * (2 * wave + i) + sub;  // 0..255
-    int tr = row0 + min(row, m - 1);
-    if (use_map) tr = a.row_token[tr];
-    gb[i] = B + (size_t)tr * b_stride;
+    for (int i = 0; i < T_LW; ++i) {
+      const int row = min(64 * lw + 8 * i + lrow, m - 1);
+      const int tr = use_map ? a.row_token[row0 + row] : row;
+      off[i] = (uint32_t)tr * (uint32_t)(b_stride * 2);
+    }
   }
+  // this lane's eight LDS store positions (stage buffer 0)
+  const int srow0 = (load_b ? TBN : 0) + 64 * lw + lrow;
+  auto load_stage = [&](int s, u32x4 (&pre)[T_LW]) __attribute__((always_inline)) {
+    // a piece past the end of the rows is pulled back inside (it is zeroed before the store)
+    const uint32_t kk = 2u * (uint32_t)min(s * TBK + piece * 8, klen - 8);
+#pragma unroll
+    for (int i = 0; i < T_LW; ++i) pre[i] = *reinterpret_cast<const u32x4 *>(wbase + (off[i] + kk));
+  };
+  auto store_stage = [&](int s, int buf, u32x4 (&pre)[T_LW], bool ragged) __attribute__((always_inline)) {
+    if (ragged && s * TBK + piece * 8 >= klen) {
+#pragma unroll
+      for (int i = 0; i < T_LW; ++i) pre[i] = (u32x4){0u, 0u, 0u, 0u};
+    }
+#pragma unroll
+    for (int i = 0; i < T_LW; ++i) {
+      const int row = srow0 + 8 * i;
+      *reinterpret_cast<u32x4 *>(smem + buf * T_STAGE_BYTES + row * T_ROW_BYTES + ((piece ^ ((row >> 1) & 7)) << 4)) =
+          pre[i];
+    }
+  };
 
   f32x16 acc[4][2];  // [weight tile: 2 of the first half, 2 of the second][token tile]
 #pragma unroll
@@ -166,25 +193,12 @@ __global__ __launch_bounds__(T_THREADS) void expert_tiled_kernel(StreamArgs a, i
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[h][t][v] = 0.f;
 
-  const int nkb = (klen + TBK - 1) / TBK;
-  const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
-  // exactly T_LW loads per wave; a piece past the end of the rows is pulled back inside
-  // (its products are masked below)
-  auto issue = [&](int kb) __attribute__((always_inline)) {
-    const int k = min(kb * TBK + mypiece * 8, klen - 8);
-    const uint32_t sbase = lds0 + (uint32_t)(kb % T_STAGES) * T_STAGE_BYTES;
-#pragma unroll
-    for (int i = 0; i < 2; ++i) t_dma16(ga[i] + k, sbase + (uint32_t)(2 * wave + i) * 1024u);
-#pragma unroll
-    for (int i = 0; i < 2; ++i) t_dma16(gb[i] + k, sbase + T_A_BYTES + (uint32_t)(2 * wave + i) * 1024u);
-  };
-
   // Operand fragments of one 16-element half step: 4 weight tiles and 2 token tiles.
-  const int key = (r32 >> 2) & 3;
+  const int key = (r32 >> 1) & 7;
   const char *pa0 = smem + (64 * wr + r32) * T_ROW_BYTES;
   const char *pb0 = smem + T_A_BYTES + (64 * wt + r32) * T_ROW_BYTES;
-  auto read_half = [&](int kb, int st, u32x4 (&fa)[4], u32x4 (&fb)[2]) __attribute__((always_inline)) {
-    const int so = (kb % T_STAGES) * T_STAGE_BYTES + (((2 * st + q) ^ key) << 4);
+  auto read_half = [&](int buf, int hs, u32x4 (&fa)[4], u32x4 (&fb)[2]) __attribute__((always_inline)) {
+    const int so = buf * T_STAGE_BYTES + (((2 * hs + q) ^ key) << 4);
 #pragma unroll
     for (int h = 0; h < 4; ++h)
       fa[h] = *reinterpret_cast<const u32x4 *>(pa0 + so + ((h >> 1) * 128 + (h & 1) * 32) * T_ROW_BYTES);
@@ -197,66 +211,53 @@ __global__ __launch_bounds__(T_THREADS) void expert_tiled_kernel(StreamArgs a, i
 #pragma unroll
       for (int t = 0; t < 2; ++t) acc[h][t] = mfma32(fa[h], fb[t], acc[h][t]);
   };
-  // stage kb has landed (this wave's part) when at most the `younger` later stages' loads are pending
-  auto wait_stage = [&](int younger) __attribute__((always_inline)) {
-    if (younger >= 3) t_wait_vm<3 * T_LW>();
-    else if (younger == 2) t_wait_vm<2 * T_LW>();
-    else if (younger == 1) t_wait_vm<T_LW>();
-    else t_wait_vm<0>();
-  };
 
-  int issued = 0;  // stages whose loads have been issued
-  for (; issued < T_STAGES && issued < nkb; ++issued) issue(issued);
-  int kb = 0;
-  // Steady state, whole steps only, no branches inside: the fragments are double-buffered in
-  // registers, so the LDS reads of the next half step are in flight while the MFMAs of the
-  // current one run.  Once every wave holds both halves of stage kb in registers (the
-  // barrier), that stage's slot is free for stage kb + T_STAGES.
-  const int n_main = max(klen / TBK - T_STAGES, 0);
-  if (n_main > 0) {
-    u32x4 fa0[4], fb0[2], fa1[4], fb1[2];
-    t_wait_vm<(T_STAGES - 1) * T_LW>();
-    t_barrier();
-    read_half(0, 0, fa0, fb0);
-    read_half(0, 1, fa1, fb1);
-    for (; kb < n_main; ++kb) {
-      // (the scheduling fences keep the compiler from sinking the reads below the MFMAs)
-      mfma_half(fa0, fb0);
-      __builtin_amdgcn_sched_barrier(0);
-      t_wait_vm<2 * T_LW>();  // this wave's part of stage kb+1 has landed
-      t_barrier();            // ... and everyone's; everyone has stage kb in registers
-      issue(kb + T_STAGES);
-      read_half(kb + 1, 0, fa0, fb0);
-      __builtin_amdgcn_sched_barrier(0);
-      mfma_half(fa1, fb1);
-      __builtin_amdgcn_sched_barrier(0);
-      read_half(kb + 1, 1, fa1, fb1);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    issued = n_main + T_STAGES;
-    mfma_half(fa0, fb0);  // stage n_main, already in registers
+  const int nkb = (klen + TBK - 1) / TBK;
+  const bool ragged = (klen % TBK) != 0;  // then the last stage is zero-padded
+  u32x4 pre[T_LW], fa0[4], fb0[2], fa1[4], fb1[2];
+  load_stage(0, pre);
+  store_stage(0, 0, pre, ragged && nkb == 1);
+  if (nkb > 1) load_stage(1, pre);
+  t_barrier();
+  read_half(0, 0, fa0, fb0);
+  read_half(0, 1, fa1, fb1);
+  // One stage: four half steps from buffer kb & 1.  Before the third half step's MFMAs
+  // retire, the prefetched registers (stage kb+1) go to the other buffer, whose last
+  // readers passed the previous barrier, and the loads of stage kb+2 are issued; after the
+  // barrier the first fragments of stage kb+1 are read under the last MFMAs of stage kb.
+  // (The scheduling fences keep the compiler from sinking the reads below the MFMAs.)
+  auto step = [&](int kb, auto has_next, auto has_next2) __attribute__((always_inline)) {
+    const int buf = kb & 1;
+    mfma_half(fa0, fb0);
+    __builtin_amdgcn_sched_barrier(0);
+    read_half(buf, 2, fa0, fb0);
+    __builtin_amdgcn_sched_barrier(0);
     mfma_half(fa1, fb1);
-    kb = n_main + 1;
-  }
-  // The last steps (and short contractions): one barrier per step, fragments read and used
-  // in place, pieces past the end of a ragged last step count as zero.
-  for (; kb < nkb; ++kb) {
-    wait_stage(issued - 1 - kb);
-    t_barrier();  // everyone's part of stage kb is in LDS; everyone is done reading stage kb-1
-    if (issued < nkb && issued <= kb + T_STAGES - 1) {
-      issue(issued);  // into the slot of stage kb-1 or older
-      ++issued;
+    __builtin_amdgcn_sched_barrier(0);
+    read_half(buf, 3, fa1, fb1);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_half(fa0, fb0);
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (decltype(has_next)::value) {
+      store_stage(kb + 1, buf ^ 1, pre, ragged && !decltype(has_next2)::value);
+      if constexpr (decltype(has_next2)::value) load_stage(kb + 2, pre);
+      t_barrier();  // stage kb+1 is in LDS for everyone; everyone has stage kb in registers
+      read_half(buf ^ 1, 0, fa0, fb0);
     }
-#pragma unroll
-    for (int st = 0; st < 2; ++st) {
-      u32x4 fa[4], fb[2];
-      read_half(kb, st, fa, fb);
-      if (kb * TBK + (2 * st + q) * 8 >= klen) {
-#pragma unroll
-        for (int t = 0; t < 2; ++t) fb[t] = (u32x4){0u, 0u, 0u, 0u};
-      }
-      mfma_half(fa, fb);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_half(fa1, fb1);
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (decltype(has_next)::value) read_half(buf ^ 1, 1, fa1, fb1);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  {
+    int kb = 0;
+    for (; kb + 2 < nkb; ++kb) step(kb, std::true_type{}, std::true_type{});
+    if (kb + 1 < nkb) {
+      step(kb, std::true_type{}, std::false_type{});
+      ++kb;
     }
+    step(kb, std::false_type{}, std::false_type{});
   }
 
   // ---- epilogue: lane holds, for token (64wt + 32t + r32), features 8g + 4q + c -------------
@@ -309,6 +310,8 @@ static hipError_t launch_tiled(int mode, const StreamArgs &a, hipStream_t s) {
     if (e != hipSuccess) return e;
     attr_set[mode] = true;
   }
+  // row offsets are kept as 32-bit byte counts inside the kernel
+  if ((unsigned long long)a.T * (unsigned long long)a.d * 2ull >= (1ull << 32)) return hipErrorInvalidValue;
   const int parts = (mode == TMODE_DOWN && a.S > 0) ? (a.S + a.part_k - 1) / a.part_k : 1;
   const int n_shared = (a.S > 0 && a.T > PLAN_BIG_MAX_ROWS) ? ((a.T + TBM - 1) / TBM) * parts : 0;
   // experts with more than 128 rows: at most T*K/129 of them, each with ceil(m/256) blocks
