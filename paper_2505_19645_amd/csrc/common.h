@@ -92,8 +92,11 @@ hipError_t launch_topk_permute(const double *logits, int T, int E, int K, int sc
                                int32_t *n_active, int32_t *row_token, int32_t *plan, hipStream_t s);
 hipError_t launch_gate_up(const StreamArgs &a, hipStream_t s);
 hipError_t launch_down(const StreamArgs &a, hipStream_t s);
-hipError_t launch_gate_up_tiled(const StreamArgs &a, hipStream_t s);
-hipError_t launch_down_tiled(const StreamArgs &a, hipStream_t s);
+// The tiled kernels are persistent and cut the work into equal shares; a tile cut by a
+// share boundary is completed through `partials` (tiled_partials_bytes() bytes).
+size_t tiled_partials_bytes();
+hipError_t launch_gate_up_tiled(const StreamArgs &a, float *partials, hipStream_t s);
+hipError_t launch_down_tiled(const StreamArgs &a, float *partials, hipStream_t s);
 hipError_t launch_combine(const float *y, const float *ys, int n_parts, const float *w,
                           const float *gate, const int32_t *inv, int T, int K, int d, uint16_t *out,
                           float *out_f32, hipStream_t s);

@@ -24,8 +24,16 @@
 //  * The MFMA fragments of a 16-element half step are double-buffered in
 //    registers: the LDS reads of the next half step run under the MFMAs of the
 //    current one; one s_barrier per stage.
-//  * Workgroup ids are remapped so that runs of 4 consecutive tiles (the token blocks
-//    of one expert that share a weight tile) land on the same XCD and meet in its L2.
+//  * Persistent launch, one workgroup per CU.  Four workgroups on one XCD form a team
+//    that walks runs of 4 consecutive tiles in lockstep (the token blocks of one expert
+//    that share a weight tile meet in that XCD's L2).  Normally whole runs are dealt
+//    round-robin.  When that would leave the busiest team more than 15 % above the mean,
+//    the list of (run, stage) units is instead cut into equal contiguous shares, one per
+//    team, so every CU gets the same number of stages whatever the tile count.  A tile
+//    that straddles a cut is not finished here:
+//    each of its workgroups writes its partial accumulators, and a small second kernel
+//    adds the partials of every cut tile in k order (the same order on every run) and
+//    runs the epilogue.  No atomics, no fences, nobody waits for anybody.
 //
 // MFMA operand use (32x32x16): lane l = 32*q + r supplies 8 consecutive
 // contraction elements (piece 2*s + q of half step s) of weight row r as A and of
@@ -62,34 +70,68 @@ __device__ __forceinline__ f32x16 mfma32(u32x4 a, u32x4 b, f32x16 c) {
                                                  c, 0, 0, 0);
 }
 
-template <int MODE>
-__global__ __launch_bounds__(T_THREADS) void expert_tiled_kernel(StreamArgs a, int n_shared_entries,
-                                                           int rt_shared, int rt_routed) {
-  extern __shared__ __attribute__((aligned(1024))) char smem[];
+// Launch-wide schedule, filled by the host.
+struct TiledSched {
+  int n_shared_entries;   // token blocks (x k-parts for the down projection) of the shared expert
+  int rt_shared, rt_routed;  // row tiles per shared / routed entry
+  int nkb_s, nkb_r;       // stages per shared / routed tile (upper bound over the region)
+  float *partials;        // [2 * workgroups of the main kernel] slots of T_THREADS * 128 floats
+  int n_teams;            // teams of the main kernel (its grid / 4)
+};
+#define T_SLOT_FLOATS (T_THREADS * 128)
+
+// The schedule both kernels derive from the plan: units of (run, stage), two regions.
+struct TiledWork {
+  int n_large, n_sh_tiles, n_r_tiles;
+  long runs_s, runs;  // runs of the shared region, of both
+  long W_s, W;        // units of the shared region, of both
+  int nkb_s, nkb_r, n_teams;
+  bool cut;           // shares end inside runs (else on run boundaries)
+};
+__device__ __forceinline__ TiledWork tiled_work(const StreamArgs &a, const TiledSched &sc) {
+  // Tiles are numbered densely per region: the shared expert's first (row tile major, its
+  // token blocks adjacent), then the routed experts' (row tile major over the actual number
+  // of large entries, blocks of one expert adjacent).  A run is 4 consecutive tiles.
+  TiledWork w;
+  w.n_large = a.plan[2];
+  w.n_sh_tiles = sc.n_shared_entries * sc.rt_shared;
+  w.n_r_tiles = w.n_large * sc.rt_routed;
+  w.runs_s = (w.n_sh_tiles + 3) / 4;
+  w.runs = w.runs_s + (w.n_r_tiles + 3) / 4;
+  w.nkb_s = sc.nkb_s;
+  w.nkb_r = sc.nkb_r;
+  w.n_teams = sc.n_teams;
+  w.W_s = w.runs_s * sc.nkb_s;
+  w.W = w.W_s + (w.runs - w.runs_s) * sc.nkb_r;
+  // Cutting runs costs a round trip of partial sums through memory and a second epilogue
+  // pass: only worth it when whole runs would leave the busiest team more than 15 % above
+  // the mean, and pointless when there are not even as many runs as teams.
+  const long per_team = (w.runs + w.n_teams - 1) / w.n_teams;
+  w.cut = w.runs > w.n_teams && per_team * w.n_teams * 100 > w.runs * 115;
+  return w;
+}
+// when runs are cut: first unit of team g's share (g = n_teams: one past the end)
+__device__ __forceinline__ long tiled_team_start(const TiledWork &w, int g) { return (w.W * g) / w.n_teams; }
+
+// One piece: stages [st0, st1) of one tile (stage numbers in units of the region's nkb_reg).
+// FIXUP: no multiplication; the accumulators are the sum of the tile's stored pieces.
+template <int MODE, bool FIXUP>
+__device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSched &sc, char *smem, bool shared_region,
+                                            int tile, int st0, int st1, int nkb_reg, long run_base, int slot,
+                                            int team_member, const TiledWork &w) {
+  const int n_large = w.n_large;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wr = wave & 1, wt = wave >> 1;  // wt: 0..3
   const int r32 = lane & 31, q = lane >> 5;
-
-  // ---- which tile ---------------------------------------------------------------------
-  // The tiles with work are numbered densely: first the shared expert's (row tile major,
-  // its token blocks adjacent), then the routed experts' (row tile major over the actual
-  // number of large entries, blocks of one expert adjacent).  Workgroup ids are dealt to
-  // the 8 XCDs round-robin; the remap hands each XCD runs of 4 consecutive tile numbers
-  // (blocks that share a weight tile) and deals those runs round-robin.
-  const int xcd = blockIdx.x % 8, g = blockIdx.x / 8;
-  const int lin = ((g / 4) * 8 + xcd) * 4 + (g % 4);
-  const int n_large = a.plan[2];
-  const int n_sh_tiles = n_shared_entries * rt_shared;
+  const int n_shared_entries = sc.n_shared_entries;
   int rt, entry;
-  if (lin < n_sh_tiles) {
-    rt = lin / n_shared_entries;
-    entry = lin % n_shared_entries;
+  if (shared_region) {
+    rt = tile / n_shared_entries;
+    entry = tile % n_shared_entries;
   } else {
-    const int lr = lin - n_sh_tiles;
-    if (n_large == 0 || lr >= n_large * rt_routed) return;
-    rt = lr / n_large;
-    entry = n_shared_entries + lr % n_large;
+    rt = tile / n_large;
+    entry = n_shared_entries + tile % n_large;
   }
 
   const int parts = (MODE == TMODE_DOWN && a.S > 0) ? (a.S + a.part_k - 1) / a.part_k : 1;
@@ -132,7 +174,6 @@ __global__ __launch_bounds__(T_THREADS) void expert_tiled_kernel(StreamArgs a, i
   // first output feature of this tile; gate/up: 128 features (rows i0.. of both matrices),
   // down: 256 features (rows i0.. and i0+128..)
   const int i0 = (MODE == TMODE_GATE_UP) ? rt * 128 : rt * 256;
-  if (i0 >= n_rows) return;
   const int rv0 = min(128, n_rows - i0);                                               // valid rows, first half
   const int rv1 = (MODE == TMODE_GATE_UP) ? rv0 : max(1, min(128, n_rows - i0 - 128));  // second half
   const bool second_ok = (MODE == TMODE_GATE_UP) || (n_rows - i0 > 128);
@@ -212,15 +253,10 @@ __global__ __launch_bounds__(T_THREADS) void expert_tiled_kernel(StreamArgs a, i
       for (int t = 0; t < 2; ++t) acc[h][t] = mfma32(fa[h], fb[t], acc[h][t]);
   };
 
-  const int nkb = (klen + TBK - 1) / TBK;
-  const bool ragged = (klen % TBK) != 0;  // then the last stage is zero-padded
+  const int nkb = (klen + TBK - 1) / TBK;          // this tile's own stage count (<= nkb_reg)
+  const int s0 = min(st0, nkb), s1 = min(st1, nkb);  // the part of the piece that exists
+  const bool ragged = (klen % TBK) != 0 && s1 == nkb;  // then the piece's last stage is zero-padded
   u32x4 pre[T_LW], fa0[4], fb0[2], fa1[4], fb1[2];
-  load_stage(0, pre);
-  store_stage(0, 0, pre, ragged && nkb == 1);
-  if (nkb > 1) load_stage(1, pre);
-  t_barrier();
-  read_half(0, 0, fa0, fb0);
-  read_half(0, 1, fa1, fb1);
   // One stage: four half steps from buffer kb & 1.  Before the third half step's MFMAs
   // retire, the prefetched registers (stage kb+1) go to the other buffer, whose last
   // readers passed the previous barrier, and the loads of stage kb+2 are issued; after the
@@ -250,14 +286,65 @@ __global__ __launch_bounds__(T_THREADS) void expert_tiled_kernel(StreamArgs a, i
     if constexpr (decltype(has_next)::value) read_half(buf ^ 1, 1, fa1, fb1);
     __builtin_amdgcn_sched_barrier(0);
   };
-  {
-    int kb = 0;
-    for (; kb + 2 < nkb; ++kb) step(kb, std::true_type{}, std::true_type{});
-    if (kb + 1 < nkb) {
+  if (!FIXUP && s0 < s1) {
+    load_stage(s0, pre);
+    t_barrier();  // everyone is done with the LDS of the previous piece
+    store_stage(s0, s0 & 1, pre, ragged && s0 + 1 == s1);
+    if (s0 + 1 < s1) load_stage(s0 + 1, pre);
+    t_barrier();
+    read_half(s0 & 1, 0, fa0, fb0);
+    read_half(s0 & 1, 1, fa1, fb1);
+    int kb = s0;
+    for (; kb + 2 < s1; ++kb) step(kb, std::true_type{}, std::true_type{});
+    if (kb + 1 < s1) {
       step(kb, std::true_type{}, std::false_type{});
       ++kb;
     }
     step(kb, std::false_type{}, std::false_type{});
+  }
+
+  // ---- a tile cut by the schedule: its pieces meet in memory, the second kernel finishes it --
+  if (!FIXUP && !(st0 == 0 && st1 == nkb_reg)) {
+    f32x4 *mine = reinterpret_cast<f32x4 *>(sc.partials + (size_t)slot * T_SLOT_FLOATS);
+#pragma unroll
+    for (int h = 0; h < 4; ++h)
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const f32x16 &v = acc[h][t];
+          mine[((h * 2 + t) * 4 + g) * T_THREADS + tid] = (f32x4){v[4 * g], v[4 * g + 1], v[4 * g + 2], v[4 * g + 3]};
+        }
+    return;
+  }
+  if (FIXUP) {
+    // contributors: the teams whose shares meet this run's units, in k order
+    const int n_teams = w.n_teams;
+    auto team_start = [&](int g) -> long { return tiled_team_start(w, g); };
+    auto team_of = [&](long u) -> int {
+      int g = (int)min((long)n_teams - 1, (u * n_teams) / w.W);
+      while (g + 1 < n_teams && team_start(g + 1) <= u) ++g;
+      while (g > 0 && team_start(g) > u) --g;
+      return g;
+    };
+    const int g_lo = team_of(run_base), g_hi = team_of(run_base + nkb_reg - 1);
+    for (int gg = g_lo; gg <= g_hi; ++gg) {
+      const long ts = team_start(gg);
+      if (ts == team_start(gg + 1)) continue;  // an empty share
+      const int wg = ((gg / 8) * 4 + team_member) * 8 + (gg % 8);
+      const int sl = 2 * wg + (ts >= run_base ? 0 : 1);  // its first piece, or its last
+      const f32x4 *theirs = reinterpret_cast<const f32x4 *>(sc.partials + (size_t)sl * T_SLOT_FLOATS);
+#pragma unroll
+      for (int h = 0; h < 4; ++h)
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const f32x4 p = theirs[((h * 2 + t) * 4 + g) * T_THREADS + tid];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc[h][t][4 * g + c] += p[c];
+          }
+    }
   }
 
   // ---- epilogue: lane holds, for token (64wt + 32t + r32), features 8g + 4q + c -------------
@@ -301,7 +388,81 @@ __global__ __launch_bounds__(T_THREADS) void expert_tiled_kernel(StreamArgs a, i
   }
 }
 
-static hipError_t launch_tiled(int mode, const StreamArgs &a, hipStream_t s) {
+template <int MODE>
+__global__ __launch_bounds__(T_THREADS) void expert_tiled_kernel(StreamArgs a, TiledSched sc) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  // Workgroup ids are dealt to the 8 XCDs round-robin: team g lives on XCD g % 8.
+  const int xcd = blockIdx.x % 8, j = blockIdx.x / 8;
+  const int team = (j / 4) * 8 + xcd, member = j % 4;
+  const TiledWork w = tiled_work(a, sc);
+  if (w.W == 0) return;
+  if (!w.cut) {
+    // whole runs, dealt round-robin: at any time the chip works on consecutive runs, whose
+    // tiles share token blocks and weight tiles in the caches
+    for (long run = team; run < w.runs; run += w.n_teams) {
+      const bool shared_region = run < w.runs_s;
+      const int nkb_reg = shared_region ? sc.nkb_s : sc.nkb_r;
+      const long lrun = shared_region ? run : run - w.runs_s;
+      const int tile = (int)(4 * lrun + member);
+      if (tile < (shared_region ? w.n_sh_tiles : w.n_r_tiles))
+        tiled_piece<MODE, false>(a, sc, smem, shared_region, tile, 0, nkb_reg, nkb_reg, 0, 0, member, w);
+    }
+    return;
+  }
+  long u = tiled_team_start(w, team);
+  const long u_end = tiled_team_start(w, team + 1);
+  int piece = 0;
+  while (u < u_end) {
+    const bool shared_region = u < w.W_s;
+    const int nkb_reg = shared_region ? sc.nkb_s : sc.nkb_r;
+    const long ur = shared_region ? u : u - w.W_s;
+    const long run = ur / nkb_reg;
+    const int st0 = (int)(ur % nkb_reg);
+    const int st1 = (int)min((long)nkb_reg, st0 + (u_end - u));
+    const int tile = (int)(4 * run + member);
+    if (tile < (shared_region ? w.n_sh_tiles : w.n_r_tiles))
+      tiled_piece<MODE, false>(a, sc, smem, shared_region, tile, st0, st1, nkb_reg, u - st0,
+                               2 * (int)blockIdx.x + (piece == 0 ? 0 : 1), member, w);
+    u += st1 - st0;
+    ++piece;
+  }
+}
+
+// Finishes the tiles the main kernel's share boundaries cut.  Workgroup (g, member): if the
+// boundary between teams g and g+1 is the first one inside its run, sum that run's pieces.
+template <int MODE>
+__global__ __launch_bounds__(T_THREADS) void expert_tiled_fixup_kernel(StreamArgs a, TiledSched sc) {
+  const int g = blockIdx.x / 4, member = blockIdx.x % 4;
+  const TiledWork w = tiled_work(a, sc);
+  if (w.W == 0 || !w.cut || g + 1 >= w.n_teams) return;
+  const long b = tiled_team_start(w, g + 1);  // first unit of team g+1
+  if (b >= w.W) return;
+  const bool shared_region = b < w.W_s;
+  const int nkb_reg = shared_region ? sc.nkb_s : sc.nkb_r;
+  const long ur = shared_region ? b : b - w.W_s;
+  const int st = (int)(ur % nkb_reg);
+  if (st == 0) return;  // the boundary falls between two runs: nothing is cut
+  const long run_base = b - st;
+  if (tiled_team_start(w, g) > run_base) return;  // an earlier boundary inside this run does the work
+  const int tile = (int)(4 * (ur / nkb_reg) + member);
+  if (tile >= (shared_region ? w.n_sh_tiles : w.n_r_tiles)) return;
+  tiled_piece<MODE, true>(a, sc, nullptr, shared_region, tile, 0, nkb_reg, nkb_reg, run_base, 0, member, w);
+}
+
+// Workspace the tiled kernels need beyond the layer's own buffers.
+static int tiled_grid() {
+  static int grid = 0;
+  if (grid == 0) {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 32)
+      cus = 32;
+    grid = (cus / 32) * 32;  // whole teams of 4 on each of the 8 XCDs
+  }
+  return grid;
+}
+size_t tiled_partials_bytes() { return (size_t)2 * tiled_grid() * T_SLOT_FLOATS * sizeof(float); }
+static hipError_t launch_tiled(int mode, const StreamArgs &a, float *partials, hipStream_t s) {
   static bool attr_set[2] = {false, false};
   const void *fn = mode == TMODE_GATE_UP ? reinterpret_cast<const void *>(expert_tiled_kernel<TMODE_GATE_UP>)
                                          : reinterpret_cast<const void *>(expert_tiled_kernel<TMODE_DOWN>);
@@ -312,31 +473,35 @@ static hipError_t launch_tiled(int mode, const StreamArgs &a, hipStream_t s) {
   }
   // row offsets are kept as 32-bit byte counts inside the kernel
   if ((unsigned long long)a.T * (unsigned long long)a.d * 2ull >= (1ull << 32)) return hipErrorInvalidValue;
+  if (a.T <= PLAN_BIG_MAX_ROWS) return hipSuccess;
   const int parts = (mode == TMODE_DOWN && a.S > 0) ? (a.S + a.part_k - 1) / a.part_k : 1;
-  const int n_shared = (a.S > 0 && a.T > PLAN_BIG_MAX_ROWS) ? ((a.T + TBM - 1) / TBM) * parts : 0;
-  // experts with more than 128 rows: at most T*K/129 of them, each with ceil(m/256) blocks
-  const long tk = (long)a.T * a.K;
-  long n_large_ub = tk / (PLAN_BIG_MAX_ROWS + 1);
-  if (n_large_ub > a.E) n_large_ub = a.E;
-  n_large_ub += tk / TBM;
-  if (n_shared + n_large_ub == 0) return hipSuccess;
-  int rt_s, rt_r;
+  TiledSched sc;
+  sc.n_shared_entries = a.S > 0 ? ((a.T + TBM - 1) / TBM) * parts : 0;
   if (mode == TMODE_GATE_UP) {
-    rt_s = (a.S + 127) / 128;
-    rt_r = (a.I + 127) / 128;
+    sc.rt_shared = (a.S + 127) / 128;
+    sc.rt_routed = (a.I + 127) / 128;
+    sc.nkb_s = sc.nkb_r = (a.d + TBK - 1) / TBK;
   } else {
-    rt_s = rt_r = (a.d + 255) / 256;
+    sc.rt_shared = sc.rt_routed = (a.d + 255) / 256;
+    sc.nkb_s = a.S > 0 ? ((a.S < a.part_k ? a.S : a.part_k) + TBK - 1) / TBK : 1;
+    sc.nkb_r = (a.I + TBK - 1) / TBK;
   }
-  const long n_lin = (long)n_shared * rt_s + n_large_ub * rt_r;
-  const long grid = ((n_lin + 31) / 32) * 32;
-  if (mode == TMODE_GATE_UP)
-    hipLaunchKernelGGL(expert_tiled_kernel<TMODE_GATE_UP>, dim3((unsigned)grid), dim3(T_THREADS), TILED_LDS_BYTES, s, a,
-                       n_shared, rt_s, rt_r);
-  else
-    hipLaunchKernelGGL(expert_tiled_kernel<TMODE_DOWN>, dim3((unsigned)grid), dim3(T_THREADS), TILED_LDS_BYTES, s, a,
-                       n_shared, rt_s, rt_r);
+  sc.partials = partials;
+  const unsigned grid = (unsigned)tiled_grid();
+  sc.n_teams = (int)grid / 4;
+  if (mode == TMODE_GATE_UP) {
+    hipLaunchKernelGGL(expert_tiled_kernel<TMODE_GATE_UP>, dim3(grid), dim3(T_THREADS), TILED_LDS_BYTES, s, a, sc);
+    hipLaunchKernelGGL(expert_tiled_fixup_kernel<TMODE_GATE_UP>, dim3(grid), dim3(T_THREADS), 0, s, a, sc);
+  } else {
+    hipLaunchKernelGGL(expert_tiled_kernel<TMODE_DOWN>, dim3(grid), dim3(T_THREADS), TILED_LDS_BYTES, s, a, sc);
+    hipLaunchKernelGGL(expert_tiled_fixup_kernel<TMODE_DOWN>, dim3(grid), dim3(T_THREADS), 0, s, a, sc);
+  }
   return hipGetLastError();
 }
 
-hipError_t launch_gate_up_tiled(const StreamArgs &a, hipStream_t s) { return launch_tiled(TMODE_GATE_UP, a, s); }
-hipError_t launch_down_tiled(const StreamArgs &a, hipStream_t s) { return launch_tiled(TMODE_DOWN, a, s); }
+hipError_t launch_gate_up_tiled(const StreamArgs &a, float *partials, hipStream_t s) {
+  return launch_tiled(TMODE_GATE_UP, a, partials, s);
+}
+hipError_t launch_down_tiled(const StreamArgs &a, float *partials, hipStream_t s) {
+  return launch_tiled(TMODE_DOWN, a, partials, s);
+}

@@ -46,6 +46,7 @@ struct Workspace {
   uint16_t *hs;    // [T, S]   bf16
   float *y;        // [T*K, d] f32
   float *ys;       // [parts, T, d] f32
+  float *tiled_partials;     // partial accumulator tiles of the MFMA-tiled kernels (T > 128 only)
   int32_t part_k, parts;
   size_t bytes;
 };
@@ -84,6 +85,7 @@ Workspace carve(const moesd_layer_desc *c, int64_t T, char *base) {
   ws.hs = (uint16_t *)take(sizeof(uint16_t) * T * S);
   ws.y = (float *)take(sizeof(float) * T * K * d);
   ws.ys = (float *)take(sizeof(float) * ws.parts * T * d);
+  ws.tiled_partials = (float *)take(T > PLAN_BIG_MAX_ROWS ? tiled_partials_bytes() : 0);
   ws.bytes = off;
   return ws;
 }
@@ -233,10 +235,12 @@ int32_t moesd_moe_forward_staged(const moesd_layer_desc *desc, const moesd_weigh
   a.T = T;
   // experts with at most 128 rows stream; the others (possible only if T > 128) are tiled
   MOESD_TRY(launch_gate_up(a, s))
-  if (T > PLAN_BIG_MAX_ROWS) { MOESD_TRY(launch_gate_up_tiled(a, s)) }
+  if (T > PLAN_BIG_MAX_ROWS) {
+    MOESD_TRY(launch_gate_up_tiled(a, ws.tiled_partials, s))
+  }
   MOESD_EVENT(2)
   MOESD_TRY(launch_down(a, s))
-  if (T > PLAN_BIG_MAX_ROWS) { MOESD_TRY(launch_down_tiled(a, s)) }
+  if (T > PLAN_BIG_MAX_ROWS) { MOESD_TRY(launch_down_tiled(a, ws.tiled_partials, s)) }
   MOESD_EVENT(3)
   MOESD_TRY(launch_combine(ws.y, ws.ys, ws.parts, w, ws.gate, iv, T, desc->top_k, desc->d,
                            (uint16_t *)out, out_f32, s))

@@ -78,6 +78,20 @@ def test_many_rows_per_expert(gpu, oracle, shape, T):
     assert got["counts"].max() > 64
 
 
+@pytest.mark.parametrize("shape,T", [
+    # many row tiles and few stages: the persistent schedule cuts gate/up tiles (routed and shared region)
+    (LayerShape("cut-gate-up", d=192, E=1, top_k=1, inter=12800, shared_inter=6400, seed=35), 520),
+    # many token blocks x row tiles of the down projection: cuts there
+    (LayerShape("cut-down", d=2048, E=1, top_k=1, inter=192, seed=36), 8500),
+])
+def test_tiles_cut_by_the_schedule(gpu, oracle, shape, T):
+    # On a 256-CU device the tiled kernels run 64 teams; with more runs of 4 tiles than teams and an
+    # uneven split, shares end inside tiles and the second kernel adds the pieces.
+    rng = np.random.default_rng(5)
+    tokens = np.sort(rng.choice(T, size=48, replace=False)).astype(np.int32)
+    run_case(gpu, oracle, shape, T, tokens=tokens)
+
+
 def test_skewed_routing_and_bias(gpu, oracle):
     shape = LayerShape("skew", d=256, E=64, top_k=8, inter=128, shared_inter=256, shared_gate=1, seed=16)
     got, ref = run_case(gpu, oracle, shape, 48, skew=1.5)
