@@ -135,6 +135,9 @@ class Runner:
             tot += row[0].elapsed_ms(row[4])
         out = {n: acc[n] / steps for n in names}
         out["total"] = tot / steps
+        # per-forward samples for the spread (first to last event of each forward, and its gate/up stage)
+        self.samples_ms = {"layer": [row[0].elapsed_ms(row[4]) for row in evs],
+                           "gate_up": [row[1].elapsed_ms(row[2]) for row in evs]}
         return out
 
 
@@ -235,9 +238,17 @@ def main():
         pass
     roofline = {"bound": "hbm", "kernel": "expert_stream_kernel<gate_up>", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": traffic, "algorithmic_bytes": gub,
+                "traffic": None if traffic is None else round(traffic["fetch_bytes"] + traffic["write_bytes"]),
+                "traffic_detail": traffic, "algorithmic_bytes": gub,
                 "avg_launch_us": round(st["gate_up"] * 1e3, 2)}
     stages = {k: round(v * 1e3, 2) for k, v in st.items()}
+
+    def spread(xs):
+        xs = sorted(xs)
+        pick = lambda q: xs[min(len(xs) - 1, int(q * len(xs)))]
+        return {"p10": round(pick(0.10) * 1e3, 2), "median": round(pick(0.50) * 1e3, 2),
+                "p90": round(pick(0.90) * 1e3, 2)}
+    spread_us = {k: spread(v) for k, v in run.samples_ms.items()}
     stages["down_GBps"] = round(dnb / (st["down"] * 1e-3) / 1e9, 1)
     layer = {"bytes": lb, "flops": fl, "hbm_roofline_us": round(hbm_time * 1e6, 2),
              "mfma_roofline_us": round(mfma_time * 1e6, 2),
@@ -346,7 +357,8 @@ def main():
                    "d": shape.d, "E": shape.E, "top_k": shape.top_k, "inter": shape.inter,
                    "shared_inter": shape.shared_inter, "skew_std": args.skew,
                    "weight_replicas": n_rep, "cold_weights": True},
-        "roofline": roofline, "cpu_baseline": cpu, "layer": layer, "stages_us": stages, "curve": curve,
+        "roofline": roofline, "cpu_baseline": cpu, "layer": layer, "stages_us": stages, "spread_us": spread_us,
+        "curve": curve,
         "model_fit": model_fit, "mfma_point": mfma,
     }
     print(json.dumps(result), flush=True)

@@ -184,3 +184,30 @@ def test_qwen15_shape_full_size_sampled_tokens(gpu, oracle):
     # bit-exact, layer output checked on sampled tokens the oracle evaluates one by one
     shape = PRESETS["qwen1.5-moe-a2.7b"]
     run_case(gpu, oracle, shape, 64, tokens=[0, 13, 31, 63], point=163)
+
+
+def test_qwen2_shape_full_size_sampled_tokens(gpu, oracle):
+    # benchmark config 2 at full size (3.5 GB of expert weights, 0.44 GB shared expert), T = 64
+    shape = PRESETS["qwen2-57b-a14b"]
+    run_case(gpu, oracle, shape, 64, tokens=[0, 21, 42, 63], point=263)
+
+
+def test_mixtral_shape_full_size_tiled_sampled_tokens(gpu, oracle):
+    # benchmark config 3 at full size and its largest T (4096: about 1024 rows per expert, the MFMA-tiled
+    # kernels with the persistent schedule the benchmark's compute-bound point times); routing bit-exact on
+    # all tokens, output on sampled tokens
+    shape = PRESETS["mixtral-8x7b"]
+    rng = np.random.default_rng(9)
+    tokens = np.sort(rng.choice(4096, size=24, replace=False)).astype(np.int32)
+    run_case(gpu, oracle, shape, 4096, tokens=tokens, point=363)
+
+
+def test_deepseek_shape_full_size_sampled_tokens(gpu, oracle):
+    # benchmark config 4 at full size (22.6 GB of expert weights, sigmoid scores, 256 experts): T = 64 and the
+    # largest T of its sweep (2560: about 80 rows per expert, shared expert through the tiled kernels)
+    shape = PRESETS["deepseek-v3"]
+    w = synth.make_layer(shape, threads=16)
+    run_case(gpu, oracle, shape, 64, tokens=[0, 17, 40, 63], point=463, weights=w)
+    rng = np.random.default_rng(11)
+    tokens = np.sort(rng.choice(2560, size=6, replace=False)).astype(np.int32)
+    run_case(gpu, oracle, shape, 2560, tokens=tokens, point=464, weights=w)
