@@ -151,11 +151,102 @@ def pick_replicas(shape, T, budget_gb=24.0):
     return max(2, min(want, cap, 12))
 
 
-SHORT_CURVE = [(1, 0), (2, 0), (4, 0), (8, 0), (16, 0), (8, 3), (16, 3), (32, 3), (64, 3), (128, 4)]
+SHORT_CURVE = [(1, 0), (2, 0), (4, 0), (8, 0), (16, 0), (8, 3), (16, 3), (32, 3), (64, 3), (128, 3), (128, 4)]
+
+
+PAPER_BATCH_SIZES = [1, 2, 4, 8, 12, 16, 20, 24, 28, 32, 36, 40, 44, 48, 52, 56, 60, 80, 100]   # Appendix C.1
+
+
+def layer_times(run, shape, Ts, steps, point_base):
+    """Mean us per layer for each T (fresh token batch per T); -> {T: (us, n_active)}."""
+    from paper_2505_19645_amd import synth
+    out = {}
+    for t in Ts:
+        run.prepare(synth.make_tokens(shape, t, point=point_base + t))
+        m = run.time_steps(steps, max(5, steps // 3))
+        out[t] = (m * 1e3, int(run.n_active.item()))
+    return out
+
+
+def efficiency_rows(times, Bs, gammas):
+    """Layer-level target efficiency t(B) / t(B*(gamma+1)) (Sec. 3.1) where both are measured."""
+    rows = []
+    for g in gammas:
+        for b in Bs:
+            if b in times and b * (g + 1) in times:
+                rows.append({"B": b, "gamma": g, "target_efficiency": round(times[b][0] / times[b * (g + 1)][0], 4)})
+    return rows
+
+
+def peak_of(rows, g):
+    cand = [r for r in rows if r["gamma"] == g]
+    return max(cand, key=lambda r: r["target_efficiency"]) if cand else None
+
+
+def mode_dense(args, shape, torch, moesd, synth):
+    """Sec. 4.2 / Fig. 2(c) at layer level: the MoE layer against a dense FFN with the same
+    activated flops (E = K = 1, intermediate size K * I), same kernels."""
+    import dataclasses
+    dense = dataclasses.replace(shape, name=shape.name + "-dense-equivalent", E=1, top_k=1,
+                                inter=shape.top_k * shape.inter)
+    Bs = [1, 2, 4, 8, 16, 32, 64, 128]
+    gammas = (1, 3)
+    Ts = sorted({b * (g + 1) for b in Bs for g in gammas} | set(Bs))
+    res = {}
+    for sh in (shape, dense):
+        w = synth.make_layer(sh, threads=min(16, os.cpu_count() or 1))
+        run = Runner(sh, w, pick_replicas(sh, 1))
+        times = layer_times(run, sh, Ts, args.curve_steps, 7000)
+        res[sh.name] = {"times_us": {str(t): round(v[0], 2) for t, v in times.items()},
+                        "rows": efficiency_rows(times, Bs, gammas)}
+        for g in gammas:
+            pk = peak_of(res[sh.name]["rows"], g)
+            log(f"[bench] {sh.name}: gamma={g} target efficiency peaks at B={pk['B']} ({pk['target_efficiency']:.2f}); "
+                + " ".join(f"{r['B']}:{r['target_efficiency']:.2f}" for r in res[sh.name]["rows"] if r["gamma"] == g))
+        del run, w
+        torch.cuda.empty_cache()
+    print(json.dumps({"metric": "layer-level target efficiency t(B)/t(B*(gamma+1)), MoE vs dense FFN of equal activated flops",
+                      "unit": "ratio", "n_gpus": 1, "data": "synthetic", "dtype": "bf16",
+                      "config": {"workload": f"{shape.name}-shaped MoE layer vs dense equivalent (E=K=1, I={dense.inter})"},
+                      "moe": res[shape.name], "dense": res[dense.name]}))
+
+
+def mode_ksweep(args, shape, torch, moesd, synth):
+    """Sec. 4.3 / Fig. 3 at layer level: the same layer with K experts per token, K in
+    {1, 2, 4, 8, 16, 32}, gamma in {2, 4}, the paper's 19 batch sizes."""
+    import dataclasses
+    gammas = (2, 4)
+    Ts = sorted({b * (g + 1) for b in PAPER_BATCH_SIZES for g in gammas} | set(PAPER_BATCH_SIZES))
+    w = synth.make_layer(shape, threads=min(16, os.cpu_count() or 1))
+    run = Runner(shape, w, 2)
+    out = []
+    for K in (1, 2, 4, 8, 16, 32):
+        if K > shape.E:
+            continue
+        sk = dataclasses.replace(shape, top_k=K)
+        run.shape, run.desc = sk, moesd.make_desc(sk)
+        times = layer_times(run, sk, Ts, args.curve_steps, 9000 + 100000 * K)
+        rows = efficiency_rows(times, PAPER_BATCH_SIZES, gammas)
+        entry = {"K": K, "rho": round(K / shape.E, 4), "T_thres_tau0.95": int(moesd.moesd_token_threshold(shape.E, K, 0.95)),
+                 "rows": rows, "times_us": {str(t): round(v[0], 2) for t, v in times.items()}}
+        for g in gammas:
+            pk = peak_of(rows, g)
+            entry[f"peak_gamma{g}"] = {"B": pk["B"], "target_efficiency": pk["target_efficiency"]}
+        out.append(entry)
+        log(f"[bench] K={K} (rho={K / shape.E:.3f}, T_thres={entry['T_thres_tau0.95']}): "
+            + ", ".join(f"gamma={g}: peak at B={entry[f'peak_gamma{g}']['B']} "
+                        f"({entry[f'peak_gamma{g}']['target_efficiency']:.2f})" for g in gammas))
+    print(json.dumps({"metric": "layer-level target efficiency vs sparsity (K sweep)", "unit": "ratio", "n_gpus": 1,
+                      "data": "synthetic", "dtype": "bf16",
+                      "config": {"workload": f"{shape.name}-shaped MoE layer, K in 1..32, gamma in (2, 4), 19 batch sizes"},
+                      "sweep": out}))
 
 
 def main():
     ap = argparse.ArgumentParser()
+    ap.add_argument("--mode", choices=["headline", "dense", "ksweep"], default="headline",
+                    help="headline: the benchmark line; dense: MoE vs dense-equivalent target efficiency; "
+                         "ksweep: target efficiency for K = 1..32 (use --config qwen2-57b-a14b)")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
@@ -191,6 +282,11 @@ def main():
     T = args.B * (args.gamma + 1)
     log(f"[bench] {shape.name}: d={shape.d} E={shape.E} K={shape.top_k} I={shape.inter} "
         f"S={shape.shared_inter}; B={args.B} gamma={args.gamma} T={T} on {torch.cuda.get_device_name(0)}")
+
+    if args.mode == "dense":
+        return mode_dense(args, shape, torch, moesd, synth)
+    if args.mode == "ksweep":
+        return mode_ksweep(args, shape, torch, moesd, synth)
 
     t0 = time.time()
     host_w = synth.make_layer(shape, skew_std=args.skew, threads=min(16, os.cpu_count() or 1))
@@ -291,6 +387,45 @@ def main():
             f"c2={model_fit['c2_us_per_expert']:.2f} us/expert ({model_fit['c2_over_k2_min']:.2f} x k2_min), "
             f"c3={model_fit['c3_us']:.2f}, mean rel err {model_fit['mean_rel_err']:.3f}")
 
+    # ---- layer-level speed-up model (Sec. 3.1 Eq. (speedup), Alg. 1) on these measurements ----
+    # The measured layer stands in for the target forward; draft and rejection times are stated
+    # fractions of t(B) (the paper: T_D/T_T usually below 1/10), sigma comes from a stated acceptance rate.
+    sd_model = None
+    times_by_T = {c["T"]: c["us"] for c in curve}
+    times_by_T.setdefault(T, ms * 1e3)
+    if len(times_by_T) >= 8:
+        from paper_2505_19645_amd import sdmodel
+        assume = {"alpha": 0.8, "draft_over_target": 0.1, "reject_over_target": 0.01, "verify_tokens": "B*(gamma+1)"}
+        rows = sdmodel.layer_speedups_from_curve(times_by_T, gammas=(1, 3), alpha=assume["alpha"],
+                                                 draft_ratio=assume["draft_over_target"],
+                                                 reject_ratio=assume["reject_over_target"])
+        if len(rows) >= 10:
+            ridge = MFMA_BF16_PEAK_TF * 1e12 / (HBM_PEAK_GBS * 1e9)
+            bias_min = (shape.shared_bytes + shape.router_bytes) / (HBM_PEAK_GBS * 1e9) * 1e6
+            k2_min = shape.expert_bytes / (HBM_PEAK_GBS * 1e9) * 1e6
+            fit = sdmodel.fit_speedup([r["B"] for r in rows], [r["gamma"] for r in rows], shape.top_k, shape.E,
+                                      [r["sigma"] for r in rows], [r["speedup"] for r in rows], ridge,
+                                      bias_min=max(bias_min, 1e-3), k2_min=k2_min, t_rej_max=max(times_by_T.values()))
+            best = {}
+            for r, pr in zip(rows, fit["pred"]):
+                r["model"] = round(float(pr), 4)
+                r["speedup"] = round(r["speedup"], 4)
+                r["sigma"] = round(r["sigma"], 4)
+                r["target_efficiency"] = round(r["target_efficiency"], 4)
+                g = r["gamma"]
+                if g not in best or r["target_efficiency"] > best[g]["target_efficiency"]:
+                    best[g] = r
+            sd_model = {"assumptions": assume, "points": rows,
+                        "params": {k: round(v, 5) for k, v in fit["params"].items()},
+                        "mean_rel_err": round(fit["mean_rel_err"], 4), "max_rel_err": round(fit["max_rel_err"], 4),
+                        "best_target_efficiency": {str(g): {"B": r["B"], "value": r["target_efficiency"]}
+                                                   for g, r in best.items()},
+                        "T_thres_tau0.95": int(moesd.moesd_token_threshold(shape.E, shape.top_k, 0.95))}
+            log(f"[bench] speed-up model over {len(rows)} (B, gamma) points: mean rel err {fit['mean_rel_err']:.3f}; "
+                + ", ".join(f"gamma={g}: target efficiency peaks at B={r['B']} ({r['target_efficiency']:.2f})"
+                            for g, r in sorted(best.items()))
+                + f"; T_thres(0.95)={sd_model['T_thres_tau0.95']}")
+
     # ---- compute-bound point: Mixtral-8x7B-shaped layer at T = 4096 (MFMA roofline) ----
     mfma = None
     if not args.no_mfma_point:
@@ -359,7 +494,7 @@ def main():
                    "weight_replicas": n_rep, "cold_weights": True},
         "roofline": roofline, "cpu_baseline": cpu, "layer": layer, "stages_us": stages, "spread_us": spread_us,
         "curve": curve,
-        "model_fit": model_fit, "mfma_point": mfma,
+        "model_fit": model_fit, "sd_speedup_model": sd_model, "mfma_point": mfma,
     }
     print(json.dumps(result), flush=True)
 
