@@ -50,8 +50,16 @@
 #define T_A_BYTES (TBN * T_ROW_BYTES)  // 32 KB
 #define T_B_BYTES (TBM * T_ROW_BYTES)  // 32 KB
 #define T_STAGE_BYTES (T_A_BYTES + T_B_BYTES)
-#define T_LW 8  // 16-byte pieces per lane per stage
-#define T_THREADS 512
+#ifndef T_WAVES
+#define T_WAVES 8  // 8: two waves per SIMD, 128 x 64 per wave; 4: one wave per SIMD, 128 x 128 per wave
+#endif
+#define T_THREADS (64 * T_WAVES)
+#define T_LW (4096 / T_THREADS)  // 16-byte pieces per lane per stage
+#define T_NT (16 / T_WAVES)      // 32-token tiles per wave
+#define T_LROWS (512 / T_WAVES)  // rows of one operand a loader wave fetches
+#ifndef T_AHEAD
+#define T_AHEAD 1  // stages of global loads in flight in registers (2 needs more registers than either variant has)
+#endif
 #define TILED_LDS_BYTES (2 * T_STAGE_BYTES)
 
 enum { TMODE_GATE_UP = 0, TMODE_DOWN = 1 };
@@ -78,7 +86,7 @@ struct TiledSched {
   float *partials;        // [2 * workgroups of the main kernel] slots of T_THREADS * 128 floats
   int n_teams;            // teams of the main kernel (its grid / 4)
 };
-#define T_SLOT_FLOATS (T_THREADS * 128)
+#define T_SLOT_FLOATS (T_THREADS * 64 * T_NT)
 
 // The schedule both kernels derive from the plan: units of (run, stage), two regions.
 struct TiledWork {
@@ -122,7 +130,7 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
   const int n_large = w.n_large;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wr = wave & 1, wt = wave >> 1;  // wt: 0..3
+  const int wr = wave & 1, wt = wave >> 1;  // wt: token part, 0 .. T_WAVES/2 - 1
   const int r32 = lane & 31, q = lane >> 5;
   const int n_shared_entries = sc.n_shared_entries;
   int rt, entry;
@@ -182,31 +190,31 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
   // rows (w < 4) or of the token rows (w >= 4), instruction i rows 8i..8i+7, lane l row
   // (l >> 3), piece (l & 7)
   const int lrow = lane >> 3, piece = lane & 7;
-  const bool load_b = wave >= 4;
-  const int lw = wave & 3;
+  const bool load_b = wave >= T_WAVES / 2;
+  const int lw = wave % (T_WAVES / 2);  // which T_LROWS rows of the operand
   const char *wbase;    // wave-uniform: first row this wave may touch, at the k origin
   uint32_t off[T_LW];   // this lane's rows (clamped into the valid rows), in bytes from wbase
   if (!load_b) {
-    const bool second = lw >= 2;
+    const bool second = lw * T_LROWS >= 128;
     const uint16_t *base = (second && second_ok) ? A1 : A0;
     const int rv = second ? rv1 : rv0;
     wbase = reinterpret_cast<const char *>(base + (size_t)i0 * a_stride);
 #pragma unroll
     for (int i = 0; i < T_LW; ++i) {
-      const int hrow = 64 * (lw & 1) + 8 * i + lrow;
+      const int hrow = (lw * T_LROWS) % 128 + 8 * i + lrow;
       off[i] = (uint32_t)min(hrow, rv - 1) * (uint32_t)(a_stride * 2);
     }
   } else {
     wbase = reinterpret_cast<const char *>(use_map ? B : B + (size_t)row0 * b_stride);
 #pragma unroll
     for (int i = 0; i < T_LW; ++i) {
-      const int row = min(64 * lw + 8 * i + lrow, m - 1);
+      const int row = min(T_LROWS * lw + 8 * i + lrow, m - 1);
       const int tr = use_map ? a.row_token[row0 + row] : row;
       off[i] = (uint32_t)tr * (uint32_t)(b_stride * 2);
     }
   }
   // this lane's eight LDS store positions (stage buffer 0)
-  const int srow0 = (load_b ? TBN : 0) + 64 * lw + lrow;
+  const int srow0 = (load_b ? TBN : 0) + T_LROWS * lw + lrow;
   auto load_stage = [&](int s, u32x4 (&pre)[T_LW]) __attribute__((always_inline)) {
     // a piece past the end of the rows is pulled back inside (it is zeroed before the store)
     const uint32_t kk = 2u * (uint32_t)min(s * TBK + piece * 8, klen - 8);
@@ -226,44 +234,48 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
     }
   };
 
-  f32x16 acc[4][2];  // [weight tile: 2 of the first half, 2 of the second][token tile]
+  f32x16 acc[4][T_NT];  // [weight tile: 2 of the first half, 2 of the second][token tile]
 #pragma unroll
   for (int h = 0; h < 4; ++h)
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int t = 0; t < T_NT; ++t)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[h][t][v] = 0.f;
 
   // Operand fragments of one 16-element half step: 4 weight tiles and 2 token tiles.
   const int key = (r32 >> 1) & 7;
   const char *pa0 = smem + (64 * wr + r32) * T_ROW_BYTES;
-  const char *pb0 = smem + T_A_BYTES + (64 * wt + r32) * T_ROW_BYTES;
-  auto read_half = [&](int buf, int hs, u32x4 (&fa)[4], u32x4 (&fb)[2]) __attribute__((always_inline)) {
+  const char *pb0 = smem + T_A_BYTES + (32 * T_NT * wt + r32) * T_ROW_BYTES;
+  auto read_half = [&](int buf, int hs, u32x4 (&fa)[4], u32x4 (&fb)[T_NT]) __attribute__((always_inline)) {
     const int so = buf * T_STAGE_BYTES + (((2 * hs + q) ^ key) << 4);
 #pragma unroll
     for (int h = 0; h < 4; ++h)
       fa[h] = *reinterpret_cast<const u32x4 *>(pa0 + so + ((h >> 1) * 128 + (h & 1) * 32) * T_ROW_BYTES);
 #pragma unroll
-    for (int t = 0; t < 2; ++t) fb[t] = *reinterpret_cast<const u32x4 *>(pb0 + so + t * 32 * T_ROW_BYTES);
+    for (int t = 0; t < T_NT; ++t) fb[t] = *reinterpret_cast<const u32x4 *>(pb0 + so + t * 32 * T_ROW_BYTES);
   };
-  auto mfma_half = [&](const u32x4 (&fa)[4], const u32x4 (&fb)[2]) __attribute__((always_inline)) {
+  auto mfma_half = [&](const u32x4 (&fa)[4], const u32x4 (&fb)[T_NT]) __attribute__((always_inline)) {
 #pragma unroll
     for (int h = 0; h < 4; ++h)
 #pragma unroll
-      for (int t = 0; t < 2; ++t) acc[h][t] = mfma32(fa[h], fb[t], acc[h][t]);
+      for (int t = 0; t < T_NT; ++t) acc[h][t] = mfma32(fa[h], fb[t], acc[h][t]);
   };
 
   const int nkb = (klen + TBK - 1) / TBK;          // this tile's own stage count (<= nkb_reg)
   const int s0 = min(st0, nkb), s1 = min(st1, nkb);  // the part of the piece that exists
   const bool ragged = (klen % TBK) != 0 && s1 == nkb;  // then the piece's last stage is zero-padded
-  u32x4 pre[T_LW], fa0[4], fb0[2], fa1[4], fb1[2];
-  // One stage: four half steps from buffer kb & 1.  Before the third half step's MFMAs
-  // retire, the prefetched registers (stage kb+1) go to the other buffer, whose last
-  // readers passed the previous barrier, and the loads of stage kb+2 are issued; after the
-  // barrier the first fragments of stage kb+1 are read under the last MFMAs of stage kb.
-  // (The scheduling fences keep the compiler from sinking the reads below the MFMAs.)
-  auto step = [&](int kb, auto has_next, auto has_next2) __attribute__((always_inline)) {
-    const int buf = kb & 1;
+  u32x4 pre[T_AHEAD][T_LW], fa0[4], fb0[T_NT], fa1[4], fb1[T_NT];
+  const int n = s1 - s0;  // stages of this piece; stage s0 + j lives in LDS buffer j & 1 and in pre[j % T_AHEAD]
+  // One stage (four half steps) from buffer j & 1.  PI: which register set holds stage j+1.
+  // Stage j+1 goes from registers to the other buffer (its last readers passed the previous
+  // barrier), the loads of stage j+1+T_AHEAD are issued into the freed registers; after the
+  // barrier the first fragments of stage j+1 are read under the last MFMAs of stage j.
+  auto step = [&](int j, auto pi, auto has_next, auto has_load) __attribute__((always_inline)) {
+    constexpr int PI = decltype(pi)::value;
+    constexpr bool HN = decltype(has_next)::value, HL = decltype(has_load)::value;
+    const int buf = j & 1;
+#if defined(T_PHASES)
+    // phases, fenced so that the compiler cannot sink the reads below the MFMAs
     mfma_half(fa0, fb0);
     __builtin_amdgcn_sched_barrier(0);
     read_half(buf, 2, fa0, fb0);
@@ -274,33 +286,126 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
     __builtin_amdgcn_sched_barrier(0);
     mfma_half(fa0, fb0);
     __builtin_amdgcn_sched_barrier(0);
-    if constexpr (decltype(has_next)::value) {
-      store_stage(kb + 1, buf ^ 1, pre, ragged && !decltype(has_next2)::value);
-      if constexpr (decltype(has_next2)::value) load_stage(kb + 2, pre);
-      t_barrier();  // stage kb+1 is in LDS for everyone; everyone has stage kb in registers
+    if constexpr (HN) {
+      store_stage(s0 + j + 1, buf ^ 1, pre[PI], ragged && j + 2 == n);
+      if constexpr (HL) load_stage(s0 + j + 1 + T_AHEAD, pre[PI]);
+      t_barrier();  // stage j+1 is in LDS for everyone; everyone has stage j in registers
       read_half(buf ^ 1, 0, fa0, fb0);
     }
     __builtin_amdgcn_sched_barrier(0);
     mfma_half(fa1, fb1);
     __builtin_amdgcn_sched_barrier(0);
-    if constexpr (decltype(has_next)::value) read_half(buf ^ 1, 1, fa1, fb1);
+    if constexpr (HN) read_half(buf ^ 1, 1, fa1, fb1);
     __builtin_amdgcn_sched_barrier(0);
-  };
-  if (!FIXUP && s0 < s1) {
-    load_stage(s0, pre);
-    t_barrier();  // everyone is done with the LDS of the previous piece
-    store_stage(s0, s0 & 1, pre, ragged && s0 + 1 == s1);
-    if (s0 + 1 < s1) load_stage(s0 + 1, pre);
-    t_barrier();
-    read_half(s0 & 1, 0, fa0, fb0);
-    read_half(s0 & 1, 1, fa1, fb1);
-    int kb = s0;
-    for (; kb + 2 < s1; ++kb) step(kb, std::true_type{}, std::true_type{});
-    if (kb + 1 < s1) {
-      step(kb, std::true_type{}, std::false_type{});
-      ++kb;
+#else
+    // Every other instruction is issued in the shadow of an MFMA (scheduling groups:
+    // 0x008 MFMA, 0x020 VMEM read, 0x100 DS read, 0x200 DS write).  The LDS stores are
+    // spread one per MFMA: bunching them was measured 7 % slower.
+    constexpr int MH = 4 * T_NT;  // MFMAs of a half step
+    constexpr int RH = 4 + T_NT;  // fragment reads of a half step
+    mfma_half(fa0, fb0);
+    if constexpr (HN) store_stage(s0 + j + 1, buf ^ 1, pre[PI], ragged && j + 2 == n);
+#pragma unroll
+    for (int i = 0; i < MH; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      if (HN) __builtin_amdgcn_sched_group_barrier(0x200, T_LW / MH, 0);
     }
-    step(kb, std::false_type{}, std::false_type{});
+    __builtin_amdgcn_sched_barrier(0);
+    read_half(buf, 2, fa0, fb0);
+    mfma_half(fa1, fb1);
+    if constexpr (HL) load_stage(s0 + j + 1 + T_AHEAD, pre[PI]);
+#pragma unroll
+    for (int i = 0; i < RH; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < MH - RH; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      if (HL) __builtin_amdgcn_sched_group_barrier(0x020, T_LW / (MH - RH), 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    read_half(buf, 3, fa1, fb1);
+    mfma_half(fa0, fb0);
+#pragma unroll
+    for (int i = 0; i < RH; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, MH - RH, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (HN) {
+      t_barrier();  // stage j+1 is in LDS for everyone; everyone has stage j in registers
+      read_half(buf ^ 1, 0, fa0, fb0);
+    }
+    mfma_half(fa1, fb1);
+    if constexpr (HN) read_half(buf ^ 1, 1, fa1, fb1);
+#pragma unroll
+    for (int i = 0; i < 2 * RH - MH; ++i) {  // 2 RH reads over MH MFMAs: two each at first, then one each
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      if (HN) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 2 * (MH - RH); ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      if (HN) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#endif
+  };
+  using std::integral_constant;
+  using P0 = integral_constant<int, 0>;
+#if T_AHEAD > 1
+  using P1 = integral_constant<int, T_AHEAD - 1>;
+#endif
+  using Y = std::true_type;
+  using N = std::false_type;
+  if (!FIXUP && n > 0) {
+#pragma unroll
+    for (int a2 = 0; a2 < T_AHEAD; ++a2)
+      if (a2 < n) load_stage(s0 + a2, pre[a2]);
+    t_barrier();  // everyone is done with the LDS of the previous piece
+    store_stage(s0, 0, pre[0], ragged && n == 1);
+    if (T_AHEAD < n) load_stage(s0 + T_AHEAD, pre[0]);
+    t_barrier();
+    read_half(0, 0, fa0, fb0);
+    read_half(0, 1, fa1, fb1);
+    int j = 0;
+    // steady state: branch-free, so the compiler's wait counts stay exact; the last stages are
+    // straight-line sequences chosen by how many remain (no loop around differently shaped steps)
+#if T_AHEAD == 1
+    for (; j + 2 < n; ++j) step(j, P0{}, Y{}, Y{});
+    if (j + 1 < n) {
+      step(j, P0{}, Y{}, N{});
+      ++j;
+    }
+    step(j, P0{}, N{}, N{});
+#else
+    for (; j + 4 < n; j += 2) {
+      step(j, P1{}, Y{}, Y{});
+      step(j + 1, P0{}, Y{}, Y{});
+    }
+    switch (n - j) {  // j is even here
+      case 4:
+        step(j, P1{}, Y{}, Y{});
+        step(j + 1, P0{}, Y{}, N{});
+        step(j + 2, P1{}, Y{}, N{});
+        step(j + 3, P0{}, N{}, N{});
+        break;
+      case 3:
+        step(j, P1{}, Y{}, N{});
+        step(j + 1, P0{}, Y{}, N{});
+        step(j + 2, P1{}, N{}, N{});
+        break;
+      case 2:
+        step(j, P1{}, Y{}, N{});
+        step(j + 1, P0{}, N{}, N{});
+        break;
+      default:
+        step(j, P1{}, N{}, N{});
+        break;
+    }
+#endif
   }
 
   // ---- a tile cut by the schedule: its pieces meet in memory, the second kernel finishes it --
@@ -309,11 +414,11 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
 #pragma unroll
     for (int h = 0; h < 4; ++h)
 #pragma unroll
-      for (int t = 0; t < 2; ++t)
+      for (int t = 0; t < T_NT; ++t)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const f32x16 &v = acc[h][t];
-          mine[((h * 2 + t) * 4 + g) * T_THREADS + tid] = (f32x4){v[4 * g], v[4 * g + 1], v[4 * g + 2], v[4 * g + 3]};
+          mine[((h * T_NT + t) * 4 + g) * T_THREADS + tid] = (f32x4){v[4 * g], v[4 * g + 1], v[4 * g + 2], v[4 * g + 3]};
         }
     return;
   }
@@ -337,10 +442,10 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
 #pragma unroll
       for (int h = 0; h < 4; ++h)
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+        for (int t = 0; t < T_NT; ++t)
 #pragma unroll
           for (int g = 0; g < 4; ++g) {
-            const f32x4 p = theirs[((h * 2 + t) * 4 + g) * T_THREADS + tid];
+            const f32x4 p = theirs[((h * T_NT + t) * 4 + g) * T_THREADS + tid];
 #pragma unroll
             for (int c = 0; c < 4; ++c) acc[h][t][4 * g + c] += p[c];
           }
@@ -350,8 +455,8 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
   // ---- epilogue: lane holds, for token (64wt + 32t + r32), features 8g + 4q + c -------------
   // weight tile h: half (h >> 1), rows 64wr + 32(h & 1) .. +31 of that half
 #pragma unroll
-  for (int t = 0; t < 2; ++t) {
-    const int j = 64 * wt + 32 * t + r32;
+  for (int t = 0; t < T_NT; ++t) {
+    const int j = 32 * T_NT * wt + 32 * t + r32;
     if (j < m) {
       const size_t orow = (size_t)(row0 + j);
 #pragma unroll
