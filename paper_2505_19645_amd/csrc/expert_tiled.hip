@@ -502,15 +502,35 @@ __global__ __launch_bounds__(T_THREADS) void expert_tiled_kernel(StreamArgs a, T
   const TiledWork w = tiled_work(a, sc);
   if (w.W == 0) return;
   if (!w.cut) {
-    // whole runs, dealt round-robin: at any time the chip works on consecutive runs, whose
-    // tiles share token blocks and weight tiles in the caches
-    for (long run = team; run < w.runs; run += w.n_teams) {
-      const bool shared_region = run < w.runs_s;
+    // Whole tiles.  The shared expert's runs (4 consecutive tiles) are dealt round-robin over
+    // the teams.  The routed experts' work is the grid (entry group of 4 token blocks) x (row
+    // tile); it is walked entry group by entry group and handed out 8 cells at a time to the
+    // 8 teams of one XCD, so an XCD's workgroups read the same 4 token blocks (and each team
+    // its own weight tile): on the Mixtral-shaped layer at T = 4096 this took the gate/up kernel's
+    // L2 fill traffic from 8.8 GB to 4.7 GB per launch (1.9 GB of weights are the floor).
+    const int tl = team / 8, tpx = w.n_teams / 8;  // team within its XCD, teams per XCD
+    const long sh_rounds = (w.runs_s + w.n_teams - 1) / w.n_teams;
+    const long cells = (long)((w.n_large + 3) / 4) * sc.rt_routed;
+    const long groups = (cells + tpx - 1) / tpx;
+    const long n_it = sh_rounds + (groups + 7) / 8;
+    for (long it = 0; it < n_it; ++it) {
+      bool shared_region, valid;
+      int tile;
+      if (it < sh_rounds) {
+        const long run = team + it * w.n_teams;
+        shared_region = true;
+        tile = (int)(4 * run + member);
+        valid = run < w.runs_s && tile < w.n_sh_tiles;
+      } else {
+        const long q = (xcd + 8 * (it - sh_rounds)) * tpx + tl;
+        const int eg = (int)(q / sc.rt_routed), rt = (int)(q % sc.rt_routed);
+        const int entry = 4 * eg + member;
+        shared_region = false;
+        valid = q < cells && entry < w.n_large;
+        tile = rt * w.n_large + entry;
+      }
       const int nkb_reg = shared_region ? sc.nkb_s : sc.nkb_r;
-      const long lrun = shared_region ? run : run - w.runs_s;
-      const int tile = (int)(4 * lrun + member);
-      if (tile < (shared_region ? w.n_sh_tiles : w.n_r_tiles))
-        tiled_piece<MODE, false>(a, sc, smem, shared_region, tile, 0, nkb_reg, nkb_reg, 0, 0, member, w);
+      if (valid) tiled_piece<MODE, false>(a, sc, smem, shared_region, tile, 0, nkb_reg, nkb_reg, 0, 0, member, w);
     }
     return;
   }
