@@ -44,7 +44,9 @@
 #define RING 6             // slots in the ring
 #define AHEAD 4            // slots in flight
 #define LW 6               // loads per wave per slot
-#define RED_BYTES 8192     // 4 waves x 2 halves x 256 floats
+#define RED_ROW 20         // floats per token row of a partial tile: 16 features + 4 of padding (bank spread)
+#define RED_TILE (16 * RED_ROW)
+#define RED_BYTES (8 * RED_TILE * 4)  // 4 waves x 2 halves x 16 rows
 #define SMALL_M 16
 #define BIG_TB 64
 #define STREAM_LDS_BYTES (RING * SLOT_BYTES + RED_BYTES)
@@ -376,6 +378,28 @@ __device__ __forceinline__ void store_out(void *out, int out_n, size_t orow, int
   }
 }
 
+// the same for 4 neighbouring features i..i+3 (i and out_n are multiples of 4, so the four
+// are inside the row together or not at all)
+template <int MODE>
+__device__ __forceinline__ void store_out4(void *out, int out_n, size_t orow, int i, int second_off, f32x4 s0,
+                                           f32x4 s1) {
+  if (MODE == MODE_GATE_UP) {
+    if (i < out_n) {
+      uint32_t hb[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) hb[c] = f32_to_bf16_bits(silu_f32(s0[c]) * s1[c]);
+      u32x2 o;
+      o[0] = hb[0] | (hb[1] << 16);
+      o[1] = hb[2] | (hb[3] << 16);
+      *reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(out) + orow * out_n + i) = o;
+    }
+  } else {
+    float *y = reinterpret_cast<float *>(out);
+    if (i < out_n) *reinterpret_cast<f32x4 *>(y + orow * out_n + i) = s0;
+    if (i + second_off < out_n) *reinterpret_cast<f32x4 *>(y + orow * out_n + i + second_off) = s1;
+  }
+}
+
 // All tiles of one class for this workgroup: the software pipeline.
 template <int MODE, bool WIDE>
 __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_, const ClassCfg &c,
@@ -435,14 +459,15 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
   int pend_m = 0, pend_row0 = 0, pend_i0 = 0, pend_n = 0;
   void *pend_out = nullptr;
 
-  auto flush_pending = [&]() __attribute__((always_inline)) {  // after a barrier: add the waves' partial tiles
-    const int l2 = tid & 63, rr = tid >> 6;
-    const int j = l2 & 15, fi = 4 * (l2 >> 4) + rr;
+  // After a barrier: add the waves' partial tiles.  Thread t takes token row t >> 4 and feature
+  // t & 15 (of both halves), so 16 neighbouring lanes store 16 neighbouring features of a row.
+  auto flush_pending = [&]() __attribute__((always_inline)) {
+    const int j = tid >> 4, fi = tid & 15;
     float s0 = 0.f, s1 = 0.f;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
-      s0 += red[(w * 2 + 0) * 256 + tid];
-      s1 += red[(w * 2 + 1) * 256 + tid];
+      s0 += red[(w * 2 + 0) * RED_TILE + j * RED_ROW + fi];
+      s1 += red[(w * 2 + 1) * RED_TILE + j * RED_ROW + fi];
     }
     if (j < pend_m) store_out<MODE>(pend_out, pend_n, (size_t)(pend_row0 + j), pend_i0 + fi, 16, s0, s1);
     pend = false;
@@ -568,12 +593,9 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
         for (int nt = 0; nt < NACC; ++nt)
           if (nt < ntc) {
             const int j = nt * 16 + r16;
-            if (j < cen.m) {
-#pragma unroll
-              for (int rr = 0; rr < 4; ++rr)
-                store_out<MODE>(cen.out, cen.out_n, (size_t)(cen.row0 + j), i0 + 16 * wave + 4 * q + rr, 64,
-                                acc0[nt][rr], acc1[nt][rr]);
-            }
+            if (j < cen.m)  // 4 neighbouring features per lane: one vector store per half
+              store_out4<MODE>(cen.out, cen.out_n, (size_t)(cen.row0 + j), i0 + 16 * wave + 4 * q, 64, acc0[nt],
+                               acc1[nt]);
           }
 #pragma unroll
         for (int nt = 0; nt < NACC; ++nt) {
@@ -582,11 +604,9 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
         }
       } else {
         if (cen.nkb == 1) wg_barrier();  // the previous tile's sums may still be read from `red`
-#pragma unroll
-        for (int rr = 0; rr < 4; ++rr) {
-          red[(wave * 2 + 0) * 256 + rr * 64 + lane] = acc0[0][rr];
-          red[(wave * 2 + 1) * 256 + rr * 64 + lane] = acc1[0][rr];
-        }
+        // lane (q, r16) holds features 4q..4q+3 of token row r16: one 16-byte store per half
+        *reinterpret_cast<f32x4 *>(red + (wave * 2 + 0) * RED_TILE + r16 * RED_ROW + 4 * q) = acc0[0];
+        *reinterpret_cast<f32x4 *>(red + (wave * 2 + 1) * RED_TILE + r16 * RED_ROW + 4 * q) = acc1[0];
         pend = true;
         pend_m = cen.m;
         pend_row0 = cen.row0;

@@ -508,15 +508,25 @@ __global__ __launch_bounds__(T_THREADS) void expert_tiled_kernel(StreamArgs a, T
     // 8 teams of one XCD, so an XCD's workgroups read the same 4 token blocks (and each team
     // its own weight tile): on the Mixtral-shaped layer at T = 4096 this took the gate/up kernel's
     // L2 fill traffic from 8.8 GB to 4.7 GB per launch (1.9 GB of weights are the floor).
+    // (With few large entries the groups of 4 would be mostly empty: then the routed tiles are
+    // dealt as plain runs of 4 consecutive tiles too.)
     const int tl = team / 8, tpx = w.n_teams / 8;  // team within its XCD, teams per XCD
+    const int eg_n = (w.n_large + 3) / 4;
+    // at most 10 % of the group slots empty, and enough work that the two phases (shared, then
+    // routed) starting at team 0 each cost nothing
+    const bool grid = (4 * eg_n - w.n_large) * 10 <= w.n_large && w.runs > 2 * w.n_teams;
     const long sh_rounds = (w.runs_s + w.n_teams - 1) / w.n_teams;
-    const long cells = (long)((w.n_large + 3) / 4) * sc.rt_routed;
-    const long groups = (cells + tpx - 1) / tpx;
-    const long n_it = sh_rounds + (groups + 7) / 8;
+    const long cells = (long)eg_n * sc.rt_routed;
+    const long n_it = grid ? sh_rounds + ((cells + tpx - 1) / tpx + 7) / 8 : (w.runs + w.n_teams - 1) / w.n_teams;
     for (long it = 0; it < n_it; ++it) {
       bool shared_region, valid;
       int tile;
-      if (it < sh_rounds) {
+      if (!grid) {  // shared and routed runs as one list, dealt round-robin
+        const long run = team + it * w.n_teams;
+        shared_region = run < w.runs_s;
+        tile = (int)(4 * (shared_region ? run : run - w.runs_s) + member);
+        valid = run < w.runs && tile < (shared_region ? w.n_sh_tiles : w.n_r_tiles);
+      } else if (it < sh_rounds) {
         const long run = team + it * w.n_teams;
         shared_region = true;
         tile = (int)(4 * run + member);
