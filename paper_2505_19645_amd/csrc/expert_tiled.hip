@@ -113,9 +113,10 @@ __device__ __forceinline__ TiledWork tiled_work(const StreamArgs &a, const Tiled
   w.W = w.W_s + (w.runs - w.runs_s) * sc.nkb_r;
   // Cutting runs costs a round trip of partial sums through memory and a second epilogue
   // pass: only worth it when whole runs would leave the busiest team more than 15 % above
-  // the mean, and pointless when there are not even as many runs as teams.
+  // the mean, or when at least half the teams would idle and every team still gets 32 stages.
   const long per_team = (w.runs + w.n_teams - 1) / w.n_teams;
-  w.cut = w.runs > w.n_teams && per_team * w.n_teams * 100 > w.runs * 115;
+  w.cut = (w.runs > w.n_teams && per_team * w.n_teams * 100 > w.runs * 115) ||
+          (2 * w.runs <= w.n_teams && w.W >= 32L * w.n_teams);  // half the teams idle, and long contractions
   return w;
 }
 // when runs are cut: first unit of team g's share (g = n_teams: one past the end)

@@ -142,7 +142,7 @@ int32_t moesd_permute(int32_t E, int32_t K, int32_t T, const int32_t *topk_ids, 
   if (!counts || !offsets || !n_active) return MOESD_INVALID_ARG;
   if (T > 0 && (!topk_ids || !perm || !inv_perm)) return MOESD_INVALID_ARG;
   hipError_t e = launch_permute(topk_ids, (int64_t)T * K, E, K, counts, offsets, perm, inv_perm,
-                                n_active, nullptr, nullptr, (hipStream_t)stream);
+                                n_active, nullptr, nullptr, 0x7fffffff, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e);
   return MOESD_OK;
 }
@@ -167,7 +167,7 @@ int32_t moesd_moe_forward_staged(const moesd_layer_desc *desc, const moesd_weigh
     // nothing to compute; keep the counting outputs well defined if asked for
     if (counts && offsets && n_active) {
       e = launch_permute(nullptr, 0, desc->E, desc->top_k, counts, offsets, nullptr, nullptr,
-                         n_active, nullptr, nullptr, s);
+                         n_active, nullptr, nullptr, 0x7fffffff, s);
       if (e != hipSuccess) return hip_fail(e);
     }
     return MOESD_OK;
@@ -206,8 +206,12 @@ int32_t moesd_moe_forward_staged(const moesd_layer_desc *desc, const moesd_weigh
   } else {
     MOESD_TRY(launch_topk(ws.logits, T, desc->E, desc->top_k, desc->score_func, desc->renormalize,
                           desc->routed_scale, gated ? 1 : 0, ids, w, ws.gate, s))
+    // Experts with 65..128 rows join the tiled kernels' list when at least enough of them exist
+    // for about three quarters of the CUs to get a gate/up tile (128 weight rows each).
+    int tiled_min = 0x7fffffff;
+    if (T > PLAN_BIG_MAX_ROWS) tiled_min = (192 + (desc->inter + 127) / 128 - 1) / ((desc->inter + 127) / 128);
     MOESD_TRY(launch_permute(ids, (int64_t)T * desc->top_k, desc->E, desc->top_k, cnt, off, pm, iv, na,
-                             ws.row_token, ws.plan, s))
+                             ws.row_token, ws.plan, tiled_min, s))
   }
   MOESD_EVENT(1)
 

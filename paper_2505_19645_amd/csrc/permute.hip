@@ -27,11 +27,11 @@ __device__ __forceinline__ void permute_body(
     const int32_t *ids, int64_t n, int E, int K, int nbits, int32_t *__restrict__ counts,
     int32_t *__restrict__ offsets, int32_t *__restrict__ perm, int32_t *__restrict__ inv,
     int32_t *__restrict__ n_active, int32_t *__restrict__ row_token, int32_t *__restrict__ plan,
-    int32_t *smem) {
+    int tiled_min, int32_t *smem) {
   int32_t *hist = smem;                     // [PERM_WAVES][E]
   int32_t *scan = smem + PERM_WAVES * E;    // [PERM_THREADS] scratch for the scan over experts
   __shared__ int32_t wave_tot[4][PERM_WAVES];
-  __shared__ int32_t active_tot;
+  __shared__ int32_t active_tot, mid_tot;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // contiguous segment per wave, a whole number of 64-slot steps
@@ -41,7 +41,10 @@ __device__ __forceinline__ void permute_body(
   const int64_t end = beg + seg < n ? beg + seg : n;
 
   for (int i = tid; i < PERM_WAVES * E; i += PERM_THREADS) hist[i] = 0;
-  if (tid == 0) active_tot = 0;
+  if (tid == 0) {
+    active_tot = 0;
+    mid_tot = 0;
+  }
   __syncthreads();
 
   // pass 1: per-wave histogram
@@ -72,10 +75,18 @@ __device__ __forceinline__ void permute_body(
   // offsets; the others place each expert in the expert kernels' work lists
   // (1..16 rows: "small"; 17..128: one "big" entry per 64-row block; more: one
   // "large" entry per 256-row block)
+  // Experts with 65..128 rows: two passes of the streaming kernel over their weights, or one
+  // 256-row tile of the MFMA kernel that is at most half full.  The tile wins when there are
+  // enough such experts to fill the chip with tiles (tiled_min, from the host; never if the
+  // tiled kernels do not run).
   const int v = (tid < E) ? total : 0;
+  const unsigned long long midb = __ballot(v > 64);
+  if (lane == 0 && midb) atomicAdd(&mid_tot, __popcll(midb));
+  __syncthreads();
+  const int big_max = (mid_tot >= tiled_min) ? 64 : PLAN_BIG_MAX_ROWS;
   const int v_small = (v >= 1 && v <= 16) ? 1 : 0;
-  const int v_big = (v > 16 && v <= PLAN_BIG_MAX_ROWS) ? (v + 63) / 64 : 0;
-  const int v_large = (v > PLAN_BIG_MAX_ROWS) ? (v + 255) / 256 : 0;
+  const int v_big = (v > 16 && v <= big_max) ? (v + 63) / 64 : 0;
+  const int v_large = (v > big_max) ? (v + 255) / 256 : 0;
   int incl = v, incl_s = v_small, incl_b = v_big, incl_l = v_large;
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) {
@@ -168,9 +179,9 @@ __global__ __launch_bounds__(PERM_THREADS) void permute_kernel(
     const int32_t *__restrict__ ids, int64_t n, int E, int K, int nbits,
     int32_t *__restrict__ counts, int32_t *__restrict__ offsets, int32_t *__restrict__ perm,
     int32_t *__restrict__ inv, int32_t *__restrict__ n_active, int32_t *__restrict__ row_token,
-    int32_t *__restrict__ plan) {
+    int32_t *__restrict__ plan, int tiled_min) {
   extern __shared__ int32_t smem[];
-  permute_body(ids, n, E, K, nbits, counts, offsets, perm, inv, n_active, row_token, plan, smem);
+  permute_body(ids, n, E, K, nbits, counts, offsets, perm, inv, n_active, row_token, plan, tiled_min, smem);
 }
 
 // Few tokens: the same workgroup first picks every token's top-K (wave w takes
@@ -189,12 +200,12 @@ __global__ __launch_bounds__(PERM_THREADS) void topk_permute_kernel(
   __threadfence_block();
   __syncthreads();
   permute_body(ids, (int64_t)T * K, E, K, nbits, counts, offsets, perm, inv, n_active, row_token, plan,
-               smem);
+               0x7fffffff, smem);  // few tokens: no expert comes near 64 rows
 }
 
 hipError_t launch_permute(const int32_t *ids, int64_t n, int E, int K, int32_t *counts,
                           int32_t *offsets, int32_t *perm, int32_t *inv, int32_t *n_active,
-                          int32_t *row_token, int32_t *plan, hipStream_t s) {
+                          int32_t *row_token, int32_t *plan, int tiled_min, hipStream_t s) {
   int nbits = 1;
   while ((1 << nbits) < E) ++nbits;
   const size_t smem = sizeof(int32_t) * ((size_t)PERM_WAVES * E + PERM_THREADS);
@@ -204,7 +215,7 @@ hipError_t launch_permute(const int32_t *ids, int64_t n, int E, int K, int32_t *
     if (e != hipSuccess) return e;
   }
   hipLaunchKernelGGL(permute_kernel, dim3(1), dim3(PERM_THREADS), smem, s, ids, n, E, K, nbits,
-                     counts, offsets, perm, inv, n_active, row_token, plan);
+                     counts, offsets, perm, inv, n_active, row_token, plan, tiled_min);
   return hipGetLastError();
 }
 

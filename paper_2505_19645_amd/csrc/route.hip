@@ -18,6 +18,7 @@
 // matrix over E workgroups and no wave walks more than d/2048 dependent steps.
 // ---------------------------------------------------------------------------
 #define RL_TT 8
+#define RL_TILED_MIN_WGS 192  // the register-tiled kernel below runs when it has at least this many workgroups
 
 __device__ __forceinline__ double bf16_pair_lo(uint32_t u) { return (double)__uint_as_float(u << 16); }
 __device__ __forceinline__ double bf16_pair_hi(uint32_t u) { return (double)__uint_as_float(u & 0xFFFF0000u); }
@@ -75,10 +76,105 @@ __global__ __launch_bounds__(256) void router_logits_kernel(
   }
 }
 
+// Many tokens: register-tiled variant.  A wave owns 8 tokens x 8 experts over the whole
+// contraction (lane l takes the 16-byte pieces l, l+64, ...), so a converted token value
+// feeds 8 FMAs and a converted weight value 8 more: a quarter of a conversion per FMA
+// instead of more than one above, and the token rows are read once per 32 experts
+// (the 4 waves of a workgroup take 4 expert blocks of the same 8 tokens).
+// The 64 partial sums of a lane are reduced across the wave by halving: in each of six
+// steps a lane keeps the half of its values that its partner does not, so lane l ends
+// with the full sum of (token l >> 3, expert l & 7) after 63 exchanges.
+#define RLT_TT 8
+#define RLT_EB 8
+__global__ __launch_bounds__(256) void router_logits_tiled_kernel(
+    const uint16_t *__restrict__ x, const uint16_t *__restrict__ wr, const float *__restrict__ bias,
+    const uint16_t *__restrict__ wsg, int T, int d, int E, int Etot, double *__restrict__ logits) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int t0 = blockIdx.x * RLT_TT;
+  const int e0 = (blockIdx.y * 4 + wave) * RLT_EB;
+  if (e0 >= Etot) return;
+  const uint16_t *xrow[RLT_TT];
+  const uint16_t *wrow[RLT_EB];
+#pragma unroll
+  for (int i = 0; i < RLT_TT; ++i) xrow[i] = x + (size_t)min(t0 + i, T - 1) * d;
+#pragma unroll
+  for (int j = 0; j < RLT_EB; ++j) {
+    const int e = min(e0 + j, Etot - 1);
+    wrow[j] = (e < E) ? wr + (size_t)e * d : wsg;
+  }
+  double acc[RLT_TT][RLT_EB];
+#pragma unroll
+  for (int i = 0; i < RLT_TT; ++i)
+#pragma unroll
+    for (int j = 0; j < RLT_EB; ++j) acc[i][j] = 0.0;
+
+  for (int k = lane * 8; k < d; k += 64 * 8) {  // d is a multiple of 8
+    u32x4 xv[RLT_TT], wv[RLT_EB];
+#pragma unroll
+    for (int i = 0; i < RLT_TT; ++i) xv[i] = ld16(xrow[i] + k);
+#pragma unroll
+    for (int j = 0; j < RLT_EB; ++j) wv[j] = ld16(wrow[j] + k);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      double xl[RLT_TT], xh[RLT_TT];
+#pragma unroll
+      for (int i = 0; i < RLT_TT; ++i) {
+        xl[i] = bf16_pair_lo(xv[i][c]);
+        xh[i] = bf16_pair_hi(xv[i][c]);
+      }
+#pragma unroll
+      for (int j = 0; j < RLT_EB; ++j) {
+        const double wl = bf16_pair_lo(wv[j][c]), wh = bf16_pair_hi(wv[j][c]);
+#pragma unroll
+        for (int i = 0; i < RLT_TT; ++i) {
+          acc[i][j] = fma(xl[i], wl, acc[i][j]);
+          acc[i][j] = fma(xh[i], wh, acc[i][j]);
+        }
+      }
+    }
+  }
+  // halving reduction over the 64 lanes; value index v = 8 * token + expert
+  double v[64];
+#pragma unroll
+  for (int i = 0; i < RLT_TT; ++i)
+#pragma unroll
+    for (int j = 0; j < RLT_EB; ++j) v[i * RLT_EB + j] = acc[i][j];
+#pragma unroll
+  for (int step = 0; step < 6; ++step) {
+    const int half = 32 >> step;          // values kept per lane after this step
+    const bool upper = (lane >> (5 - step)) & 1;  // lane bit that decides which half it keeps
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+      if (i < half) {
+        const double keep = upper ? v[i + half] : v[i];
+        const double send = upper ? v[i] : v[i + half];
+        v[i] = keep + __shfl_xor(send, 32 >> step, 64);
+      }
+    }
+  }
+  // lane l now holds value index: bit (5 - step) of l chose the upper half at step `step`,
+  // i.e. index l itself
+  const int ti = lane >> 3, ej = lane & 7;
+  const int t = t0 + ti, e = e0 + ej;
+  if (t < T && e < Etot) {
+    double r = v[0];
+    if (e < E && bias) r += (double)bias[e];
+    logits[(size_t)t * Etot + e] = r;
+  }
+}
+
 hipError_t launch_router_logits(const uint16_t *x, const uint16_t *w_router, const float *bias,
                                 const uint16_t *w_shared_gate, int T, int d, int E, double *logits,
                                 hipStream_t s) {
   const int Etot = E + (w_shared_gate ? 1 : 0);
+  // the tiled kernel has 32x fewer workgroups: only when those still fill the chip
+  const long tiled_wgs = (long)((T + RLT_TT - 1) / RLT_TT) * ((Etot + 4 * RLT_EB - 1) / (4 * RLT_EB));
+  if (tiled_wgs >= RL_TILED_MIN_WGS) {
+    dim3 grid((T + RLT_TT - 1) / RLT_TT, (Etot + 4 * RLT_EB - 1) / (4 * RLT_EB));
+    hipLaunchKernelGGL(router_logits_tiled_kernel, grid, dim3(256), 0, s, x, w_router, bias, w_shared_gate,
+                       T, d, E, Etot, logits);
+    return hipGetLastError();
+  }
   dim3 grid((T + RL_TT - 1) / RL_TT, Etot);
   hipLaunchKernelGGL(router_logits_kernel, grid, dim3(256), 0, s, x, w_router, bias, w_shared_gate, T,
                      d, E, Etot, logits);
