@@ -96,7 +96,12 @@ int64_t moesd_token_threshold(int32_t E, int32_t K, double tau);
 
 /* Bytes of device scratch that moesd_route / moesd_moe_forward need for up to
  * T_max tokens (256-byte aligned pieces; the caller's buffer must itself be
- * 256-byte aligned).  Returns 0 if the descriptor is invalid. */
+ * 256-byte aligned).  Besides the per-token buffers (logits, routing outputs,
+ * the bf16 activation [T*K, I] and the fp32 expert outputs [T*K, d]) it holds,
+ * for T_max > 128, 512 KB per compute unit of partial-sum space for the
+ * MFMA-tiled expert kernels (128 MB on a 256-CU device).  The size depends on
+ * the device the calling thread has current.  Returns 0 if the descriptor is
+ * invalid. */
 size_t moesd_workspace_bytes(const moesd_layer_desc *desc, int32_t T_max);
 
 /* ---------------------------------------------------------------------------
