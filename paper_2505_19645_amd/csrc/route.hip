@@ -18,7 +18,9 @@
 // matrix over E workgroups and no wave walks more than d/2048 dependent steps.
 // ---------------------------------------------------------------------------
 #define RL_TT 8
-#define RL_TILED_MIN_WGS 192  // the register-tiled kernel below runs when it has at least this many workgroups
+// the register-tiled kernels below run when they have at least this many workgroups
+#define RL_TILED8_MIN_WGS 288  // 8 tokens x 8 experts per wave
+#define RL_TILED4_MIN_WGS 192  // 8 tokens x 4 experts per wave
 
 __device__ __forceinline__ double bf16_pair_lo(uint32_t u) { return (double)__uint_as_float(u << 16); }
 __device__ __forceinline__ double bf16_pair_hi(uint32_t u) { return (double)__uint_as_float(u & 0xFFFF0000u); }
@@ -76,16 +78,18 @@ __global__ __launch_bounds__(256) void router_logits_kernel(
   }
 }
 
-// Many tokens: register-tiled variant.  A wave owns 8 tokens x 8 experts over the whole
-// contraction (lane l takes the 16-byte pieces l, l+64, ...), so a converted token value
-// feeds 8 FMAs and a converted weight value 8 more: a quarter of a conversion per FMA
-// instead of more than one above, and the token rows are read once per 32 experts
-// (the 4 waves of a workgroup take 4 expert blocks of the same 8 tokens).
-// The 64 partial sums of a lane are reduced across the wave by halving: in each of six
-// steps a lane keeps the half of its values that its partner does not, so lane l ends
-// with the full sum of (token l >> 3, expert l & 7) after 63 exchanges.
+// Many tokens: register-tiled variant.  A wave owns 8 tokens x RLT_EB (8 or 4) experts over
+// the whole contraction (lane l takes the 16-byte pieces l, l+64, ...), so a converted token
+// value feeds RLT_EB FMAs and a converted weight value 8: a quarter (three eighths) of a
+// conversion per FMA instead of more than one above, and the token rows are read once per
+// 4 * RLT_EB experts (the 4 waves of a workgroup take 4 expert blocks of the same 8 tokens).
+// The narrower block has twice the workgroups, for the sizes where the wider one would leave
+// compute units idle.
+// The partial sums of a lane are reduced across the wave by halving: in each of six
+// steps a lane keeps the half of its (zero-padded to 64) values that its partner does not,
+// so lane l ends with the full sum of value index l = RLT_EB * token + expert.
 #define RLT_TT 8
-#define RLT_EB 8
+template <int RLT_EB>
 __global__ __launch_bounds__(256) void router_logits_tiled_kernel(
     const uint16_t *__restrict__ x, const uint16_t *__restrict__ wr, const float *__restrict__ bias,
     const uint16_t *__restrict__ wsg, int T, int d, int E, int Etot, double *__restrict__ logits) {
@@ -108,23 +112,37 @@ __global__ __launch_bounds__(256) void router_logits_tiled_kernel(
 #pragma unroll
     for (int j = 0; j < RLT_EB; ++j) acc[i][j] = 0.0;
 
-  for (int k = lane * 8; k < d; k += 64 * 8) {  // d is a multiple of 8
-    u32x4 xv[RLT_TT], wv[RLT_EB];
+  // the pieces of the next step are fetched before the FMAs of the current one
+  u32x4 xv[RLT_TT], wv[RLT_EB];
+  {
+    const int k = min(lane * 8, d - 8);
 #pragma unroll
     for (int i = 0; i < RLT_TT; ++i) xv[i] = ld16(xrow[i] + k);
 #pragma unroll
     for (int j = 0; j < RLT_EB; ++j) wv[j] = ld16(wrow[j] + k);
+  }
+  for (int k = lane * 8; k < d; k += 64 * 8) {  // d is a multiple of 8
+    u32x4 xc[RLT_TT], wc[RLT_EB];
+#pragma unroll
+    for (int i = 0; i < RLT_TT; ++i) xc[i] = xv[i];
+#pragma unroll
+    for (int j = 0; j < RLT_EB; ++j) wc[j] = wv[j];
+    const int kn = min(k + 64 * 8, d - 8);  // (a step past the end re-reads the last piece; unused)
+#pragma unroll
+    for (int i = 0; i < RLT_TT; ++i) xv[i] = ld16(xrow[i] + kn);
+#pragma unroll
+    for (int j = 0; j < RLT_EB; ++j) wv[j] = ld16(wrow[j] + kn);
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       double xl[RLT_TT], xh[RLT_TT];
 #pragma unroll
       for (int i = 0; i < RLT_TT; ++i) {
-        xl[i] = bf16_pair_lo(xv[i][c]);
-        xh[i] = bf16_pair_hi(xv[i][c]);
+        xl[i] = bf16_pair_lo(xc[i][c]);
+        xh[i] = bf16_pair_hi(xc[i][c]);
       }
 #pragma unroll
       for (int j = 0; j < RLT_EB; ++j) {
-        const double wl = bf16_pair_lo(wv[j][c]), wh = bf16_pair_hi(wv[j][c]);
+        const double wl = bf16_pair_lo(wc[j][c]), wh = bf16_pair_hi(wc[j][c]);
 #pragma unroll
         for (int i = 0; i < RLT_TT; ++i) {
           acc[i][j] = fma(xl[i], wl, acc[i][j]);
@@ -133,8 +151,11 @@ __global__ __launch_bounds__(256) void router_logits_tiled_kernel(
       }
     }
   }
-  // halving reduction over the 64 lanes; value index v = 8 * token + expert
+  // halving reduction over the 64 lanes; value index v = RLT_EB * token + expert, the
+  // values beyond RLT_TT * RLT_EB are zero padding
   double v[64];
+#pragma unroll
+  for (int i = 0; i < 64; ++i) v[i] = 0.0;
 #pragma unroll
   for (int i = 0; i < RLT_TT; ++i)
 #pragma unroll
@@ -154,9 +175,9 @@ __global__ __launch_bounds__(256) void router_logits_tiled_kernel(
   }
   // lane l now holds value index: bit (5 - step) of l chose the upper half at step `step`,
   // i.e. index l itself
-  const int ti = lane >> 3, ej = lane & 7;
+  const int ti = lane / RLT_EB, ej = lane % RLT_EB;
   const int t = t0 + ti, e = e0 + ej;
-  if (t < T && e < Etot) {
+  if (ti < RLT_TT && t < T && e < Etot) {
     double r = v[0];
     if (e < E && bias) r += (double)bias[e];
     logits[(size_t)t * Etot + e] = r;
@@ -167,12 +188,17 @@ hipError_t launch_router_logits(const uint16_t *x, const uint16_t *w_router, con
                                 const uint16_t *w_shared_gate, int T, int d, int E, double *logits,
                                 hipStream_t s) {
   const int Etot = E + (w_shared_gate ? 1 : 0);
-  // the tiled kernel has 32x fewer workgroups: only when those still fill the chip
-  const long tiled_wgs = (long)((T + RLT_TT - 1) / RLT_TT) * ((Etot + 4 * RLT_EB - 1) / (4 * RLT_EB));
-  if (tiled_wgs >= RL_TILED_MIN_WGS) {
-    dim3 grid((T + RLT_TT - 1) / RLT_TT, (Etot + 4 * RLT_EB - 1) / (4 * RLT_EB));
-    hipLaunchKernelGGL(router_logits_tiled_kernel, grid, dim3(256), 0, s, x, w_router, bias, w_shared_gate,
-                       T, d, E, Etot, logits);
+  // the tiled kernels have 16x or 32x fewer workgroups: only when those still fill the chip
+  const int tb = (T + RLT_TT - 1) / RLT_TT;
+  const int eb8 = (Etot + 31) / 32, eb4 = (Etot + 15) / 16;
+  if ((long)tb * eb8 >= RL_TILED8_MIN_WGS) {
+    hipLaunchKernelGGL(router_logits_tiled_kernel<8>, dim3(tb, eb8), dim3(256), 0, s, x, w_router, bias,
+                       w_shared_gate, T, d, E, Etot, logits);
+    return hipGetLastError();
+  }
+  if ((long)tb * eb4 >= RL_TILED4_MIN_WGS) {
+    hipLaunchKernelGGL(router_logits_tiled_kernel<4>, dim3(tb, eb4), dim3(256), 0, s, x, w_router, bias,
+                       w_shared_gate, T, d, E, Etot, logits);
     return hipGetLastError();
   }
   dim3 grid((T + RL_TT - 1) / RL_TT, Etot);
