@@ -58,6 +58,10 @@
 #define KBW 128
 #define ROWW_BYTES 256
 #define WIDE_B_OFF 8192    // second slot: weight rows 96..127, then the 64 token rows
+// the schedule's cost model, in hundredths of a routed expert's small slot
+#define COST_WIDE_SLOT 140
+#define COST_CLASS_SWITCH 1300
+#define COST_DISTINCT_ROWS 15
 
 enum { MODE_GATE_UP = 0, MODE_DOWN = 1 };
 
@@ -660,27 +664,40 @@ __global__ __launch_bounds__(256) void expert_stream_kernel(StreamArgs a,
   const int n_wide = cw.n_sh + n_big_e * cw.per_r;
   const int n_small = cs.n_sh + n_small_e * cs.per_r;
   {
-    // cost in slots: a small tile is nkb slots, a wide tile 2*nkbw (same weight bytes per slot)
+    // Wide tiles are dealt round-robin; the small line is then cut so that every workgroup's
+    // estimated time is the same.  Costs in hundredths of the time of one small slot of a routed
+    // expert, from per-workgroup timelines on the MI355X: a wide slot moves the same bytes as a
+    // small one but takes 1.4x as long (more LDS traffic per byte), moving from the wide to the
+    // small class drains and refills the ring (about 13 slots), and a small slot whose 16 token
+    // rows are all distinct (the shared expert at T = 16) takes 1.15x as long as one with a few.
     const int kr = (MODE == MODE_GATE_UP) ? a.d : a.I;
-    const long c_small = (kr + KB - 1) / KB;
-    const long c_wide = 2 * ((kr + KBW - 1) / KBW);
-    const long C = n_wide * c_wide + n_small * c_small;  // total
-    // wide tiles round-robin; the small line is cut in proportion to what is left of
-    // each workgroup's equal share (all quantities scaled by G)
+    const long nkb_s = (kr + KB - 1) / KB, nkb_w = (kr + KBW - 1) / KBW;
+    const long c_wide = 2 * nkb_w * COST_WIDE_SLOT;
+    const long c_sh = nkb_s * (100 + COST_DISTINCT_ROWS * min(a.T, SMALL_M) / SMALL_M);
+    const long c_r = nkb_s * 100;
+    const long n_shs = cs.n_sh, n_rs = n_small - cs.n_sh;
+    const long S = n_shs * c_sh + n_rs * c_r;  // the small line
     const int k = n_wide / G, rem = n_wide % G;
+    const long sw = S > 0 ? COST_CLASS_SWITCH : 0;
+    const long C = n_wide * c_wide + (k > 0 ? G : rem) * sw + S;
     cw.n_mine = k + (bid < rem ? 1 : 0);
     cw.id0 = bid;
     cw.stride = G;
-    const long r_hi = max(0L, C - (long)(k + 1) * c_wide * G);
-    const long r_lo = max(0L, C - (long)k * c_wide * G);
-    const long p0 = (long)min(bid, rem) * r_hi + (long)max(0, bid - rem) * r_lo;
-    const long p1 = (long)min(bid + 1, rem) * r_hi + (long)max(0, bid + 1 - rem) * r_lo;
+    // what is left of a workgroup's equal share for small tiles (all quantities scaled by G)
+    const long r_hi = max(0L, C - ((k + 1) * c_wide + sw) * G);
+    const long r_lo = max(0L, C - (k * c_wide + (k > 0 ? sw : 0)) * G);
     const long p_tot = (long)rem * r_hi + (long)(G - rem) * r_lo;
-    int sb0 = 0, sb1 = 0;
-    if (p_tot > 0) {
-      sb0 = (int)((long)n_small * p0 / p_tot);
-      sb1 = (int)((long)n_small * p1 / p_tot);
-    }
+    // first small tile of workgroup b: the tile at cost position S * p(b) / p_tot of the line
+    auto first_small = [&](int b) -> int {
+      if (p_tot <= 0 || b <= 0) return 0;
+      if (b >= G) return n_small;
+      const long pb = (long)min(b, rem) * r_hi + (long)max(0, b - rem) * r_lo;
+      const double x = (double)S * (double)pb / (double)p_tot;
+      const double head = (double)(n_shs * c_sh);
+      const double t = x <= head ? x / (double)c_sh : (double)n_shs + (x - head) / (double)c_r;
+      return min((int)t, n_small);
+    };
+    const int sb0 = p_tot > 0 ? first_small(bid) : 0, sb1 = p_tot > 0 ? first_small(bid + 1) : 0;
     cs.n_mine = sb1 - sb0;
     cs.id0 = sb0;
     cs.stride = 1;
