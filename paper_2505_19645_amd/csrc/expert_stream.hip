@@ -59,7 +59,7 @@
 #define ROWW_BYTES 256
 #define WIDE_B_OFF 8192    // second slot: weight rows 96..127, then the 64 token rows
 // the schedule's cost model, in hundredths of a routed expert's small slot
-#define COST_WIDE_SLOT 140
+#define COST_WIDE_SLOT 120
 #define COST_CLASS_SWITCH 1300
 #define COST_DISTINCT_ROWS 15
 
@@ -477,11 +477,12 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
     pend = false;
   };
 
-  for (int i = 0; i < AHEAD && l_live; ++i) advance_load();
+  constexpr int AH = AHEAD;  // (5 of the 6 slots in flight for the small tiles measured the same)
+  for (int i = 0; i < AH && l_live; ++i) advance_load();
 
   while (true) {
-    // slot c_slot must have landed: at most AHEAD-1 younger slots may be pending
-    if (l_slot - c_slot == AHEAD) wait_vm<(AHEAD - 1) * LW>();
+    // slot c_slot must have landed: at most AH-1 younger slots may be pending
+    if (l_slot - c_slot == AH) wait_vm<(AH - 1) * LW>();
     else wait_vm<0>();
     wg_barrier();
     if (l_live) advance_load();
@@ -667,7 +668,7 @@ __global__ __launch_bounds__(256) void expert_stream_kernel(StreamArgs a,
     // Wide tiles are dealt round-robin; the small line is then cut so that every workgroup's
     // estimated time is the same.  Costs in hundredths of the time of one small slot of a routed
     // expert, from per-workgroup timelines on the MI355X: a wide slot moves the same bytes as a
-    // small one but takes 1.4x as long (more LDS traffic per byte), moving from the wide to the
+    // small one but takes about 1.2x as long (more LDS traffic per byte), moving from the wide to the
     // small class drains and refills the ring (about 13 slots), and a small slot whose 16 token
     // rows are all distinct (the shared expert at T = 16) takes 1.15x as long as one with a few.
     const int kr = (MODE == MODE_GATE_UP) ? a.d : a.I;
