@@ -16,7 +16,7 @@ class OracleDesc(C.Structure):
     _fields_ = [("d", C.c_int32), ("E", C.c_int32), ("top_k", C.c_int32), ("inter", C.c_int32),
                 ("shared_inter", C.c_int32), ("score_func", C.c_int32),
                 ("renormalize", C.c_int32), ("shared_gate", C.c_int32),
-                ("routed_scale", C.c_double)]
+                ("routed_scale", C.c_double), ("n_group", C.c_int32), ("topk_group", C.c_int32)]
 
 
 _lib = None
@@ -31,6 +31,7 @@ def lib():
         L.oracle_expected_active_experts.argtypes = [C.c_int32, C.c_int32, C.c_int64]
         L.oracle_expected_tokens_per_expert.restype = C.c_double
         L.oracle_expected_tokens_per_expert.argtypes = [C.c_int32, C.c_int32, C.c_int64]
+        L.oracle_expected_active_experts_p.restype = C.c_double
         L.oracle_token_threshold.restype = C.c_int64
         L.oracle_token_threshold.argtypes = [C.c_int32, C.c_int32, C.c_double]
         L.oracle_route.restype = C.c_int32
@@ -60,11 +61,18 @@ def desc_of(shape) -> OracleDesc:
     renormalize, shared_gate, routed_scale attributes."""
     return OracleDesc(shape.d, shape.E, shape.top_k, shape.inter, shape.shared_inter,
                       shape.score_func, shape.renormalize, shape.shared_gate,
-                      float(shape.routed_scale))
+                      float(shape.routed_scale), int(getattr(shape, "n_group", 0)),
+                      int(getattr(shape, "topk_group", 0)))
 
 
 def expected_active_experts(E, K, t):
     return lib().oracle_expected_active_experts(E, K, t)
+
+
+def expected_active_experts_p(p, t):
+    """N(t) for per-expert activation probabilities p (sums to K): sum_e 1 - (1 - p_e)^t."""
+    p = np.ascontiguousarray(p, np.float64)
+    return lib().oracle_expected_active_experts_p(_p(p), C.c_int32(p.size), C.c_int64(t))
 
 
 def expected_tokens_per_expert(E, K, t):

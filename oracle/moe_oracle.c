@@ -16,6 +16,13 @@
  *   key[t,e]   = fp32(logit[t,e])                       (one rounding)
  *   ids[t,:]   = the K experts with the largest key, equal keys -> lower index,
  *                listed in that order
+ *                (group-limited variant, n_group > 1: the E experts form n_group
+ *                equal consecutive groups; a group's score is the sum of the scores
+ *                of its two members with the largest key, rounded once to fp32; the
+ *                topk_group groups with the largest group score, equal -> lower
+ *                index, stay; ids are taken among their members only.  This is the
+ *                routing rule published for the model family of benchmark config 4,
+ *                without its selection bias.)
  *   score      = softmax over all E of logit, or sigmoid(logit)
  *   w[t,s]     = score[ids[t,s]] / sum_s' score[ids[t,s']]   (if renormalize)
  *                times routed_scale
@@ -33,7 +40,9 @@
  * Pins (tests/test_oracle_*.py): brute-force subset routing on tiny inputs,
  * sum_s w = 1, numpy stable argsort for the permutation, reductions to plain
  * matrix products (E=1,K=1; K=E; identical experts; expert relabelling), the
- * closed form N(t) against Monte-Carlo and against exact enumeration.
+ * closed form N(t) against Monte-Carlo and against exact enumeration; the
+ * group-limited rule against a sort-based restatement, a hand-made case and
+ * its two degenerate settings (one group; all groups kept).
  * Absolute output values have no worked example in the paper: they are pinned
  * only through those reductions ("parity unpinned" by the paper itself).
  */
@@ -48,6 +57,8 @@ typedef struct {
   int32_t renormalize;
   int32_t shared_gate;
   double  routed_scale;
+  int32_t n_group;     /* 0 or 1: no groups */
+  int32_t topk_group;  /* groups kept per token */
 } oracle_desc;
 
 /* bf16 word -> double (exact) */
@@ -93,6 +104,20 @@ double oracle_expected_active_experts(int32_t E, int32_t K, int64_t t) {
   return (double)E * (1.0 - pow((double)(E - K) / (double)E, (double)t));
 }
 
+/* N(t) without the uniformity assumption.  The step before Eq. N(t) (an expert is
+ * activated unless none of the t tokens activates it) holds for every expert on its
+ * own: with p[e] the probability that one token activates expert e (sum_e p[e] = K)
+ * and independent tokens, N(t) = sum_e (1 - (1 - p[e])^t).  p[e] = K/E gives Eq. N(t). */
+double oracle_expected_active_experts_p(const double *p, int32_t E, int64_t t) {
+  if (E < 1 || t < 0 || !p) return NAN;
+  double n = 0.0;
+  for (int e = 0; e < E; ++e) {
+    if (!(p[e] >= 0.0) || !(p[e] <= 1.0)) return NAN;
+    n += 1.0 - pow(1.0 - p[e], (double)t);
+  }
+  return n;
+}
+
 /* Eq. Texp */
 double oracle_expected_tokens_per_expert(int32_t E, int32_t K, int64_t t) {
   if (E < 1 || K < 0 || K > E || t < 0) return NAN;
@@ -119,7 +144,11 @@ int32_t oracle_route(const oracle_desc *c, const uint16_t *x, const uint16_t *wr
                      const float *bias, int32_t T, double *logits_out, int32_t *ids,
                      double *w) {
   const int E = c->E, K = c->top_k, d = c->d;
-  if (E < 1 || K < 1 || K > E || T < 0) return 1;
+  if (E < 1 || K < 1 || K > E || T < 0 || c->n_group > 1024) return 1;
+  const int G = c->n_group > 1 ? c->n_group : 1;
+  const int Gk = G > 1 ? c->topk_group : 1;
+  if (E % G != 0 || Gk < 1 || Gk > G || K > Gk * (E / G)) return 1;
+  const int gs = E / G;
 #pragma omp parallel
   {
     double *l = (double *)malloc(sizeof(double) * E);
@@ -146,6 +175,29 @@ int32_t oracle_route(const oracle_desc *c, const uint16_t *x, const uint16_t *wr
       }
       /* K rounds of "largest remaining key, first index on equality" */
       memset(taken, 0, E);
+      if (G > 1) {
+        /* group-limited selection: everything outside the kept groups is "taken" */
+        float gkey[1024];
+        char gkeep[1024];
+        for (int g = 0; g < G; ++g) {
+          int a = -1, b = -1; /* the two largest keys of the group, first index on equality */
+          for (int e = g * gs; e < (g + 1) * gs; ++e) {
+            if (a < 0 || key[e] > key[a]) { b = a; a = e; }
+            else if (b < 0 || key[e] > key[b]) b = e;
+          }
+          gkey[g] = (float)(p[a] + (b >= 0 ? p[b] : 0.0));
+          gkeep[g] = 0;
+        }
+        for (int s = 0; s < Gk; ++s) {
+          int best = -1;
+          for (int g = 0; g < G; ++g) {
+            if (gkeep[g]) continue;
+            if (best < 0 || gkey[g] > gkey[best]) best = g;
+          }
+          gkeep[best] = 1;
+        }
+        for (int e = 0; e < E; ++e) taken[e] = !gkeep[e / gs];
+      }
       for (int s = 0; s < K; ++s) {
         int best = -1;
         for (int e = 0; e < E; ++e) {

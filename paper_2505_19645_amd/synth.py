@@ -46,6 +46,8 @@ class LayerShape:
     shared_gate: int = 0
     routed_scale: float = 1.0
     seed: int = 0
+    n_group: int = 0      # > 1: group-limited selection (E experts in n_group consecutive groups)
+    topk_group: int = 0   # groups kept per token
 
     @property
     def expert_bytes(self) -> int:
