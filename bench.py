@@ -242,11 +242,61 @@ def mode_ksweep(args, shape, torch, moesd, synth):
                       "sweep": out}))
 
 
+def mode_routing(args, shape, torch, moesd, synth):
+    """Activated experts under routing variants, router only (moesd_route + moesd_permute): unconstrained,
+    group-limited (8 groups, 4 kept, when E allows) and a skewed router; the measured mean count over independent
+    batches against Eq. N(t) (Sec. 3.2) and against its per-expert form with probabilities measured on a
+    separate sample."""
+    import dataclasses
+    import numpy as np
+    dev = "cuda:0"
+    variants = [("uniform", shape, 0.0)]
+    if shape.E % 8 == 0 and shape.top_k <= 4 * (shape.E // 8):
+        variants.append(("group-limited 8/4", dataclasses.replace(shape, n_group=8, topk_group=4), 0.0))
+    variants.append(("skewed (bias std 1.0)", shape, 1.0))
+    Ts = (1, 4, 16, 64, 256)
+    n_sample, per_T = 8192, 4096
+    out = []
+    for label, sh, skew in variants:
+        r = synth.make_router(sh, skew)
+        desc = moesd.make_desc(sh)
+        wr = torch.from_numpy(r["w_router"].view(np.int16)).to(dev)
+        bias = None if r["router_bias"] is None else torch.from_numpy(r["router_bias"]).to(dev)
+
+        def route(n, point):
+            x = torch.from_numpy(synth.make_tokens(sh, n, point=point).view(np.int16)).to(dev)
+            ids = torch.empty((n, sh.top_k), dtype=torch.int32, device=dev)
+            w = torch.empty((n, sh.top_k), dtype=torch.float32, device=dev)
+            ws = torch.empty(max(moesd.moesd_workspace_bytes(desc, n), 256), dtype=torch.uint8, device=dev)
+            moesd.moesd_route(desc, x, wr, bias, n, ids, w, ws)
+            return ids.cpu().numpy()
+
+        p = np.bincount(route(n_sample, 7001).ravel(), minlength=sh.E) / float(n_sample)
+        ids = route(per_T, 7002)
+        rows = []
+        for T in Ts:
+            nb = per_T // T
+            n_act = np.array([len(np.unique(ids[i * T:(i + 1) * T])) for i in range(nb)], np.float64)
+            rows.append({"T": T, "batches": nb, "n_active_mean": round(float(n_act.mean()), 3),
+                         "n_active_sem": round(float(n_act.std(ddof=1) / np.sqrt(nb)), 3) if nb > 1 else None,
+                         "N_uniform": round(moesd.moesd_expected_active_experts(sh.E, sh.top_k, T), 3),
+                         "N_measured_p": round(moesd.moesd_expected_active_experts_p(p.tolist(), T), 3)})
+        out.append({"variant": label, "p_min": round(float(p.min()), 5), "p_max": round(float(p.max()), 5),
+                    "p_uniform": round(sh.top_k / sh.E, 5), "rows": rows})
+        log(f"[bench] {label}: " + ", ".join(f"T={r_['T']}: {r_['n_active_mean']} (uniform {r_['N_uniform']}, "
+                                             f"per-expert {r_['N_measured_p']})" for r_ in rows))
+    print(json.dumps({"metric": "activated experts vs Eq. N(t) under routing variants", "unit": "experts", "n_gpus": 1,
+                      "data": "synthetic", "dtype": "f64",
+                      "config": {"workload": f"{shape.name}-shaped router, {per_T} tokens cut into batches of T"},
+                      "variants": out}))
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--mode", choices=["headline", "dense", "ksweep"], default="headline",
+    ap.add_argument("--mode", choices=["headline", "dense", "ksweep", "routing"], default="headline",
                     help="headline: the benchmark line; dense: MoE vs dense-equivalent target efficiency; "
-                         "ksweep: target efficiency for K = 1..32 (use --config qwen2-57b-a14b)")
+                         "ksweep: target efficiency for K = 1..32 (use --config qwen2-57b-a14b); "
+                         "routing: activated experts under routing variants (use --config deepseek-v3)")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
@@ -287,6 +337,8 @@ def main():
         return mode_dense(args, shape, torch, moesd, synth)
     if args.mode == "ksweep":
         return mode_ksweep(args, shape, torch, moesd, synth)
+    if args.mode == "routing":
+        return mode_routing(args, shape, torch, moesd, synth)
 
     t0 = time.time()
     host_w = synth.make_layer(shape, skew_std=args.skew, threads=min(16, os.cpu_count() or 1))

@@ -58,6 +58,8 @@ typedef struct {
   int32_t renormalize;  /* 1: top-k scores are divided by their sum              */
   int32_t shared_gate;  /* 1: shared expert scaled by sigmoid(x . w_shared_gate) */
   float   routed_scale; /* multiplies every routed weight (1.0 = none)           */
+  int32_t n_group;      /* > 1: group-limited selection, see moesd_route; else off */
+  int32_t topk_group;   /* groups kept per token (1 .. n_group)                    */
 } moesd_layer_desc;
 
 /* All weights: device pointers, bf16, read-only, caller-owned. */
@@ -80,6 +82,14 @@ typedef struct {
 /* Expected number of activated experts after t tokens under uniform routing,
  * Eq. N(t):  E * (1 - ((E-K)/E)^t).  NaN if E<1, K<0, K>E or t<0. */
 double moesd_expected_active_experts(int32_t E, int32_t K, int64_t t);
+
+/* The same expectation without the uniformity assumption that Sec. 3.2 makes:
+ * the step before Eq. N(t) (an expert is activated unless none of the t tokens
+ * activates it) applied to each expert with its own probability p[e] of being
+ * activated by one token (host array of E values in [0,1], summing to K), tokens
+ * independent:  sum_e (1 - (1 - p[e])^t).  p[e] = K/E gives Eq. N(t); any other p
+ * with the same sum gives less.  NaN on bad input. */
+double moesd_expected_active_experts_p(const double *p, int32_t E, int64_t t);
 
 /* Mean tokens per activated expert, Eq. Texp:  t*K / N(t)  =
  * rho*t / (1 - (1-rho)^t).  Returns 0 for t == 0 or K == 0; NaN on bad input. */
@@ -116,6 +126,14 @@ size_t moesd_workspace_bytes(const moesd_layer_desc *desc, int32_t T_max);
  * (descending key, ascending index) order.  Weights are softmax-over-E or
  * sigmoid scores of the winners, optionally divided by their sum, times
  * routed_scale.
+ * With desc->n_group > 1 the selection is group-limited (the rule published for
+ * the model family of benchmark config 4, without its selection bias; Sec. 3.2
+ * models unconstrained selection): the experts form n_group equal consecutive
+ * groups (E divisible by n_group, n_group <= 64), a group's score is the sum of
+ * the scores of its two members with the largest keys, rounded once to fp32,
+ * the topk_group groups with the largest score stay (equal scores: the lower
+ * group index) and the K winners are taken among their members
+ * (K <= topk_group * E / n_group).
  *   x          device [T, d] bf16
  *   w_router   device [E, d] bf16;  router_bias device [E] fp32 or NULL
  *   topk_ids   device [T, K] int32 (out);  topk_w  device [T, K] fp32 (out)

@@ -13,7 +13,8 @@ LIB_PATH = os.path.join(HERE, "libmoesd.so")
 OK, INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP_ERROR = 0, 1, 2, 3, 4
 N_STAGE_EVENTS = 5
 
-EXPORTS = ["moesd_expected_active_experts", "moesd_expected_tokens_per_expert",
+EXPORTS = ["moesd_expected_active_experts", "moesd_expected_active_experts_p",
+           "moesd_expected_tokens_per_expert",
            "moesd_token_threshold", "moesd_workspace_bytes", "moesd_route", "moesd_permute",
            "moesd_moe_forward", "moesd_moe_forward_staged", "moesd_status_string",
            "moesd_last_hip_error"]
@@ -22,7 +23,8 @@ EXPORTS = ["moesd_expected_active_experts", "moesd_expected_tokens_per_expert",
 class LayerDesc(C.Structure):
     _fields_ = [("d", C.c_int32), ("E", C.c_int32), ("top_k", C.c_int32), ("inter", C.c_int32),
                 ("shared_inter", C.c_int32), ("score_func", C.c_int32), ("renormalize", C.c_int32),
-                ("shared_gate", C.c_int32), ("routed_scale", C.c_float)]
+                ("shared_gate", C.c_int32), ("routed_scale", C.c_float), ("n_group", C.c_int32),
+                ("topk_group", C.c_int32)]
 
 
 class Weights(C.Structure):
@@ -51,6 +53,8 @@ def lib():
         L = C.CDLL(LIB_PATH)
         L.moesd_expected_active_experts.restype = C.c_double
         L.moesd_expected_active_experts.argtypes = [C.c_int32, C.c_int32, C.c_int64]
+        L.moesd_expected_active_experts_p.restype = C.c_double
+        L.moesd_expected_active_experts_p.argtypes = [C.POINTER(C.c_double), C.c_int32, C.c_int64]
         L.moesd_expected_tokens_per_expert.restype = C.c_double
         L.moesd_expected_tokens_per_expert.argtypes = [C.c_int32, C.c_int32, C.c_int64]
         L.moesd_token_threshold.restype = C.c_int64
@@ -89,7 +93,8 @@ def make_desc(shape) -> LayerDesc:
     shared_gate, routed_scale (e.g. synth.LayerShape)."""
     return LayerDesc(shape.d, shape.E, shape.top_k, shape.inter, shape.shared_inter,
                      shape.score_func, shape.renormalize, shape.shared_gate,
-                     float(shape.routed_scale))
+                     float(shape.routed_scale), int(getattr(shape, "n_group", 0)),
+                     int(getattr(shape, "topk_group", 0)))
 
 
 def _ptr(t):
@@ -122,6 +127,12 @@ def make_weights(w: dict) -> Weights:
 
 def moesd_expected_active_experts(E: int, K: int, t: int) -> float:
     return lib().moesd_expected_active_experts(E, K, t)
+
+
+def moesd_expected_active_experts_p(p, t: int) -> float:
+    """p: per-expert probabilities of being activated by one token (any sequence of floats)."""
+    arr = (C.c_double * len(p))(*[float(v) for v in p])
+    return lib().moesd_expected_active_experts_p(arr, len(p), t)
 
 
 def moesd_expected_tokens_per_expert(E: int, K: int, t: int) -> float:

@@ -15,6 +15,18 @@ double moesd_expected_active_experts(int32_t E, int32_t K, int64_t t) {
   return (double)E * -std::expm1(log_miss);
 }
 
+// The per-expert form of the step before Eq. N(t): expert e is missed by one token
+// with probability 1 - p[e].
+double moesd_expected_active_experts_p(const double *p, int32_t E, int64_t t) {
+  if (!p || E < 1 || t < 0) return std::numeric_limits<double>::quiet_NaN();
+  double n = 0.0;
+  for (int32_t e = 0; e < E; ++e) {
+    if (!(p[e] >= 0.0) || !(p[e] <= 1.0)) return std::numeric_limits<double>::quiet_NaN();
+    n += p[e] >= 1.0 ? (t > 0 ? 1.0 : 0.0) : -std::expm1((double)t * std::log1p(-p[e]));
+  }
+  return n;
+}
+
 // Eq. Texp: t*K routed rows spread over N(t) activated experts.
 double moesd_expected_tokens_per_expert(int32_t E, int32_t K, int64_t t) {
   if (E < 1 || K < 0 || K > E || t < 0) return std::numeric_limits<double>::quiet_NaN();

@@ -79,9 +79,10 @@ struct StreamArgs {
 hipError_t launch_router_logits(const uint16_t *x, const uint16_t *w_router, const float *bias,
                                 const uint16_t *w_shared_gate, int T, int d, int E, double *logits,
                                 hipStream_t s);
+// groups = n_group | topk_group << 16 (0: unconstrained selection)
 hipError_t launch_topk(const double *logits, int T, int E, int K, int score_func, int renorm,
-                       float scale, int has_shared_gate, int32_t *ids, float *w, float *gate,
-                       hipStream_t s);
+                       float scale, int groups, int has_shared_gate, int32_t *ids, float *w,
+                       float *gate, hipStream_t s);
 // row_token / plan may be NULL (standalone permutation).  tiled_min: experts with 65..128 rows
 // go to the tiled kernels' list if at least that many experts have more than 64 rows
 // (INT_MAX: never).
@@ -90,8 +91,8 @@ hipError_t launch_permute(const int32_t *ids, int64_t n, int E, int K, int32_t *
                           int32_t *row_token, int32_t *plan, int tiled_min, hipStream_t s);
 // top-K and permutation in one launch; only for E <= 256 and few tokens
 hipError_t launch_topk_permute(const double *logits, int T, int E, int K, int score_func, int renorm,
-                               float scale, int has_shared_gate, int32_t *ids, float *w, float *gate,
-                               int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv,
+                               float scale, int groups, int has_shared_gate, int32_t *ids, float *w,
+                               float *gate, int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv,
                                int32_t *n_active, int32_t *row_token, int32_t *plan, hipStream_t s);
 hipError_t launch_gate_up(const StreamArgs &a, hipStream_t s);
 hipError_t launch_down(const StreamArgs &a, hipStream_t s);

@@ -21,6 +21,12 @@ int32_t check_desc(const moesd_layer_desc *c) {
   if (c->d < 8 || c->d % 8 || c->inter < 8 || c->inter % 8) return MOESD_INVALID_ARG;
   if (c->shared_inter < 0 || c->shared_inter % 8) return MOESD_INVALID_ARG;
   if (c->E > MOESD_MAX_E || c->top_k > MOESD_MAX_K) return MOESD_UNSUPPORTED;
+  if (c->n_group > 1) {
+    if (c->E % c->n_group != 0 || c->topk_group < 1 || c->topk_group > c->n_group ||
+        (int64_t)c->top_k > (int64_t)c->topk_group * (c->E / c->n_group))
+      return MOESD_INVALID_ARG;
+    if (c->n_group > 64) return MOESD_UNSUPPORTED;
+  }
   if (c->score_func != MOESD_SCORE_SOFTMAX && c->score_func != MOESD_SCORE_SIGMOID)
     return MOESD_UNSUPPORTED;
   if ((c->renormalize | 1) != 1 || (c->shared_gate | 1) != 1) return MOESD_UNSUPPORTED;
@@ -50,6 +56,11 @@ struct Workspace {
   int32_t part_k, parts;
   size_t bytes;
 };
+
+// the group-limited selection's two settings in one launch argument (0: unconstrained)
+inline int groups_of(const moesd_layer_desc *c) {
+  return c->n_group > 1 ? (c->n_group | (c->topk_group << 16)) : 0;
+}
 
 // The shared expert's down projection is cut along its intermediate dimension
 // into parts about as long as a routed expert's, so that every tile of the down
@@ -128,7 +139,7 @@ int32_t moesd_route(const moesd_layer_desc *desc, const void *x, const void *w_r
                                       nullptr, T, desc->d, desc->E, ws.logits, s);
   if (e != hipSuccess) return hip_fail(e);
   e = launch_topk(ws.logits, T, desc->E, desc->top_k, desc->score_func, desc->renormalize,
-                  desc->routed_scale, 0, topk_ids, topk_w, nullptr, s);
+                  desc->routed_scale, groups_of(desc), 0, topk_ids, topk_w, nullptr, s);
   if (e != hipSuccess) return hip_fail(e);
   return MOESD_OK;
 }
@@ -201,11 +212,11 @@ int32_t moesd_moe_forward_staged(const moesd_layer_desc *desc, const moesd_weigh
                                  T, desc->d, desc->E, ws.logits, s))
   if (T <= 32 && desc->E <= 256) {
     MOESD_TRY(launch_topk_permute(ws.logits, T, desc->E, desc->top_k, desc->score_func,
-                                  desc->renormalize, desc->routed_scale, gated ? 1 : 0, ids, w, ws.gate,
-                                  cnt, off, pm, iv, na, ws.row_token, ws.plan, s))
+                                  desc->renormalize, desc->routed_scale, groups_of(desc), gated ? 1 : 0, ids, w,
+                                  ws.gate, cnt, off, pm, iv, na, ws.row_token, ws.plan, s))
   } else {
     MOESD_TRY(launch_topk(ws.logits, T, desc->E, desc->top_k, desc->score_func, desc->renormalize,
-                          desc->routed_scale, gated ? 1 : 0, ids, w, ws.gate, s))
+                          desc->routed_scale, groups_of(desc), gated ? 1 : 0, ids, w, ws.gate, s))
     // Experts with 65..128 rows join the tiled kernels' list when at least enough of them exist
     // for about three quarters of the CUs to get a gate/up tile (128 weight rows each).
     int tiled_min = 0x7fffffff;

@@ -189,14 +189,14 @@ __global__ __launch_bounds__(PERM_THREADS) void permute_kernel(
 template <int SLOTS>
 __global__ __launch_bounds__(PERM_THREADS) void topk_permute_kernel(
     const double *__restrict__ logits, int T, int E, int Etot, int K, int score_func, int renorm,
-    float scale, int32_t *ids, float *__restrict__ w, float *__restrict__ gate, int nbits,
+    float scale, int groups, int32_t *ids, float *__restrict__ w, float *__restrict__ gate, int nbits,
     int32_t *__restrict__ counts, int32_t *__restrict__ offsets, int32_t *__restrict__ perm,
     int32_t *__restrict__ inv, int32_t *__restrict__ n_active, int32_t *__restrict__ row_token,
     int32_t *__restrict__ plan) {
   extern __shared__ int32_t smem[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   for (int t = wave; t < T; t += PERM_WAVES)
-    topk_token<SLOTS>(logits, t, lane, E, Etot, K, score_func, renorm, scale, ids, w, gate);
+    topk_token<SLOTS>(logits, t, lane, E, Etot, K, score_func, renorm, scale, groups, ids, w, gate);
   __threadfence_block();
   __syncthreads();
   permute_body(ids, (int64_t)T * K, E, K, nbits, counts, offsets, perm, inv, n_active, row_token, plan,
@@ -220,8 +220,8 @@ hipError_t launch_permute(const int32_t *ids, int64_t n, int E, int K, int32_t *
 }
 
 hipError_t launch_topk_permute(const double *logits, int T, int E, int K, int score_func, int renorm,
-                               float scale, int has_shared_gate, int32_t *ids, float *w, float *gate,
-                               int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv,
+                               float scale, int groups, int has_shared_gate, int32_t *ids, float *w,
+                               float *gate, int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv,
                                int32_t *n_active, int32_t *row_token, int32_t *plan, hipStream_t s) {
   const int Etot = E + (has_shared_gate ? 1 : 0);
   int nbits = 1;
@@ -229,11 +229,11 @@ hipError_t launch_topk_permute(const double *logits, int T, int E, int K, int sc
   const size_t smem = sizeof(int32_t) * ((size_t)PERM_WAVES * E + PERM_THREADS);
   if (E <= 64) {
     hipLaunchKernelGGL(topk_permute_kernel<1>, dim3(1), dim3(PERM_THREADS), smem, s, logits, T, E, Etot,
-                       K, score_func, renorm, scale, ids, w, gate, nbits, counts, offsets, perm, inv,
+                       K, score_func, renorm, scale, groups, ids, w, gate, nbits, counts, offsets, perm, inv,
                        n_active, row_token, plan);
   } else if (E <= 256) {
     hipLaunchKernelGGL(topk_permute_kernel<4>, dim3(1), dim3(PERM_THREADS), smem, s, logits, T, E, Etot,
-                       K, score_func, renorm, scale, ids, w, gate, nbits, counts, offsets, perm, inv,
+                       K, score_func, renorm, scale, groups, ids, w, gate, nbits, counts, offsets, perm, inv,
                        n_active, row_token, plan);
   } else {
     return hipErrorInvalidValue;  // callers use the two-kernel path for wider routers

@@ -218,27 +218,27 @@ hipError_t launch_router_logits(const uint16_t *x, const uint16_t *w_router, con
 template <int SLOTS>
 __global__ __launch_bounds__(256) void topk_kernel(const double *__restrict__ logits, int T, int E,
                                                    int Etot, int K, int score_func, int renorm,
-                                                   float scale, int32_t *__restrict__ ids,
+                                                   float scale, int groups, int32_t *__restrict__ ids,
                                                    float *__restrict__ w, float *__restrict__ gate) {
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (t >= T) return;
-  topk_token<SLOTS>(logits, t, lane, E, Etot, K, score_func, renorm, scale, ids, w, gate);
+  topk_token<SLOTS>(logits, t, lane, E, Etot, K, score_func, renorm, scale, groups, ids, w, gate);
 }
 
 hipError_t launch_topk(const double *logits, int T, int E, int K, int score_func, int renorm,
-                       float scale, int has_shared_gate, int32_t *ids, float *w, float *gate,
-                       hipStream_t s) {
+                       float scale, int groups, int has_shared_gate, int32_t *ids, float *w,
+                       float *gate, hipStream_t s) {
   const int Etot = E + (has_shared_gate ? 1 : 0);
   const dim3 grid((T + 3) / 4), block(256);
   if (E <= 64)
     hipLaunchKernelGGL(topk_kernel<1>, grid, block, 0, s, logits, T, E, Etot, K, score_func, renorm,
-                       scale, ids, w, gate);
+                       scale, groups, ids, w, gate);
   else if (E <= 256)
     hipLaunchKernelGGL(topk_kernel<4>, grid, block, 0, s, logits, T, E, Etot, K, score_func, renorm,
-                       scale, ids, w, gate);
+                       scale, groups, ids, w, gate);
   else
     hipLaunchKernelGGL(topk_kernel<MOESD_MAX_E / 64>, grid, block, 0, s, logits, T, E, Etot, K,
-                       score_func, renorm, scale, ids, w, gate);
+                       score_func, renorm, scale, groups, ids, w, gate);
   return hipGetLastError();
 }

@@ -49,8 +49,8 @@ __device__ __forceinline__ double wave_max_f64(double v) {
 template <int SLOTS>  // experts per lane: E <= 64 * SLOTS
 __device__ __forceinline__ void topk_token(const double *__restrict__ logits, int t, int lane, int E,
                                            int Etot, int K, int score_func, int renorm, float scale,
-                                           int32_t *__restrict__ ids, float *__restrict__ w,
-                                           float *__restrict__ gate) {
+                                           int groups, int32_t *__restrict__ ids,
+                                           float *__restrict__ w, float *__restrict__ gate) {
   const double *lrow = logits + (size_t)t * Etot;
 
   unsigned long long key[SLOTS];
@@ -66,9 +66,12 @@ __device__ __forceinline__ void topk_token(const double *__restrict__ logits, in
     }
   }
 
-  // full-softmax normaliser, needed only when the winners are not renormalised
+  // groups = n_group | topk_group << 16; n_group <= 1: unconstrained selection
+  const int n_group = groups & 0xFFFF, topk_group = groups >> 16;
+
+  // full-softmax normaliser, needed when the winners are not renormalised and for group scores
   double mx = 0.0, z = 1.0;
-  if (score_func == MOESD_SCORE_SOFTMAX && !renorm) {
+  if (score_func == MOESD_SCORE_SOFTMAX && (!renorm || n_group > 1)) {
     double m = -1.0e300;
 #pragma nounroll
     for (int e = lane; e < E; e += 64) m = fmax(m, lrow[e]);
@@ -77,6 +80,56 @@ __device__ __forceinline__ void topk_token(const double *__restrict__ logits, in
 #pragma nounroll
     for (int e = lane; e < E; e += 64) sacc += exp(lrow[e] - mx);
     z = wave_sum_f64(sacc);
+  }
+
+  // Group-limited selection: a group's score is the sum of the scores of its two members with
+  // the largest keys, rounded once to fp32; the topk_group best groups (equal scores: the lower
+  // index) keep their members, every other expert's key is cleared.  Lane g holds group g's score.
+  if (n_group > 1) {
+    const int gs = E / n_group;
+    int grp[SLOTS];
+#pragma unroll
+    for (int j = 0; j < SLOTS; ++j) grp[j] = (lane + 64 * j) / gs;
+    unsigned long long gkey = 0ull;
+#pragma nounroll
+    for (int g = 0; g < n_group; ++g) {
+      unsigned long long b1 = 0ull;
+#pragma unroll
+      for (int j = 0; j < SLOTS; ++j)
+        if (grp[j] == g && key[j] > b1) b1 = key[j];
+      b1 = wave_max_u64(b1);  // never 0: a group has at least one member
+      unsigned long long b2 = 0ull;
+#pragma unroll
+      for (int j = 0; j < SLOTS; ++j)
+        if (grp[j] == g && key[j] != b1 && key[j] > b2) b2 = key[j];
+      b2 = wave_max_u64(b2);  // 0: the group has one member
+      const int e1 = (int)(0xFFFFFFFFu - (uint32_t)(b1 & 0xFFFFFFFFull));
+      const int e2 = b2 ? (int)(0xFFFFFFFFu - (uint32_t)(b2 & 0xFFFFFFFFull)) : e1;
+      const double l1 = lrow[e1], l2 = lrow[e2];
+      double s1, s2;
+      if (score_func == MOESD_SCORE_SOFTMAX) {
+        s1 = exp(l1 - mx) / z;
+        s2 = exp(l2 - mx) / z;
+      } else {
+        s1 = 1.0 / (1.0 + exp(-l1));
+        s2 = 1.0 / (1.0 + exp(-l2));
+      }
+      const float gf = (float)(s1 + (b2 ? s2 : 0.0));  // >= 0: its bit pattern is ordered as it is
+      if (lane == g)
+        gkey = ((unsigned long long)(__float_as_uint(gf) | 0x80000000u) << 32) |
+               (unsigned long long)(0xFFFFFFFFu - (uint32_t)g);
+    }
+    unsigned long long keep = 0ull;
+#pragma nounroll
+    for (int s = 0; s < topk_group; ++s) {
+      const unsigned long long best = wave_max_u64(gkey);
+      const int g = (int)(0xFFFFFFFFu - (uint32_t)(best & 0xFFFFFFFFull));
+      keep |= 1ull << g;
+      if (lane == g) gkey = 0ull;
+    }
+#pragma unroll
+    for (int j = 0; j < SLOTS; ++j)
+      if (!((keep >> (grp[j] & 63)) & 1ull)) key[j] = 0ull;
   }
 
   int my_id = 0;        // lane s keeps the s-th winner

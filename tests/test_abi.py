@@ -91,6 +91,13 @@ def test_forward_argument_errors_need_no_gpu():
     assert _fwd(bad, 16) == binding.UNSUPPORTED
     bad = moesd.make_desc(LayerShape("b", 256, 8, 2, 516))
     assert _fwd(bad, 16) == binding.INVALID_ARG                                 # inter % 8
+    for G, Gk in ((3, 1), (4, 0), (4, 5), (8, 1)):                              # E % G; no group; > G; K > Gk*E/G
+        bad = moesd.make_desc(LayerShape("b", 256, 8, 2, 512, n_group=G, topk_group=Gk))
+        assert _fwd(bad, 16) == binding.INVALID_ARG, (G, Gk)
+    bad = moesd.make_desc(LayerShape("b", 256, 256, 2, 512, n_group=128, topk_group=4))
+    assert _fwd(bad, 16) == binding.UNSUPPORTED                                 # more than 64 groups
+    ok = moesd.make_desc(LayerShape("b", 256, 8, 2, 512, n_group=4, topk_group=2))
+    assert moesd.moesd_workspace_bytes(ok, 16) > 0
     sh = moesd.make_desc(PRESETS["qwen1.5-moe-a2.7b"])
     assert _fwd(sh, 16, ws_bytes=1 << 30, wt={"ws_down": None}) == binding.INVALID_ARG
     assert _fwd(sh, 16, ws_bytes=1 << 30, wt={"w_shared_gate": None}) == binding.INVALID_ARG
@@ -105,3 +112,22 @@ def test_forward_argument_errors_need_no_gpu():
     with pytest.raises(binding.MoesdError):
         binding.moesd_moe_forward(d, binding.Weights(), 0x1000, -1, 0x1000, 0x1000,
                                   workspace_bytes=1 << 20, stream=0)
+
+
+def test_nonuniform_activation_count_against_the_oracle(oracle):
+    import numpy as np
+    rng = np.random.default_rng(4)
+    for E, K, t in ((60, 4, 64), (256, 8, 1), (8, 8, 5), (40, 3, 0), (16, 2, 100000)):
+        p = rng.random(E) ** 3
+        p *= K / p.sum()
+        p = np.minimum(p, 1.0)
+        a = moesd.moesd_expected_active_experts_p(p.tolist(), t)
+        b = oracle.expected_active_experts_p(p, t)
+        assert abs(a - b) <= 1e-12 * max(1.0, b)
+        u = moesd.moesd_expected_active_experts_p([K / E] * E, t)
+        assert abs(u - moesd.moesd_expected_active_experts(E, K, t)) <= 1e-10 * max(1.0, u)
+        if t > 1 and K < E:
+            assert a < u                                    # any other p with the same sum activates fewer
+    assert math.isnan(moesd.moesd_expected_active_experts_p([0.5, 1.5], 2))
+    assert moesd.moesd_expected_active_experts_p([1.0, 0.0], 0) == 0.0
+    assert moesd.moesd_expected_active_experts_p([1.0, 0.0], 3) == 1.0

@@ -92,6 +92,22 @@ def test_tiles_cut_by_the_schedule(gpu, oracle, shape, T):
     run_case(gpu, oracle, shape, T, tokens=tokens)
 
 
+@pytest.mark.parametrize("shape,T", [
+    # group-limited selection (the routing rule of config 4's model family): one and several experts per lane,
+    # sigmoid and softmax scores, the fused top-K + permutation kernel (T <= 32) and the separate ones
+    (LayerShape("grp-16", d=256, E=16, top_k=4, inter=128, score_func=1, n_group=4, topk_group=2, seed=41), 23),
+    (LayerShape("grp-256", d=256, E=256, top_k=8, inter=64, score_func=1, n_group=8, topk_group=4, seed=42), 29),
+    (LayerShape("grp-256", d=256, E=256, top_k=8, inter=64, score_func=1, n_group=8, topk_group=4, seed=42), 150),
+    (LayerShape("grp-softmax", d=128, E=24, top_k=5, inter=64, n_group=4, topk_group=2, renormalize=0, seed=43), 70),
+    (LayerShape("grp-320", d=128, E=320, top_k=6, inter=64, score_func=1, n_group=64, topk_group=3, seed=44), 40),
+    (LayerShape("grp-single", d=128, E=8, top_k=2, inter=64, score_func=1, n_group=8, topk_group=2, seed=45), 9),
+])
+def test_group_limited_selection(gpu, oracle, shape, T):
+    got, ref = run_case(gpu, oracle, shape, T, skew=0.8)
+    gs = shape.E // shape.n_group
+    assert all(len(set((got["ids"][t] // gs).tolist())) <= shape.topk_group for t in range(T))
+
+
 def test_skewed_routing_and_bias(gpu, oracle):
     shape = LayerShape("skew", d=256, E=64, top_k=8, inter=128, shared_inter=256, shared_gate=1, seed=16)
     got, ref = run_case(gpu, oracle, shape, 48, skew=1.5)
