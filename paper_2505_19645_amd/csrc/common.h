@@ -73,6 +73,7 @@ struct StreamArgs {
   const int32_t *plan;
   int32_t d, E, K, I, S, T;
   int32_t part_k;                             // k-part length of the shared down projection
+  int32_t shared_stream;                      // 1: the streaming kernels take the shared expert, 0: the tiled ones
 };
 
 // host-side launch entry points, one per source file
@@ -99,6 +100,10 @@ hipError_t launch_down(const StreamArgs &a, hipStream_t s);
 // The tiled kernels are persistent and cut the work into equal shares; a tile cut by a
 // share boundary is completed through `partials` (tiled_partials_bytes() bytes).
 size_t tiled_partials_bytes();
+// Which kernels should take the shared expert of S x d at T > 128 tokens: 1 = the streaming
+// kernels (its weights pass once per 64 tokens), 0 = the MFMA-tiled kernels (a few 256-row tiles
+// can leave most of the chip idle for as long as one tile takes).
+int shared_expert_streams(int T, int d, int S, int part_k);
 hipError_t launch_gate_up_tiled(const StreamArgs &a, float *partials, hipStream_t s);
 hipError_t launch_down_tiled(const StreamArgs &a, float *partials, hipStream_t s);
 hipError_t launch_combine(const float *y, const float *ys, int n_parts, const float *w,

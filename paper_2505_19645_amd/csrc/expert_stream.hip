@@ -650,7 +650,7 @@ __global__ __launch_bounds__(256) void expert_stream_kernel(StreamArgs a,
   // small tiles: [shared expert's, if it has at most 16 rows][small routed entries]
   const int n_small_e = sload(plan, 0), n_big_e = sload(plan, 1);
   const bool has_shared = a.S > 0;
-  const bool shared_wide = a.T > SMALL_M && a.T <= PLAN_BIG_MAX_ROWS;   // more rows: the tiled kernel takes it
+  const bool shared_wide = a.T > SMALL_M && a.shared_stream;   // otherwise the tiled kernel takes it
   const bool shared_small = a.T <= SMALL_M;
   const int parts = (MODE == MODE_DOWN && has_shared) ? (a.S + a.part_k - 1) / a.part_k : 1;
   ClassCfg cw, cs;

@@ -597,6 +597,22 @@ static int tiled_grid() {
   }
   return grid;
 }
+// Estimated microseconds either way, from measurements on the MI355X: the streaming kernels move
+// the shared expert's 3*S*d*2 bytes once per 64 tokens at about 3.2 TB/s when they share the chip
+// with the routed experts' wide tiles; a tiled kernel needs ceil(tiles / CUs) rounds of a tile's
+// stages, 1.5 us (gate/up) and 1.8 us (down) each, plus a fix-up launch.
+int shared_expert_streams(int T, int d, int S, int part_k) {
+  if (S <= 0 || T <= PLAN_BIG_MAX_ROWS) return 1;
+  const double n_cu = (double)tiled_grid();
+  const double stream_us = (double)((T + 63) / 64) * (3.0 * S * (double)d * 2.0) / 3.2e6;
+  const double tb = (double)((T + TBM - 1) / TBM);
+  const int parts = (S + part_k - 1) / part_k;
+  const double gu_rounds = ceil(tb * ((S + 127) / 128) / n_cu), dn_rounds = ceil(tb * parts * ((d + 255) / 256) / n_cu);
+  const double gu_stages = (double)((d + TBK - 1) / TBK), dn_stages = (double)(((S < part_k ? S : part_k) + TBK - 1) / TBK);
+  const double tiled_us = gu_rounds * gu_stages * 1.5 + dn_rounds * dn_stages * 1.8 + 8.0;
+  return stream_us < tiled_us ? 1 : 0;
+}
+
 size_t tiled_partials_bytes() { return (size_t)2 * tiled_grid() * T_SLOT_FLOATS * sizeof(float); }
 static hipError_t launch_tiled(int mode, const StreamArgs &a, float *partials, hipStream_t s) {
   static bool attr_set[2] = {false, false};
@@ -612,7 +628,7 @@ static hipError_t launch_tiled(int mode, const StreamArgs &a, float *partials, h
   if (a.T <= PLAN_BIG_MAX_ROWS) return hipSuccess;
   const int parts = (mode == TMODE_DOWN && a.S > 0) ? (a.S + a.part_k - 1) / a.part_k : 1;
   TiledSched sc;
-  sc.n_shared_entries = a.S > 0 ? ((a.T + TBM - 1) / TBM) * parts : 0;
+  sc.n_shared_entries = (a.S > 0 && !a.shared_stream) ? ((a.T + TBM - 1) / TBM) * parts : 0;
   if (mode == TMODE_GATE_UP) {
     sc.rt_shared = (a.S + 127) / 128;
     sc.rt_routed = (a.I + 127) / 128;
