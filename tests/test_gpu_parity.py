@@ -199,7 +199,10 @@ def test_qwen15_shape_full_size_sampled_tokens(gpu, oracle):
     # benchmark config 1 at full size, T = 64 (B=16, gamma=3): all routing outputs
     # bit-exact, layer output checked on sampled tokens the oracle evaluates one by one
     shape = PRESETS["qwen1.5-moe-a2.7b"]
-    run_case(gpu, oracle, shape, 64, tokens=[0, 13, 31, 63], point=163)
+    w = synth.make_layer(shape, threads=16)
+    run_case(gpu, oracle, shape, 64, tokens=[0, 13, 31, 63], point=163, weights=w)
+    # T = 256 (B=64, gamma=3): routed experts in 64-row wide tiles, the shared expert streamed in four token blocks
+    run_case(gpu, oracle, shape, 256, tokens=[0, 77, 130, 255], point=164, weights=w)
 
 
 def test_qwen2_shape_full_size_sampled_tokens(gpu, oracle):
@@ -213,9 +216,12 @@ def test_mixtral_shape_full_size_tiled_sampled_tokens(gpu, oracle):
     # kernels with the persistent schedule the benchmark's compute-bound point times); routing bit-exact on
     # all tokens, output on sampled tokens
     shape = PRESETS["mixtral-8x7b"]
+    w = synth.make_layer(shape, threads=16)
     rng = np.random.default_rng(9)
     tokens = np.sort(rng.choice(4096, size=24, replace=False)).astype(np.int32)
-    run_case(gpu, oracle, shape, 4096, tokens=tokens, point=363)
+    run_case(gpu, oracle, shape, 4096, tokens=tokens, point=363, weights=w)
+    # T = 128 (about 32 rows per expert): every expert in wide tiles, several thousand of them
+    run_case(gpu, oracle, shape, 128, tokens=[0, 41, 90, 127], point=364, weights=w)
 
 
 def test_deepseek_shape_full_size_sampled_tokens(gpu, oracle):
