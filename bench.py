@@ -316,7 +316,7 @@ def main():
 
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU; the layer is not sharded across GPUs "
-            "(expert parallelism is described in DESIGN.md only). Use --gpus 1.")
+            "(how it would shard by expert parallelism is described in the design notes only). Use --gpus 1.")
         sys.exit(2)
 
     import numpy as np

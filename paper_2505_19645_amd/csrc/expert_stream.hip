@@ -12,16 +12,17 @@
 //             w_gate + the same 16 of w_up, or 32 rows of w_down), contraction
 //             blocks of 256 elements; a block is one 24 KB slot: 16 KB of
 //             weights + 8 KB of tokens.
-//      wide:  17..64 rows.  128 weight rows (64 + 64, or 128 of w_down),
-//             contraction blocks of 128 elements; a block is two slots: 32 KB
-//             of weights + 16 KB of tokens.
+//      wide:  17..64 rows.  128 weight rows (64 + 64, or 128 of w_down), contraction
+//             blocks of 256 elements; a block is three 32 KB slots: the 64 token
+//             rows, 64 rows of the first operand half, 64 of the second.
 //    Experts with 65..128 rows run as two wide blocks (their weights stream twice);
 //    beyond that they belong to the MFMA-tiled kernel.
-//  * Every slot is exactly six global_load_lds_dwordx4 per wave, each moving
-//    1 KB (two 512-byte or four 256-byte row pieces, contiguous in HBM) straight
-//    into LDS; the weights carry the non-temporal hint (each byte is read once).
-//    So the hand-written s_waitcnt counts are compile-time constants.  Loads run
-//    four slots ahead in a ring of six, across tile borders; the compiler sees no
+//  * Every slot is exactly six (wide: eight) global_load_lds_dwordx4 per wave, each
+//    moving 1 KB (two 512-byte row pieces, contiguous in HBM: 256-byte pieces stream
+//    at three quarters of the rate) straight into LDS; the weights carry the
+//    non-temporal hint (each byte is read once).  So the hand-written s_waitcnt
+//    counts are compile-time constants.  Loads run four slots ahead in a ring of six
+//    (wide: three in a ring of four), across tile borders; the compiler sees no
 //    vector memory load in the loop and cannot serialise the prefetch.
 //  * Work split: wide tiles are dealt round-robin, then every workgroup gets a
 //    contiguous run of small tiles sized so that all finish together.
@@ -31,8 +32,10 @@
 //    writes stay linear.
 //  * Small tiles: the four waves split the eight 32-element MFMA steps of a
 //    block and add their partial 16x16 tiles through LDS in a fixed order.
-//    Wide tiles: wave w owns weight rows 16w..16w+15 of each half against all
-//    four token tiles; no reduction.  Results never depend on scheduling.
+//    Wide tiles: the waves form 2 x 2: a wave multiplies 32 token rows, whose
+//    fragments of the whole block it keeps in registers (the token slot is free as
+//    soon as it has been read), by 32 rows of every weight slot; no reduction.
+//    Results never depend on scheduling.
 //
 // MFMA operand use (v_mfma_f32_16x16x32_bf16): lane l = 16*q + r supplies 8
 // consecutive contraction elements (piece 4*s + q of step s) of weight row r
@@ -54,10 +57,18 @@
 #define KB 256             // contraction elements per block
 #define ROW_BYTES 512
 #define A_BYTES 16384      // 2 halves x 16 rows x 512 B
-// wide tiles
-#define KBW 128
-#define ROWW_BYTES 256
-#define WIDE_B_OFF 8192    // second slot: weight rows 96..127, then the 64 token rows
+// wide tiles: 512-byte row pieces as well (256-byte pieces stream from HBM at about three quarters of
+// the rate), three 32 KB slots per block: the 64 token rows, 64 rows of the first operand half, 64
+// of the second
+#define KBW 256
+#define WSLOT_BYTES 32768
+#define WRING 4            // every slot is consumed in the step it arrives in
+#define WAHEAD 3
+#define WLW 8              // loads per wave per slot
+#ifndef WNW
+#define WNW 2              // weight slots per block: a wide tile has 64 * WNW weight rows (4 measured no
+#endif                     // faster where tiles abound and much slower where they are few)
+#define WHROWS (32 * WNW)  // rows of each operand half in a wide tile
 // the schedule's cost model, in hundredths of a routed expert's small slot
 #define COST_WIDE_SLOT 120
 #define COST_CLASS_SWITCH 1300
@@ -224,17 +235,19 @@ __device__ __forceinline__ Entry load_entry(const StreamArgs &a, const Tables &t
 // first weight row of row tile rt
 template <int MODE, bool WIDE>
 __device__ __forceinline__ int tile_i0(int rt) {
-  if (MODE == MODE_GATE_UP) return WIDE ? rt * 64 : rt * 16;
-  return WIDE ? rt * 128 : rt * 32;
+  if (MODE == MODE_GATE_UP) return WIDE ? rt * WHROWS : rt * 16;
+  return WIDE ? rt * 2 * WHROWS : rt * 32;
 }
 
 // Per-lane source pointers of the DMA instructions this wave issues.
 //   small: a[0..3] weights, b[0..1] tokens
-//   wide:  a[0..5] first slot, a[6..7] second slot, b[0..3] tokens
+//   wide:  b[0..7] tokens; the weight rows' addresses are formed when a slot is issued (i0: the
+//          tile's first weight row)
 template <bool WIDE>
 struct LoadPtrs {
-  const uint16_t *a[WIDE ? 8 : 4];
-  const uint16_t *b[WIDE ? 4 : 2];
+  const uint16_t *a[WIDE ? 1 : 4];
+  const uint16_t *b[WIDE ? 8 : 2];
+  int i0;
 };
 
 template <int MODE, bool WIDE>
@@ -255,20 +268,17 @@ __device__ __forceinline__ void setup_b(LoadPtrs<WIDE> &lp, const Entry &en,
       lp.b[i] = en.b + (size_t)tok * en.b_stride + ((pos ^ (r & 15)) << 3);
     }
   } else {
-    const int sub = lane >> 4, pos = lane & 15;
+    const int half = lane >> 5, pos = lane & 31;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int jb = wave * 4 + i;  // token rows 4*jb .. 4*jb+3
-      int t0 = en.row0 + min(4 * jb, en.m - 1), t1 = en.row0 + min(4 * jb + 1, en.m - 1);
-      int t2 = en.row0 + min(4 * jb + 2, en.m - 1), t3 = en.row0 + min(4 * jb + 3, en.m - 1);
+    for (int i = 0; i < 8; ++i) {
+      const int pair = wave * 8 + i;  // token rows 2*pair, 2*pair+1
+      int ta = en.row0 + min(2 * pair, en.m - 1), tb = en.row0 + min(2 * pair + 1, en.m - 1);
       if (en.use_map) {
-        t0 = sload(row_token, t0);
-        t1 = sload(row_token, t1);
-        t2 = sload(row_token, t2);
-        t3 = sload(row_token, t3);
+        ta = sload(row_token, ta);
+        tb = sload(row_token, tb);
       }
-      const int tok = sub == 0 ? t0 : (sub == 1 ? t1 : (sub == 2 ? t2 : t3));
-      const int r = 4 * jb + sub;
+      const int tok = half ? tb : ta;
+      const int r = 2 * pair + half;
       lp.b[i] = en.b + (size_t)tok * en.b_stride + ((pos ^ (r & 15)) << 3);
     }
   }
@@ -292,32 +302,16 @@ __device__ __forceinline__ void setup_a(LoadPtrs<WIDE> &lp, const Entry &en, int
       lp.a[i] = base + (size_t)row * en.a_stride + ((pos ^ (r & 15)) << 3);
     }
   } else {
-    const int sub = lane >> 4, pos = lane & 15;
-    const int span = (MODE == MODE_GATE_UP) ? 64 : 128;
-    const int rv = min(span, en.n_rows - i0);  // valid rows of each matrix in this tile
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int j = (i < 6) ? wave * 6 + i : 24 + wave * 2 + (i - 6);  // rows 4j .. 4j+3 of 128
-      const int r = 4 * j + sub;
-      const uint16_t *base;
-      int row;
-      if (MODE == MODE_GATE_UP) {
-        base = (r >> 6) ? en.a1 : en.a0;
-        row = i0 + min(r & 63, rv - 1);
-      } else {
-        base = en.a0;
-        row = i0 + min(r, rv - 1);
-      }
-      lp.a[i] = base + (size_t)row * en.a_stride + ((pos ^ (r & 15)) << 3);
-    }
+    lp.i0 = i0;
   }
 }
 
 // Issue one slot: exactly LW loads per wave.  Pieces past the end of a row are
 // pulled back inside it; their products are masked in the MFMA loop.
-template <bool WIDE>
-__device__ __forceinline__ void issue_slot(const LoadPtrs<WIDE> &lp, int klen, int kb, bool second,
+template <int MODE, bool WIDE>
+__device__ __forceinline__ void issue_slot(const LoadPtrs<WIDE> &lp, const Entry &en, int kb, int sub,
                                            uint32_t slot_base, int wave, int lane) {
+  const int klen = en.klen;
   if (!WIDE) {
     const int k0 = kb * KB;
     const bool full = k0 + KB <= klen;
@@ -338,30 +332,35 @@ __device__ __forceinline__ void issue_slot(const LoadPtrs<WIDE> &lp, int klen, i
       dma16(lp.b[i] + koff(2 * pair + half), slot_base + A_BYTES + (uint32_t)pair * 1024u);
     }
   } else {
+    // sub 0: the 64 token rows; sub 1 .. WNW: 64 weight rows each (gate/up: the first WNW/2 slots
+    // hold w_gate rows, the others the same rows of w_up; down: consecutive rows).
+    // Wave w moves rows 16w .. 16w+15 of the slot, two per instruction.
     const int k0 = kb * KBW;
     const bool full = k0 + KBW <= klen;
-    const int pos = lane & 15, sub = lane >> 4;
+    const int pos = lane & 31, half = lane >> 5;
     auto koff = [&](int r) __attribute__((always_inline)) -> int {
       if (full) return k0;
       const int piece = pos ^ (r & 15);
       return min(k0 + piece * 8, klen - 8) - piece * 8;
     };
-    if (!second) {
+    if (sub == 0) {
 #pragma unroll
-      for (int i = 0; i < 6; ++i) {
-        const int j = wave * 6 + i;  // weight rows 4j..4j+3 (0..95)
-        dma16_stream(lp.a[i] + koff(4 * j + sub), slot_base + (uint32_t)j * 1024u);
+      for (int i = 0; i < 8; ++i) {
+        const int pair = wave * 8 + i;
+        dma16(lp.b[i] + koff(2 * pair + half), slot_base + (uint32_t)pair * 1024u);
       }
     } else {
+      const int w = sub - 1;
+      const uint16_t *base = (MODE == MODE_GATE_UP && w >= WNW / 2) ? en.a1 : en.a0;
+      const int first = (MODE == MODE_GATE_UP) ? 64 * (w % (WNW / 2)) : 64 * w;  // of the tile's rows in this matrix
+      const int rv = min((MODE == MODE_GATE_UP) ? WHROWS : 2 * WHROWS, en.n_rows - lp.i0);  // valid ones
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const int j = 24 + wave * 2 + i;  // weight rows 96..127
-        dma16_stream(lp.a[6 + i] + koff(4 * j + sub), slot_base + (uint32_t)(j - 24) * 1024u);
-      }
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int jb = wave * 4 + i;  // token rows 4jb..4jb+3
-        dma16(lp.b[i] + koff(4 * jb + sub), slot_base + WIDE_B_OFF + (uint32_t)jb * 1024u);
+      for (int i = 0; i < 8; ++i) {
+        const int pair = wave * 8 + i;
+        const int r = 2 * pair + half;
+        const int row = lp.i0 + min(first + r, rv - 1);
+        dma16_stream(base + (size_t)row * en.a_stride + (((pos ^ (r & 15)) << 3) + koff(r)),
+                     slot_base + (uint32_t)pair * 1024u);
       }
     }
   }
@@ -414,11 +413,13 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
   const int r16 = lane & 15, q = lane >> 4;
   const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
   float *red = reinterpret_cast<float *>(smem + RING * SLOT_BYTES);
-  constexpr int NACC = WIDE ? 4 : 1;
+  constexpr int NACC = 1;  // (small tiles; the wide tiles keep theirs in accw)
+  constexpr int RG = WIDE ? WRING : RING, AH = WIDE ? WAHEAD : AHEAD, LWN = WIDE ? WLW : LW;
+  constexpr int SLOTB = WIDE ? WSLOT_BYTES : SLOT_BYTES;
 
   // ---- load cursor -------------------------------------------------------------------
   int l_i = 0, l_kb = 0, l_slot = 0;
-  bool l_second = false;
+  int l_sub = 0;  // wide: 0 tokens, 1 first operand half, 2 second
   Entry len = load_entry<MODE, WIDE>(a, tb_, c, c.id0);
   LoadPtrs<WIDE> lp;
   setup_b<MODE, WIDE>(lp, len, tb_.row_token, wave, lane);
@@ -426,13 +427,13 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
   bool l_live = true;
 
   auto advance_load = [&]() __attribute__((always_inline)) {
-    issue_slot<WIDE>(lp, len.klen, l_kb, l_second, lds0 + (uint32_t)(l_slot % RING) * SLOT_BYTES, wave, lane);
+    issue_slot<MODE, WIDE>(lp, len, l_kb, l_sub, lds0 + (uint32_t)(l_slot % RG) * SLOTB, wave, lane);
     ++l_slot;
-    if (WIDE && !l_second) {
-      l_second = true;
+    if (WIDE && l_sub < WNW) {
+      ++l_sub;
       return;
     }
-    l_second = false;
+    l_sub = 0;
     if (++l_kb == len.nkb) {
       l_kb = 0;
       if (++l_i == c.n_mine) {
@@ -450,7 +451,7 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
 
   // ---- compute cursor -----------------------------------------------------------------
   int c_i = 0, c_kb = 0, c_slot = 0;
-  bool c_second = false;
+  int c_sub = 0;
   Entry cen = load_entry<MODE, WIDE>(a, tb_, c, c.id0);
   f32x4 acc0[NACC], acc1[NACC];
 #pragma unroll
@@ -477,18 +478,28 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
     pend = false;
   };
 
-  constexpr int AH = AHEAD;  // (5 of the 6 slots in flight for the small tiles measured the same)
+  // (5 of the 6 slots in flight for the small tiles measured the same as 4)
   for (int i = 0; i < AH && l_live; ++i) advance_load();
+
+  // wide: waves as 2 (row halves of a slot) x 2 (token halves); the wave's 2 x 16 token rows of the
+  // current block, all 8 steps, stay in registers
+  u32x4 fbw[WIDE ? 2 : 1][WIDE ? 8 : 1];
+  f32x4 accw[WIDE ? WNW : 1][2][2];  // [weight slot][row tile of the wave][token tile of the wave]
+#pragma unroll
+  for (int w = 0; w < (WIDE ? WNW : 1); ++w)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) accw[w][i >> 1][i & 1] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  const int wr = wave & 1, wt = wave >> 1;
 
   while (true) {
     // slot c_slot must have landed: at most AH-1 younger slots may be pending
-    if (l_slot - c_slot == AH) wait_vm<(AH - 1) * LW>();
+    if (l_slot - c_slot == AH) wait_vm<(AH - 1) * LWN>();
     else wait_vm<0>();
     wg_barrier();
     if (l_live) advance_load();
     if (!WIDE && pend) flush_pending();
 
-    const char *sb = smem + (size_t)(c_slot % RING) * SLOT_BYTES;
+    const char *sb = smem + (size_t)(c_slot % RG) * SLOTB;
     bool tile_done = false;
     if (!WIDE) {
       const int kbase = c_kb * KB;
@@ -526,65 +537,51 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
       }
       tile_done = (c_kb == cen.nkb - 1);
       ++c_kb;
-    } else if (c_second) {
-      // wave w: weight rows 16w..16w+15 of each half; weights 0..95 sit in the previous slot
-      const int kbase = c_kb * KBW;
-      const char *sa = smem + (size_t)((c_slot + RING - 1) % RING) * SLOT_BYTES;
-      const char *pa0 = sa + (size_t)(16 * wave) * ROWW_BYTES;
-      const char *pa1 = (wave < 2) ? sa + (size_t)(64 + 16 * wave) * ROWW_BYTES
-                                   : sb + (size_t)(16 * wave - 32) * ROWW_BYTES;
-      const char *pb = sb + WIDE_B_OFF;
-      const int ntc = (cen.m + 15) >> 4;
-      if (kbase + KBW <= cen.klen) {
-        // whole block: all reads are unconditional and issued ahead of the MFMAs; token
-        // tiles beyond the block's rows multiply stale LDS rows into accumulators
-        // that are never stored
-        u32x4 fa0[4], fa1[4];
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          const int off = r16 * ROWW_BYTES + (((4 * s + q) ^ r16) << 4);
-          fa0[s] = *reinterpret_cast<const u32x4 *>(pa0 + off);
-          fa1[s] = *reinterpret_cast<const u32x4 *>(pa1 + off);
-        }
-#pragma unroll
-        for (int nt = 0; nt < NACC; ++nt) {
-          u32x4 fb[4];
-#pragma unroll
-          for (int s = 0; s < 4; ++s) {
-            const int off = r16 * ROWW_BYTES + (((4 * s + q) ^ r16) << 4);
-            fb[s] = *reinterpret_cast<const u32x4 *>(pb + nt * 16 * ROWW_BYTES + off);
-          }
-#pragma unroll
-          for (int s = 0; s < 4; ++s) {
-            acc0[nt] = mfma16(fa0[s], fb[s], acc0[nt]);
-            acc1[nt] = mfma16(fa1[s], fb[s], acc1[nt]);
-          }
-        }
-      } else {
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          if (kbase + s * 32 < cen.klen) {
-            const int piece = 4 * s + q;
-            const int off = r16 * ROWW_BYTES + ((piece ^ r16) << 4);
-            const u32x4 fa0 = *reinterpret_cast<const u32x4 *>(pa0 + off);
-            const u32x4 fa1 = *reinterpret_cast<const u32x4 *>(pa1 + off);
-            const bool dead = kbase + piece * 8 >= cen.klen;
-#pragma unroll
-            for (int nt = 0; nt < NACC; ++nt)
-              if (nt < ntc) {
-                u32x4 fb = *reinterpret_cast<const u32x4 *>(pb + nt * 16 * ROWW_BYTES + off);
-                if (dead) fb = (u32x4){0u, 0u, 0u, 0u};
-                acc0[nt] = mfma16(fa0, fb, acc0[nt]);
-                acc1[nt] = mfma16(fa1, fb, acc1[nt]);
-              }
-          }
-        }
-      }
-      tile_done = (c_kb == cen.nkb - 1);
-      ++c_kb;
-      c_second = false;
     } else {
-      c_second = true;  // first slot of a wide block: nothing to compute yet
+      // Wave (wr, wt) multiplies token rows 32wt .. 32wt+31 by rows 32wr .. 32wr+31 of every weight
+      // slot.  The token fragments of a block stay in registers, so the token slot is free again as
+      // soon as it has been read, like every weight slot; nothing is added across waves.
+      const bool busy = 32 * wt < cen.m;  // (a wave without token rows only keeps the barriers)
+      if (c_sub == 0) {
+        if (busy) {
+          const int kbase = c_kb * KBW;
+#pragma unroll
+          for (int tt = 0; tt < 2; ++tt) {
+            const char *pb = sb + (size_t)(32 * wt + 16 * tt + r16) * ROW_BYTES;
+#pragma unroll
+            for (int st = 0; st < 8; ++st) {
+              const int piece = 4 * st + q;
+              fbw[tt][st] = *reinterpret_cast<const u32x4 *>(pb + ((piece ^ r16) << 4));
+              // ragged last block: pieces past the row's end hold bytes pulled back from inside it
+              if (kbase + piece * 8 >= cen.klen) fbw[tt][st] = (u32x4){0u, 0u, 0u, 0u};
+            }
+          }
+        }
+      } else if (busy) {
+#pragma unroll
+        for (int w = 0; w < WNW; ++w)
+          if (c_sub == w + 1) {
+#pragma unroll
+            for (int rtl = 0; rtl < 2; ++rtl) {
+              const char *pa = sb + (size_t)(16 * (2 * wr + rtl) + r16) * ROW_BYTES;
+              u32x4 fa[8];
+#pragma unroll
+              for (int st = 0; st < 8; ++st)
+                fa[st] = *reinterpret_cast<const u32x4 *>(pa + (((4 * st + q) ^ r16) << 4));
+#pragma unroll
+              for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+                for (int st = 0; st < 8; ++st) accw[w][rtl][tt] = mfma16(fa[st], fbw[tt][st], accw[w][rtl][tt]);
+            }
+          }
+      }
+      if (c_sub == WNW) {
+        tile_done = (c_kb == cen.nkb - 1);
+        ++c_kb;
+        c_sub = 0;
+      } else {
+        ++c_sub;
+      }
     }
     ++c_slot;
 
@@ -592,21 +589,25 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
       const int id = c.id0 + c_i * c.stride;
       const int i0 = tile_i0<MODE, WIDE>(id - cen.first);
       if (WIDE) {
-        // straight from the accumulators: token row 16*nt + r16, features 16*wave + 4q + rr
-        const int ntc = (cen.m + 15) >> 4;
+        // straight from the accumulators: token row 32wt + 16tt + r16; slot w < WNW/2 pairs with slot
+        // w + WNW/2 (gate with up rows; down: WHROWS features further on)
 #pragma unroll
-        for (int nt = 0; nt < NACC; ++nt)
-          if (nt < ntc) {
-            const int j = nt * 16 + r16;
-            if (j < cen.m)  // 4 neighbouring features per lane: one vector store per half
-              store_out4<MODE>(cen.out, cen.out_n, (size_t)(cen.row0 + j), i0 + 16 * wave + 4 * q, 64, acc0[nt],
-                               acc1[nt]);
+        for (int tt = 0; tt < 2; ++tt) {
+          const int j = 32 * wt + 16 * tt + r16;
+          if (j < cen.m) {
+#pragma unroll
+            for (int w = 0; w < WNW / 2; ++w)
+#pragma unroll
+              for (int rtl = 0; rtl < 2; ++rtl)
+                store_out4<MODE>(cen.out, cen.out_n, (size_t)(cen.row0 + j),
+                                 i0 + 64 * w + 16 * (2 * wr + rtl) + 4 * q, WHROWS, accw[w][rtl][tt],
+                                 accw[w + WNW / 2][rtl][tt]);
           }
-#pragma unroll
-        for (int nt = 0; nt < NACC; ++nt) {
-          acc0[nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
-          acc1[nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
         }
+#pragma unroll
+        for (int w = 0; w < WNW; ++w)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) accw[w][i >> 1][i & 1] = (f32x4){0.f, 0.f, 0.f, 0.f};
       } else {
         if (cen.nkb == 1) wg_barrier();  // the previous tile's sums may still be read from `red`
         // lane (q, r16) holds features 4q..4q+3 of token row r16: one 16-byte store per half
@@ -657,8 +658,8 @@ __global__ __launch_bounds__(256) void expert_stream_kernel(StreamArgs a,
   cw.parts = cs.parts = parts;
   cs.per_r = (MODE == MODE_GATE_UP) ? (a.I + 15) / 16 : (a.d + 31) / 32;
   cs.per_s = (MODE == MODE_GATE_UP) ? (a.S + 15) / 16 : (a.d + 31) / 32;
-  cw.per_r = (MODE == MODE_GATE_UP) ? (a.I + 63) / 64 : (a.d + 127) / 128;
-  cw.per_s = (MODE == MODE_GATE_UP) ? (a.S + 63) / 64 : (a.d + 127) / 128;
+  cw.per_r = (MODE == MODE_GATE_UP) ? (a.I + WHROWS - 1) / WHROWS : (a.d + 2 * WHROWS - 1) / (2 * WHROWS);
+  cw.per_s = (MODE == MODE_GATE_UP) ? (a.S + WHROWS - 1) / WHROWS : (a.d + 2 * WHROWS - 1) / (2 * WHROWS);
   const int n_tb = (a.T + BIG_TB - 1) / BIG_TB;
   cw.n_sh = (has_shared && shared_wide) ? cw.per_s * parts * n_tb : 0;
   cs.n_sh = (has_shared && shared_small) ? cs.per_s * parts : 0;
@@ -673,7 +674,7 @@ __global__ __launch_bounds__(256) void expert_stream_kernel(StreamArgs a,
     // rows are all distinct (the shared expert at T = 16) takes 1.15x as long as one with a few.
     const int kr = (MODE == MODE_GATE_UP) ? a.d : a.I;
     const long nkb_s = (kr + KB - 1) / KB, nkb_w = (kr + KBW - 1) / KBW;
-    const long c_wide = 2 * nkb_w * COST_WIDE_SLOT;
+    const long c_wide = nkb_w * (WNW + 1) * 4 * COST_WIDE_SLOT / 3;  // a wide slot is 4/3 of a small one
     const long c_sh = nkb_s * (100 + COST_DISTINCT_ROWS * min(a.T, SMALL_M) / SMALL_M);
     const long c_r = nkb_s * 100;
     const long n_shs = cs.n_sh, n_rs = n_small - cs.n_sh;
