@@ -100,10 +100,10 @@ hipError_t launch_down(const StreamArgs &a, hipStream_t s);
 // The tiled kernels are persistent and cut the work into equal shares; a tile cut by a
 // share boundary is completed through `partials` (tiled_partials_bytes() bytes).
 size_t tiled_partials_bytes();
-// Which kernels should take the shared expert of S x d at T > 128 tokens: 1 = the streaming
+// Which kernels should take the shared expert of S x d at T > 128 tokens (K of E experts per token): 1 = the streaming
 // kernels (its weights pass once per 64 tokens), 0 = the MFMA-tiled kernels (a few 256-row tiles
 // can leave most of the chip idle for as long as one tile takes).
-int shared_expert_streams(int T, int d, int S, int part_k);
+int shared_expert_streams(int T, int d, int S, int part_k, int K, int E);
 hipError_t launch_gate_up_tiled(const StreamArgs &a, float *partials, hipStream_t s);
 hipError_t launch_down_tiled(const StreamArgs &a, float *partials, hipStream_t s);
 hipError_t launch_combine(const float *y, const float *ys, int n_parts, const float *w,

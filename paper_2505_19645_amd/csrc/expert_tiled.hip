@@ -601,8 +601,11 @@ static int tiled_grid() {
 // the shared expert's 3*S*d*2 bytes once per 64 tokens at about 3.2 TB/s when they share the chip
 // with the routed experts' wide tiles; a tiled kernel needs ceil(tiles / CUs) rounds of a tile's
 // stages, 1.5 us (gate/up) and 1.8 us (down) each, plus a fix-up launch.
-int shared_expert_streams(int T, int d, int S, int part_k) {
+int shared_expert_streams(int T, int d, int S, int part_k, int K, int E) {
   if (S <= 0 || T <= PLAN_BIG_MAX_ROWS) return 1;
+  // routed experts with more than 64 rows on average keep the tiled kernels busy anyway: the shared
+  // expert's tiles then fill gaps there instead of leaving the chip idle
+  if ((long)T * K > 64L * E) return 0;
   const double n_cu = (double)tiled_grid();
   const double stream_us = (double)((T + 63) / 64) * (3.0 * S * (double)d * 2.0) / 3.2e6;
   const double tb = (double)((T + TBM - 1) / TBM);

@@ -248,7 +248,7 @@ int32_t moesd_moe_forward_staged(const moesd_layer_desc *desc, const moesd_weigh
   a.I = desc->inter;
   a.S = desc->shared_inter;
   a.T = T;
-  a.shared_stream = shared_expert_streams(T, desc->d, desc->shared_inter, ws.part_k);
+  a.shared_stream = shared_expert_streams(T, desc->d, desc->shared_inter, ws.part_k, desc->top_k, desc->E);
   // experts with at most 128 rows stream; the others (possible only if T > 128) are tiled
   MOESD_TRY(launch_gate_up(a, s))
   if (T > PLAN_BIG_MAX_ROWS) {
