@@ -21,6 +21,8 @@
 //    (row >> 1) & 7: two rows share a 256-byte bank line, so the 16 rows a
 //    quarter-wave reads, and the 2 rows x 8 pieces it writes, fall into 16
 //    different 16-byte bank groups.
+//  * A wave whose 64 token rows are all padding multiplies nothing (it still loads and
+//    stores its share of the stages): a block of at most 128 rows costs half the MFMA time.
 //  * The MFMA fragments of a 16-element half step are double-buffered in
 //    registers: the LDS reads of the next half step run under the MFMAs of the
 //    current one; one s_barrier per stage.
@@ -361,6 +363,20 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
 #endif
   using Y = std::true_type;
   using N = std::false_type;
+  // A wave whose 64 token rows are all padding (a block with few rows: the last one of an expert, or an
+  // expert with 65..128 rows) only keeps loading and storing its share of the stages and the barriers.
+  // With the usual placement of a workgroup's waves (wave i on SIMD i mod 4) a block of at most 128
+  // rows then leaves one multiplying wave per SIMD instead of two.
+  const bool idle_wave = 32 * T_NT * wt >= m;
+  auto step_idle = [&](int j, auto pi, auto has_next, auto has_load) __attribute__((always_inline)) {
+    constexpr int PI = decltype(pi)::value;
+    constexpr bool HN = decltype(has_next)::value, HL = decltype(has_load)::value;
+    if constexpr (HN) {
+      store_stage(s0 + j + 1, (j & 1) ^ 1, pre[PI], ragged && j + 2 == n);
+      if constexpr (HL) load_stage(s0 + j + 1 + T_AHEAD, pre[PI]);
+      t_barrier();
+    }
+  };
   if (!FIXUP && n > 0) {
 #pragma unroll
     for (int a2 = 0; a2 < T_AHEAD; ++a2)
@@ -369,9 +385,21 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
     store_stage(s0, 0, pre[0], ragged && n == 1);
     if (T_AHEAD < n) load_stage(s0 + T_AHEAD, pre[0]);
     t_barrier();
+    int j = 0;
+#if T_AHEAD == 1
+    if (idle_wave) {
+      for (; j + 2 < n; ++j) step_idle(j, P0{}, Y{}, Y{});
+      if (j + 1 < n) {
+        step_idle(j, P0{}, Y{}, N{});
+        ++j;
+      }
+      step_idle(j, P0{}, N{}, N{});
+    } else {
+#else
+    {
+#endif
     read_half(0, 0, fa0, fb0);
     read_half(0, 1, fa1, fb1);
-    int j = 0;
     // steady state: branch-free, so the compiler's wait counts stay exact; the last stages are
     // straight-line sequences chosen by how many remain (no loop around differently shaped steps)
 #if T_AHEAD == 1
@@ -407,6 +435,7 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
         break;
     }
 #endif
+    }
   }
 
   // ---- a tile cut by the schedule: its pieces meet in memory, the second kernel finishes it --
