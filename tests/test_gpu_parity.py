@@ -108,6 +108,31 @@ def test_group_limited_selection(gpu, oracle, shape, T):
     assert all(len(set((got["ids"][t] // gs).tolist())) <= shape.topk_group for t in range(T))
 
 
+def _random_shape(i):
+    """A small layer with every size drawn at random (seeded): odd row counts, ragged contraction lengths,
+    all expert classes, with and without shared expert, groups, bias."""
+    rng = np.random.default_rng(1000 + i)
+    E = int(rng.integers(1, 41))
+    K = int(rng.integers(1, min(E, 8) + 1))
+    kw = dict(d=8 * int(rng.integers(8, 66)), E=E, top_k=K, inter=8 * int(rng.integers(2, 40)),
+              score_func=int(rng.integers(0, 2)), renormalize=int(rng.integers(0, 2)), seed=500 + i)
+    if rng.random() < 0.6:
+        kw.update(shared_inter=8 * int(rng.integers(2, 50)), shared_gate=int(rng.integers(0, 2)))
+    divs = [g for g in range(2, E + 1) if E % g == 0 and g <= 64]
+    if divs and rng.random() < 0.3:
+        G = int(rng.choice(divs))
+        need = -(-K // (E // G))
+        kw.update(n_group=G, topk_group=int(rng.integers(need, G + 1)))
+    T = int(rng.choice([1, 3, 9, 16, 17, 40, 64, 65, 129, 200, 333, 600]))
+    return LayerShape(f"rnd{i}", **kw), T, float(rng.choice([0.0, 0.0, 1.0, 2.5]))
+
+
+@pytest.mark.parametrize("i", range(24))
+def test_random_small_shapes(gpu, oracle, i):
+    shape, T, skew = _random_shape(i)
+    run_case(gpu, oracle, shape, T, skew=skew)
+
+
 def test_skewed_routing_and_bias(gpu, oracle):
     shape = LayerShape("skew", d=256, E=64, top_k=8, inter=128, shared_inter=256, shared_gate=1, seed=16)
     got, ref = run_case(gpu, oracle, shape, 48, skew=1.5)
