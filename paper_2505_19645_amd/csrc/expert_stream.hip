@@ -10,18 +10,19 @@
 //    weight bytes that travel with them:
 //      small: an expert (or token block) with 1..16 rows.  32 weight rows (16 of
 //             w_gate + the same 16 of w_up, or 32 rows of w_down), contraction
-//             blocks of 256 elements; a block is one 24 KB slot: 16 KB of
-//             weights + 8 KB of tokens.
+//             blocks of 512 elements; a block is one 48 KB slot: 32 KB of
+//             weights + 16 KB of tokens.
 //      wide:  17..64 rows.  128 weight rows (64 + 64, or 128 of w_down), contraction
 //             blocks of 256 elements; a block is three 32 KB slots: the 64 token
 //             rows, 64 rows of the first operand half, 64 of the second.
 //    Experts with 65..128 rows run as two wide blocks (their weights stream twice);
 //    beyond that they belong to the MFMA-tiled kernel.
-//  * Every slot is exactly six (wide: eight) global_load_lds_dwordx4 per wave, each
-//    moving 1 KB (two 512-byte row pieces, contiguous in HBM: 256-byte pieces stream
-//    at three quarters of the rate) straight into LDS; the weights carry the
+//  * Every slot is exactly twelve (wide: eight) global_load_lds_dwordx4 per wave, each
+//    moving 1 KB (one 1 KB row piece, wide: two 512-byte pieces, contiguous in HBM:
+//    256-byte pieces stream at three quarters of the rate, and the longer the blocks
+//    the fewer steps a byte costs) straight into LDS; the weights carry the
 //    non-temporal hint (each byte is read once).  So the hand-written s_waitcnt
-//    counts are compile-time constants.  Loads run four slots ahead in a ring of six
+//    counts are compile-time constants.  Loads run two slots ahead in a ring of three
 //    (wide: three in a ring of four), across tile borders; the compiler sees no
 //    vector memory load in the loop and cannot serialise the prefetch.
 //  * Work split: wide tiles are dealt round-robin, then every workgroup gets a
@@ -30,7 +31,7 @@
 //    XOR-swizzled by (row & 15): the 16 rows that one quarter-wave reads then
 //    fall into 16 different 16-byte bank groups of the 64-bank LDS, while the DMA
 //    writes stay linear.
-//  * Small tiles: the four waves split the eight 32-element MFMA steps of a
+//  * Small tiles: the four waves split the sixteen 32-element MFMA steps of a
 //    block and add their partial 16x16 tiles through LDS in a fixed order.
 //    Wide tiles: the waves form 2 x 2: a wave multiplies 32 token rows, whose
 //    fragments of the whole block it keeps in registers (the token slot is free as
@@ -43,10 +44,10 @@
 // 4*q .. 4*q+3.
 #include "common.h"
 
-#define SLOT_BYTES 24576   // one ring slot
-#define RING 6             // slots in the ring
-#define AHEAD 4            // slots in flight
-#define LW 6               // loads per wave per slot
+#define SLOT_BYTES 49152   // one ring slot
+#define RING 3             // slots in the ring
+#define AHEAD 2            // slots in flight
+#define LW 12              // loads per wave per slot
 #define RED_ROW 20         // floats per token row of a partial tile: 16 features + 4 of padding (bank spread)
 #define RED_TILE (16 * RED_ROW)
 #define RED_BYTES (8 * RED_TILE * 4)  // 4 waves x 2 halves x 16 rows
@@ -54,9 +55,10 @@
 #define BIG_TB 64
 #define STREAM_LDS_BYTES (RING * SLOT_BYTES + RED_BYTES)
 // small tiles
-#define KB 256             // contraction elements per block
-#define ROW_BYTES 512
-#define A_BYTES 16384      // 2 halves x 16 rows x 512 B
+#define KB 512             // contraction elements per block
+#define SROW_BYTES 1024
+#define A_BYTES 32768      // 2 halves x 16 rows x 1 KB
+#define ROW_BYTES 512      // (wide tiles)
 // wide tiles: 512-byte row pieces as well (256-byte pieces stream from HBM at about three quarters of
 // the rate), three 32 KB slots per block: the 64 token rows, 64 rows of the first operand half, 64
 // of the second
@@ -71,7 +73,7 @@
 #define WHROWS (32 * WNW)  // rows of each operand half in a wide tile
 // the schedule's cost model, in hundredths of a routed expert's small slot
 #define COST_WIDE_SLOT 120
-#define COST_CLASS_SWITCH 1300
+#define COST_CLASS_SWITCH 650
 #define COST_DISTINCT_ROWS 15
 
 enum { MODE_GATE_UP = 0, MODE_DOWN = 1 };
@@ -240,13 +242,13 @@ __device__ __forceinline__ int tile_i0(int rt) {
 }
 
 // Per-lane source pointers of the DMA instructions this wave issues.
-//   small: a[0..3] weights, b[0..1] tokens
+//   small: a[0..7] weights, b[0..3] tokens (one 1 KB row per instruction)
 //   wide:  b[0..7] tokens; the weight rows' addresses are formed when a slot is issued (i0: the
 //          tile's first weight row)
 template <bool WIDE>
 struct LoadPtrs {
-  const uint16_t *a[WIDE ? 1 : 4];
-  const uint16_t *b[WIDE ? 8 : 2];
+  const uint16_t *a[WIDE ? 1 : 8];
+  const uint16_t *b[WIDE ? 8 : 4];
   int i0;
 };
 
@@ -254,18 +256,12 @@ template <int MODE, bool WIDE>
 __device__ __forceinline__ void setup_b(LoadPtrs<WIDE> &lp, const Entry &en,
                                         const int32_t *__restrict__ row_token, int wave, int lane) {
   if (!WIDE) {
-    const int half = lane >> 5, pos = lane & 31;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int pair = wave * 2 + i;  // token rows 2*pair, 2*pair+1
-      int ta = en.row0 + min(2 * pair, en.m - 1), tb = en.row0 + min(2 * pair + 1, en.m - 1);
-      if (en.use_map) {
-        ta = sload(row_token, ta);
-        tb = sload(row_token, tb);
-      }
-      const int tok = half ? tb : ta;
-      const int r = 2 * pair + half;
-      lp.b[i] = en.b + (size_t)tok * en.b_stride + ((pos ^ (r & 15)) << 3);
+    for (int i = 0; i < 4; ++i) {
+      const int r = wave * 4 + i;  // token row of the tile
+      int tok = en.row0 + min(r, en.m - 1);
+      if (en.use_map) tok = sload(row_token, tok);
+      lp.b[i] = en.b + (size_t)tok * en.b_stride + ((lane ^ (r & 15)) << 3);
     }
   } else {
     const int half = lane >> 5, pos = lane & 31;
@@ -288,18 +284,17 @@ template <int MODE, bool WIDE>
 __device__ __forceinline__ void setup_a(LoadPtrs<WIDE> &lp, const Entry &en, int rt, int wave, int lane) {
   const int i0 = tile_i0<MODE, WIDE>(rt);
   if (!WIDE) {
-    const int half = lane >> 5, pos = lane & 31;
     // valid rows in each 16-row half of this tile (at least 1 after clamping)
     const int rv0 = min(16, en.n_rows - i0);
     const int rv1 = (MODE == MODE_GATE_UP) ? rv0 : max(1, min(16, en.n_rows - i0 - 16));
     const int off1 = (MODE == MODE_GATE_UP) ? 0 : ((en.n_rows - i0 > 16) ? 16 : 0);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int j = wave * 4 + i;  // 0..15: half = j >> 3, row pair = j & 7
-      const int r = 2 * (j & 7) + half;
-      const uint16_t *base = (j >> 3) ? en.a1 : en.a0;
-      const int row = (j >> 3) ? i0 + off1 + min(r, rv1 - 1) : i0 + min(r, rv0 - 1);
-      lp.a[i] = base + (size_t)row * en.a_stride + ((pos ^ (r & 15)) << 3);
+    for (int i = 0; i < 8; ++i) {
+      const int j = wave * 8 + i;  // 0..31: half = j >> 4, row = j & 15
+      const int r = j & 15;
+      const uint16_t *base = (j >> 4) ? en.a1 : en.a0;
+      const int row = (j >> 4) ? i0 + off1 + min(r, rv1 - 1) : i0 + min(r, rv0 - 1);
+      lp.a[i] = base + (size_t)row * en.a_stride + ((lane ^ r) << 3);
     }
   } else {
     lp.i0 = i0;
@@ -315,21 +310,20 @@ __device__ __forceinline__ void issue_slot(const LoadPtrs<WIDE> &lp, const Entry
   if (!WIDE) {
     const int k0 = kb * KB;
     const bool full = k0 + KB <= klen;
-    const int pos = lane & 31, half = lane >> 5;
     auto koff = [&](int r) __attribute__((always_inline)) -> int {
       if (full) return k0;
-      const int piece = pos ^ (r & 15);
+      const int piece = lane ^ (r & 15);
       return min(k0 + piece * 8, klen - 8) - piece * 8;
     };
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int j = wave * 4 + i;
-      dma16_stream(lp.a[i] + koff(2 * (j & 7) + half), slot_base + (uint32_t)j * 1024u);
+    for (int i = 0; i < 8; ++i) {
+      const int j = wave * 8 + i;
+      dma16_stream(lp.a[i] + koff(j & 15), slot_base + (uint32_t)j * 1024u);
     }
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int pair = wave * 2 + i;
-      dma16(lp.b[i] + koff(2 * pair + half), slot_base + A_BYTES + (uint32_t)pair * 1024u);
+    for (int i = 0; i < 4; ++i) {
+      const int r = wave * 4 + i;
+      dma16(lp.b[i] + koff(r), slot_base + A_BYTES + (uint32_t)r * 1024u);
     }
   } else {
     // sub 0: the 64 token rows; sub 1 .. WNW: 64 weight rows each (gate/up: the first WNW/2 slots
@@ -503,31 +497,31 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
     bool tile_done = false;
     if (!WIDE) {
       const int kbase = c_kb * KB;
-      // waves split the 8 steps
+      // waves split the 16 steps
       if (kbase + KB <= cen.klen) {  // whole block: no masks, reads issued back to back
-        u32x4 fa0[2], fa1[2], fb[2];
+        u32x4 fa0[4], fa1[4], fb[4];
 #pragma unroll
-        for (int ss = 0; ss < 2; ++ss) {
-          const int piece = 4 * (wave * 2 + ss) + q;
-          const int off = r16 * ROW_BYTES + ((piece ^ r16) << 4);
+        for (int ss = 0; ss < 4; ++ss) {
+          const int piece = 4 * (wave * 4 + ss) + q;
+          const int off = r16 * SROW_BYTES + ((piece ^ r16) << 4);
           fa0[ss] = *reinterpret_cast<const u32x4 *>(sb + off);
-          fa1[ss] = *reinterpret_cast<const u32x4 *>(sb + 8192 + off);
+          fa1[ss] = *reinterpret_cast<const u32x4 *>(sb + 16 * SROW_BYTES + off);
           fb[ss] = *reinterpret_cast<const u32x4 *>(sb + A_BYTES + off);
         }
 #pragma unroll
-        for (int ss = 0; ss < 2; ++ss) {
+        for (int ss = 0; ss < 4; ++ss) {
           acc0[0] = mfma16(fa0[ss], fb[ss], acc0[0]);
           acc1[0] = mfma16(fa1[ss], fb[ss], acc1[0]);
         }
       } else {
 #pragma unroll
-        for (int ss = 0; ss < 2; ++ss) {
-          const int s = wave * 2 + ss;
+        for (int ss = 0; ss < 4; ++ss) {
+          const int s = wave * 4 + ss;
           if (kbase + s * 32 < cen.klen) {
             const int piece = 4 * s + q;
-            const int off = r16 * ROW_BYTES + ((piece ^ r16) << 4);
+            const int off = r16 * SROW_BYTES + ((piece ^ r16) << 4);
             const u32x4 fa0 = *reinterpret_cast<const u32x4 *>(sb + off);
-            const u32x4 fa1 = *reinterpret_cast<const u32x4 *>(sb + 8192 + off);
+            const u32x4 fa1 = *reinterpret_cast<const u32x4 *>(sb + 16 * SROW_BYTES + off);
             u32x4 fb = *reinterpret_cast<const u32x4 *>(sb + A_BYTES + off);
             if (kbase + piece * 8 >= cen.klen) fb = (u32x4){0u, 0u, 0u, 0u};  // ragged last step
             acc0[0] = mfma16(fa0, fb, acc0[0]);
@@ -668,13 +662,13 @@ __global__ __launch_bounds__(256) void expert_stream_kernel(StreamArgs a,
   {
     // Wide tiles are dealt round-robin; the small line is then cut so that every workgroup's
     // estimated time is the same.  Costs in hundredths of the time of one small slot of a routed
-    // expert, from per-workgroup timelines on the MI355X: a wide slot moves the same bytes as a
-    // small one but takes about 1.2x as long (more LDS traffic per byte), moving from the wide to the
-    // small class drains and refills the ring (about 13 slots), and a small slot whose 16 token
+    // expert, from per-workgroup timelines on the MI355X: a byte of a wide slot takes about 1.2x as
+    // long as one of a small slot (more LDS traffic per byte), moving from the wide to the
+    // small class drains and refills the ring (about 6 slots), and a small slot whose 16 token
     // rows are all distinct (the shared expert at T = 16) takes 1.15x as long as one with a few.
     const int kr = (MODE == MODE_GATE_UP) ? a.d : a.I;
     const long nkb_s = (kr + KB - 1) / KB, nkb_w = (kr + KBW - 1) / KBW;
-    const long c_wide = nkb_w * (WNW + 1) * 4 * COST_WIDE_SLOT / 3;  // a wide slot is 4/3 of a small one
+    const long c_wide = nkb_w * (WNW + 1) * 2 * COST_WIDE_SLOT / 3;  // a wide slot is 2/3 of a small one
     const long c_sh = nkb_s * (100 + COST_DISTINCT_ROWS * min(a.T, SMALL_M) / SMALL_M);
     const long c_r = nkb_s * 100;
     const long n_shs = cs.n_sh, n_rs = n_small - cs.n_sh;
