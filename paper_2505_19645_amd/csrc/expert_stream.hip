@@ -111,6 +111,25 @@ __device__ __forceinline__ int sload(const int32_t *p, int idx) {
   return v;
 }
 
+// the same for two and for four words, with one wait
+__device__ __forceinline__ void sload2(const int32_t *p, int i0, int i1, int &v0, int &v1) {
+  const int o0 = uni(i0) * 4, o1 = uni(i1) * 4;
+  asm volatile("s_load_dword %0, %2, %3\n\ts_load_dword %1, %2, %4\n\ts_waitcnt lgkmcnt(0)"
+               : "=&s"(v0), "=&s"(v1)
+               : "s"(p), "s"(o0), "s"(o1)
+               : "memory");
+}
+__device__ __forceinline__ void sload4(const int32_t *p, int i0, int i1, int i2, int i3, int &v0, int &v1,
+                                       int &v2, int &v3) {
+  const int o0 = uni(i0) * 4, o1 = uni(i1) * 4, o2 = uni(i2) * 4, o3 = uni(i3) * 4;
+  asm volatile(
+      "s_load_dword %0, %4, %5\n\ts_load_dword %1, %4, %6\n\ts_load_dword %2, %4, %7\n\t"
+      "s_load_dword %3, %4, %8\n\ts_waitcnt lgkmcnt(0)"
+      : "=&s"(v0), "=&s"(v1), "=&s"(v2), "=&s"(v3)
+      : "s"(p), "s"(o0), "s"(o1), "s"(o2), "s"(o3)
+      : "memory");
+}
+
 struct Tables {
   const int32_t *__restrict__ plan;
   const int32_t *__restrict__ offsets;
@@ -218,12 +237,12 @@ __device__ __forceinline__ Entry load_entry(const StreamArgs &a, const Tables &t
     const int entry = (id - c.n_sh) / per;
     int e, tbk = 0;
     if (WIDE) {
-      e = sload(tb_.plan, PLAN_HDR + a.E + 2 * entry);
-      tbk = sload(tb_.plan, PLAN_HDR + a.E + 2 * entry + 1);
+      sload2(tb_.plan, PLAN_HDR + a.E + 2 * entry, PLAN_HDR + a.E + 2 * entry + 1, e, tbk);
     } else {
       e = sload(tb_.plan, PLAN_HDR + entry);
     }
-    const int beg = sload(tb_.offsets, e), end = sload(tb_.offsets, e + 1);
+    int beg, end;
+    sload2(tb_.offsets, e, e + 1, beg, end);
     en.row0 = beg + tbk * rows;
     en.m = min(end - en.row0, rows);
     en.tiles = per;
@@ -256,26 +275,30 @@ template <int MODE, bool WIDE>
 __device__ __forceinline__ void setup_b(LoadPtrs<WIDE> &lp, const Entry &en,
                                         const int32_t *__restrict__ row_token, int wave, int lane) {
   if (!WIDE) {
+    int tok[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) tok[i] = en.row0 + min(wave * 4 + i, en.m - 1);  // token rows of the tile
+    if (en.use_map) sload4(row_token, tok[0], tok[1], tok[2], tok[3], tok[0], tok[1], tok[2], tok[3]);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int r = wave * 4 + i;  // token row of the tile
-      int tok = en.row0 + min(r, en.m - 1);
-      if (en.use_map) tok = sload(row_token, tok);
-      lp.b[i] = en.b + (size_t)tok * en.b_stride + ((lane ^ (r & 15)) << 3);
+      const int r = wave * 4 + i;
+      lp.b[i] = en.b + (size_t)tok[i] * en.b_stride + ((lane ^ (r & 15)) << 3);
     }
   } else {
     const int half = lane >> 5, pos = lane & 31;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int pair = wave * 8 + i;  // token rows 2*pair, 2*pair+1
-      int ta = en.row0 + min(2 * pair, en.m - 1), tb = en.row0 + min(2 * pair + 1, en.m - 1);
-      if (en.use_map) {
-        ta = sload(row_token, ta);
-        tb = sload(row_token, tb);
+    for (int i = 0; i < 8; i += 2) {
+      const int pair = wave * 8 + i;  // token rows 2*pair .. 2*pair+3 of this and the next instruction
+      int t4[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) t4[j] = en.row0 + min(2 * pair + j, en.m - 1);
+      if (en.use_map) sload4(row_token, t4[0], t4[1], t4[2], t4[3], t4[0], t4[1], t4[2], t4[3]);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int tok = half ? t4[2 * j + 1] : t4[2 * j];
+        const int r = 2 * (pair + j) + half;
+        lp.b[i + j] = en.b + (size_t)tok * en.b_stride + ((pos ^ (r & 15)) << 3);
       }
-      const int tok = half ? tb : ta;
-      const int r = 2 * pair + half;
-      lp.b[i] = en.b + (size_t)tok * en.b_stride + ((pos ^ (r & 15)) << 3);
     }
   }
 }
@@ -446,7 +469,7 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
   // ---- compute cursor -----------------------------------------------------------------
   int c_i = 0, c_kb = 0, c_slot = 0;
   int c_sub = 0;
-  Entry cen = load_entry<MODE, WIDE>(a, tb_, c, c.id0);
+  Entry cen = len;
   f32x4 acc0[NACC], acc1[NACC];
 #pragma unroll
   for (int nt = 0; nt < NACC; ++nt) {
@@ -643,7 +666,8 @@ __global__ __launch_bounds__(256) void expert_stream_kernel(StreamArgs a,
   // ---- the schedule ---------------------------------------------------------------
   // wide tiles: [shared expert's, if it has more than 16 rows][big routed entries]
   // small tiles: [shared expert's, if it has at most 16 rows][small routed entries]
-  const int n_small_e = sload(plan, 0), n_big_e = sload(plan, 1);
+  int n_small_e, n_big_e;
+  sload2(plan, 0, 1, n_small_e, n_big_e);
   const bool has_shared = a.S > 0;
   const bool shared_wide = a.T > SMALL_M && a.shared_stream;   // otherwise the tiled kernel takes it
   const bool shared_small = a.T <= SMALL_M;
