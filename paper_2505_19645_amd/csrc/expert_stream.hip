@@ -54,6 +54,7 @@
 #define SMALL_M 16
 #define BIG_TB 64
 #define STREAM_LDS_BYTES (RING * SLOT_BYTES + RED_BYTES)
+#define STREAM_THREADS 512  // waves 0..3 multiply, waves 4..7 load
 // small tiles
 #define KB 512             // contraction elements per block
 #define SROW_BYTES 1024
@@ -434,220 +435,232 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
   constexpr int RG = WIDE ? WRING : RING, AH = WIDE ? WAHEAD : AHEAD, LWN = WIDE ? WLW : LW;
   constexpr int SLOTB = WIDE ? WSLOT_BYTES : SLOT_BYTES;
 
-  // ---- load cursor -------------------------------------------------------------------
-  int l_i = 0, l_kb = 0, l_slot = 0;
-  int l_sub = 0;  // wide: 0 tokens, 1 first operand half, 2 second
-  Entry len = load_entry<MODE, WIDE>(a, tb_, c, c.id0);
-  LoadPtrs<WIDE> lp;
-  setup_b<MODE, WIDE>(lp, len, tb_.row_token, wave, lane);
-  setup_a<MODE, WIDE>(lp, len, c.id0 - len.first, wave, lane);
-  bool l_live = true;
+  if (wave >= 4) {
+    // ---- loading waves: the load cursor ----------------------------------------------
+    const int lw = wave - 4;
+    unsigned long long single = 0ull;  // bit s & 63: slot s is the only one of its tile
+    int l_i = 0, l_kb = 0, l_slot = 0;
+    int l_sub = 0;  // wide: 0 tokens, 1 first operand half, 2 second
+    Entry len = load_entry<MODE, WIDE>(a, tb_, c, c.id0);
+    LoadPtrs<WIDE> lp;
+    setup_b<MODE, WIDE>(lp, len, tb_.row_token, lw, lane);
+    setup_a<MODE, WIDE>(lp, len, c.id0 - len.first, lw, lane);
+    bool l_live = true;
 
-  auto advance_load = [&]() __attribute__((always_inline)) {
-    issue_slot<MODE, WIDE>(lp, len, l_kb, l_sub, lds0 + (uint32_t)(l_slot % RG) * SLOTB, wave, lane);
-    ++l_slot;
-    if (WIDE && l_sub < WNW) {
-      ++l_sub;
-      return;
-    }
-    l_sub = 0;
-    if (++l_kb == len.nkb) {
-      l_kb = 0;
-      if (++l_i == c.n_mine) {
-        l_live = false;
+    auto advance_load = [&]() __attribute__((always_inline)) {
+      issue_slot<MODE, WIDE>(lp, len, l_kb, l_sub, lds0 + (uint32_t)(l_slot % RG) * SLOTB, lw, lane);
+      // a tile of one slot: the multiplying waves put one more barrier into that slot's step
+      if (!WIDE) single = (single & ~(1ull << (l_slot & 63))) | ((unsigned long long)(len.nkb == 1) << (l_slot & 63));
+      ++l_slot;
+      if (WIDE && l_sub < WNW) {
+        ++l_sub;
         return;
       }
-      const int id = c.id0 + l_i * c.stride;
-      if (id - len.first >= len.tiles || id < len.first) {
-        len = load_entry<MODE, WIDE>(a, tb_, c, id);
-        setup_b<MODE, WIDE>(lp, len, tb_.row_token, wave, lane);
+      l_sub = 0;
+      if (++l_kb == len.nkb) {
+        l_kb = 0;
+        if (++l_i == c.n_mine) {
+          l_live = false;
+          return;
+        }
+        const int id = c.id0 + l_i * c.stride;
+        if (id - len.first >= len.tiles || id < len.first) {
+          len = load_entry<MODE, WIDE>(a, tb_, c, id);
+          setup_b<MODE, WIDE>(lp, len, tb_.row_token, lw, lane);
+        }
+        setup_a<MODE, WIDE>(lp, len, id - len.first, lw, lane);
       }
-      setup_a<MODE, WIDE>(lp, len, id - len.first, wave, lane);
+    };
+
+    for (int i = 0; i < AH && l_live; ++i) advance_load();
+    int k = 0;  // the slot whose step this is
+    while (k < l_slot) {
+      // slot k must have landed: at most AH-1 younger slots may be pending
+      if (l_slot - k == AH) wait_vm<(AH - 1) * LWN>();
+      else wait_vm<0>();
+      wg_barrier();  // slot k is in LDS for the multiplying waves; they are done with slot k-1
+      if (l_live) advance_load();
+      if (!WIDE && ((single >> (k & 63)) & 1ull)) wg_barrier();
+      ++k;
     }
-  };
-
-  // ---- compute cursor -----------------------------------------------------------------
-  int c_i = 0, c_kb = 0, c_slot = 0;
-  int c_sub = 0;
-  Entry cen = len;
-  f32x4 acc0[NACC], acc1[NACC];
+    if (!WIDE) wg_barrier();  // the last tile's reduction
+  } else {
+    // ---- multiplying waves: the compute cursor -------------------------------------------
+    int c_i = 0, c_kb = 0, c_slot = 0;
+    int c_sub = 0;
+    Entry cen = load_entry<MODE, WIDE>(a, tb_, c, c.id0);
+    f32x4 acc0[NACC], acc1[NACC];
 #pragma unroll
-  for (int nt = 0; nt < NACC; ++nt) {
-    acc0[nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    acc1[nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
-  }
-  // a finished small tile whose partial sums wait in `red` for the next barrier
-  bool pend = false;
-  int pend_m = 0, pend_row0 = 0, pend_i0 = 0, pend_n = 0;
-  void *pend_out = nullptr;
-
-  // After a barrier: add the waves' partial tiles.  Thread t takes token row t >> 4 and feature
-  // t & 15 (of both halves), so 16 neighbouring lanes store 16 neighbouring features of a row.
-  auto flush_pending = [&]() __attribute__((always_inline)) {
-    const int j = tid >> 4, fi = tid & 15;
-    float s0 = 0.f, s1 = 0.f;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      s0 += red[(w * 2 + 0) * RED_TILE + j * RED_ROW + fi];
-      s1 += red[(w * 2 + 1) * RED_TILE + j * RED_ROW + fi];
+    for (int nt = 0; nt < NACC; ++nt) {
+      acc0[nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      acc1[nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
     }
-    if (j < pend_m) store_out<MODE>(pend_out, pend_n, (size_t)(pend_row0 + j), pend_i0 + fi, 16, s0, s1);
-    pend = false;
-  };
+    // a finished small tile whose partial sums wait in `red` for the next barrier
+    bool pend = false;
+    int pend_m = 0, pend_row0 = 0, pend_i0 = 0, pend_n = 0;
+    void *pend_out = nullptr;
 
-  // (5 of the 6 slots in flight for the small tiles measured the same as 4)
-  for (int i = 0; i < AH && l_live; ++i) advance_load();
+    // After a barrier: add the waves' partial tiles.  Thread t takes token row t >> 4 and feature
+    // t & 15 (of both halves), so 16 neighbouring lanes store 16 neighbouring features of a row.
+    auto flush_pending = [&]() __attribute__((always_inline)) {
+      const int j = tid >> 4, fi = tid & 15;
+      float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        s0 += red[(w * 2 + 0) * RED_TILE + j * RED_ROW + fi];
+        s1 += red[(w * 2 + 1) * RED_TILE + j * RED_ROW + fi];
+      }
+      if (j < pend_m) store_out<MODE>(pend_out, pend_n, (size_t)(pend_row0 + j), pend_i0 + fi, 16, s0, s1);
+      pend = false;
+    };
 
-  // wide: waves as 2 (row halves of a slot) x 2 (token halves); the wave's 2 x 16 token rows of the
-  // current block, all 8 steps, stay in registers
-  u32x4 fbw[WIDE ? 2 : 1][WIDE ? 8 : 1];
-  f32x4 accw[WIDE ? WNW : 1][2][2];  // [weight slot][row tile of the wave][token tile of the wave]
+    // wide: waves as 2 (row halves of a slot) x 2 (token halves); the wave's 2 x 16 token rows of the
+    // current block, all 8 steps, stay in registers
+    u32x4 fbw[WIDE ? 2 : 1][WIDE ? 8 : 1];
+    f32x4 accw[WIDE ? WNW : 1][2][2];  // [weight slot][row tile of the wave][token tile of the wave]
 #pragma unroll
-  for (int w = 0; w < (WIDE ? WNW : 1); ++w)
+    for (int w = 0; w < (WIDE ? WNW : 1); ++w)
 #pragma unroll
-    for (int i = 0; i < 4; ++i) accw[w][i >> 1][i & 1] = (f32x4){0.f, 0.f, 0.f, 0.f};
-  const int wr = wave & 1, wt = wave >> 1;
+      for (int i = 0; i < 4; ++i) accw[w][i >> 1][i & 1] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    const int wr = wave & 1, wt = wave >> 1;
 
-  while (true) {
-    // slot c_slot must have landed: at most AH-1 younger slots may be pending
-    if (l_slot - c_slot == AH) wait_vm<(AH - 1) * LWN>();
-    else wait_vm<0>();
-    wg_barrier();
-    if (l_live) advance_load();
-    if (!WIDE && pend) flush_pending();
+    while (true) {
+      wg_barrier();  // slot c_slot has landed (the loading waves waited for it)
+      if (!WIDE && pend) flush_pending();
 
-    const char *sb = smem + (size_t)(c_slot % RG) * SLOTB;
-    bool tile_done = false;
-    if (!WIDE) {
-      const int kbase = c_kb * KB;
-      // waves split the 16 steps
-      if (kbase + KB <= cen.klen) {  // whole block: no masks, reads issued back to back
-        u32x4 fa0[4], fa1[4], fb[4];
+      const char *sb = smem + (size_t)(c_slot % RG) * SLOTB;
+      bool tile_done = false;
+      if (!WIDE) {
+        const int kbase = c_kb * KB;
+        // waves split the 16 steps
+        if (kbase + KB <= cen.klen) {  // whole block: no masks, reads issued back to back
+          u32x4 fa0[4], fa1[4], fb[4];
 #pragma unroll
-        for (int ss = 0; ss < 4; ++ss) {
-          const int piece = 4 * (wave * 4 + ss) + q;
-          const int off = r16 * SROW_BYTES + ((piece ^ r16) << 4);
-          fa0[ss] = *reinterpret_cast<const u32x4 *>(sb + off);
-          fa1[ss] = *reinterpret_cast<const u32x4 *>(sb + 16 * SROW_BYTES + off);
-          fb[ss] = *reinterpret_cast<const u32x4 *>(sb + A_BYTES + off);
-        }
-#pragma unroll
-        for (int ss = 0; ss < 4; ++ss) {
-          acc0[0] = mfma16(fa0[ss], fb[ss], acc0[0]);
-          acc1[0] = mfma16(fa1[ss], fb[ss], acc1[0]);
-        }
-      } else {
-#pragma unroll
-        for (int ss = 0; ss < 4; ++ss) {
-          const int s = wave * 4 + ss;
-          if (kbase + s * 32 < cen.klen) {
-            const int piece = 4 * s + q;
+          for (int ss = 0; ss < 4; ++ss) {
+            const int piece = 4 * (wave * 4 + ss) + q;
             const int off = r16 * SROW_BYTES + ((piece ^ r16) << 4);
-            const u32x4 fa0 = *reinterpret_cast<const u32x4 *>(sb + off);
-            const u32x4 fa1 = *reinterpret_cast<const u32x4 *>(sb + 16 * SROW_BYTES + off);
-            u32x4 fb = *reinterpret_cast<const u32x4 *>(sb + A_BYTES + off);
-            if (kbase + piece * 8 >= cen.klen) fb = (u32x4){0u, 0u, 0u, 0u};  // ragged last step
-            acc0[0] = mfma16(fa0, fb, acc0[0]);
-            acc1[0] = mfma16(fa1, fb, acc1[0]);
+            fa0[ss] = *reinterpret_cast<const u32x4 *>(sb + off);
+            fa1[ss] = *reinterpret_cast<const u32x4 *>(sb + 16 * SROW_BYTES + off);
+            fb[ss] = *reinterpret_cast<const u32x4 *>(sb + A_BYTES + off);
           }
-        }
-      }
-      tile_done = (c_kb == cen.nkb - 1);
-      ++c_kb;
-    } else {
-      // Wave (wr, wt) multiplies token rows 32wt .. 32wt+31 by rows 32wr .. 32wr+31 of every weight
-      // slot.  The token fragments of a block stay in registers, so the token slot is free again as
-      // soon as it has been read, like every weight slot; nothing is added across waves.
-      const bool busy = 32 * wt < cen.m;  // (a wave without token rows only keeps the barriers)
-      if (c_sub == 0) {
-        if (busy) {
-          const int kbase = c_kb * KBW;
 #pragma unroll
-          for (int tt = 0; tt < 2; ++tt) {
-            const char *pb = sb + (size_t)(32 * wt + 16 * tt + r16) * ROW_BYTES;
+          for (int ss = 0; ss < 4; ++ss) {
+            acc0[0] = mfma16(fa0[ss], fb[ss], acc0[0]);
+            acc1[0] = mfma16(fa1[ss], fb[ss], acc1[0]);
+          }
+        } else {
 #pragma unroll
-            for (int st = 0; st < 8; ++st) {
-              const int piece = 4 * st + q;
-              fbw[tt][st] = *reinterpret_cast<const u32x4 *>(pb + ((piece ^ r16) << 4));
-              // ragged last block: pieces past the row's end hold bytes pulled back from inside it
-              if (kbase + piece * 8 >= cen.klen) fbw[tt][st] = (u32x4){0u, 0u, 0u, 0u};
+          for (int ss = 0; ss < 4; ++ss) {
+            const int s = wave * 4 + ss;
+            if (kbase + s * 32 < cen.klen) {
+              const int piece = 4 * s + q;
+              const int off = r16 * SROW_BYTES + ((piece ^ r16) << 4);
+              const u32x4 fa0 = *reinterpret_cast<const u32x4 *>(sb + off);
+              const u32x4 fa1 = *reinterpret_cast<const u32x4 *>(sb + 16 * SROW_BYTES + off);
+              u32x4 fb = *reinterpret_cast<const u32x4 *>(sb + A_BYTES + off);
+              if (kbase + piece * 8 >= cen.klen) fb = (u32x4){0u, 0u, 0u, 0u};  // ragged last step
+              acc0[0] = mfma16(fa0, fb, acc0[0]);
+              acc1[0] = mfma16(fa1, fb, acc1[0]);
             }
           }
         }
-      } else if (busy) {
-#pragma unroll
-        for (int w = 0; w < WNW; ++w)
-          if (c_sub == w + 1) {
-#pragma unroll
-            for (int rtl = 0; rtl < 2; ++rtl) {
-              const char *pa = sb + (size_t)(16 * (2 * wr + rtl) + r16) * ROW_BYTES;
-              u32x4 fa[8];
-#pragma unroll
-              for (int st = 0; st < 8; ++st)
-                fa[st] = *reinterpret_cast<const u32x4 *>(pa + (((4 * st + q) ^ r16) << 4));
-#pragma unroll
-              for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-                for (int st = 0; st < 8; ++st) accw[w][rtl][tt] = mfma16(fa[st], fbw[tt][st], accw[w][rtl][tt]);
-            }
-          }
-      }
-      if (c_sub == WNW) {
         tile_done = (c_kb == cen.nkb - 1);
         ++c_kb;
-        c_sub = 0;
       } else {
-        ++c_sub;
-      }
-    }
-    ++c_slot;
-
-    if (tile_done) {
-      const int id = c.id0 + c_i * c.stride;
-      const int i0 = tile_i0<MODE, WIDE>(id - cen.first);
-      if (WIDE) {
-        // straight from the accumulators: token row 32wt + 16tt + r16; slot w < WNW/2 pairs with slot
-        // w + WNW/2 (gate with up rows; down: WHROWS features further on)
+        // Wave (wr, wt) multiplies token rows 32wt .. 32wt+31 by rows 32wr .. 32wr+31 of every weight
+        // slot.  The token fragments of a block stay in registers, so the token slot is free again as
+        // soon as it has been read, like every weight slot; nothing is added across waves.
+        const bool busy = 32 * wt < cen.m;  // (a wave without token rows only keeps the barriers)
+        if (c_sub == 0) {
+          if (busy) {
+            const int kbase = c_kb * KBW;
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-          const int j = 32 * wt + 16 * tt + r16;
-          if (j < cen.m) {
+            for (int tt = 0; tt < 2; ++tt) {
+              const char *pb = sb + (size_t)(32 * wt + 16 * tt + r16) * ROW_BYTES;
 #pragma unroll
-            for (int w = 0; w < WNW / 2; ++w)
-#pragma unroll
-              for (int rtl = 0; rtl < 2; ++rtl)
-                store_out4<MODE>(cen.out, cen.out_n, (size_t)(cen.row0 + j),
-                                 i0 + 64 * w + 16 * (2 * wr + rtl) + 4 * q, WHROWS, accw[w][rtl][tt],
-                                 accw[w + WNW / 2][rtl][tt]);
+              for (int st = 0; st < 8; ++st) {
+                const int piece = 4 * st + q;
+                fbw[tt][st] = *reinterpret_cast<const u32x4 *>(pb + ((piece ^ r16) << 4));
+                // ragged last block: pieces past the row's end hold bytes pulled back from inside it
+                if (kbase + piece * 8 >= cen.klen) fbw[tt][st] = (u32x4){0u, 0u, 0u, 0u};
+              }
+            }
           }
+        } else if (busy) {
+#pragma unroll
+          for (int w = 0; w < WNW; ++w)
+            if (c_sub == w + 1) {
+#pragma unroll
+              for (int rtl = 0; rtl < 2; ++rtl) {
+                const char *pa = sb + (size_t)(16 * (2 * wr + rtl) + r16) * ROW_BYTES;
+                u32x4 fa[8];
+#pragma unroll
+                for (int st = 0; st < 8; ++st)
+                  fa[st] = *reinterpret_cast<const u32x4 *>(pa + (((4 * st + q) ^ r16) << 4));
+#pragma unroll
+                for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+                  for (int st = 0; st < 8; ++st) accw[w][rtl][tt] = mfma16(fa[st], fbw[tt][st], accw[w][rtl][tt]);
+              }
+            }
         }
-#pragma unroll
-        for (int w = 0; w < WNW; ++w)
-#pragma unroll
-          for (int i = 0; i < 4; ++i) accw[w][i >> 1][i & 1] = (f32x4){0.f, 0.f, 0.f, 0.f};
-      } else {
-        if (cen.nkb == 1) wg_barrier();  // the previous tile's sums may still be read from `red`
-        // lane (q, r16) holds features 4q..4q+3 of token row r16: one 16-byte store per half
-        *reinterpret_cast<f32x4 *>(red + (wave * 2 + 0) * RED_TILE + r16 * RED_ROW + 4 * q) = acc0[0];
-        *reinterpret_cast<f32x4 *>(red + (wave * 2 + 1) * RED_TILE + r16 * RED_ROW + 4 * q) = acc1[0];
-        pend = true;
-        pend_m = cen.m;
-        pend_row0 = cen.row0;
-        pend_i0 = i0;
-        pend_n = cen.out_n;
-        pend_out = cen.out;
-        acc0[0] = (f32x4){0.f, 0.f, 0.f, 0.f};
-        acc1[0] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        if (c_sub == WNW) {
+          tile_done = (c_kb == cen.nkb - 1);
+          ++c_kb;
+          c_sub = 0;
+        } else {
+          ++c_sub;
+        }
       }
-      c_kb = 0;
-      if (++c_i == c.n_mine) break;
-      const int nid = c.id0 + c_i * c.stride;
-      if (nid - cen.first >= cen.tiles || nid < cen.first) cen = load_entry<MODE, WIDE>(a, tb_, c, nid);
+      ++c_slot;
+
+      if (tile_done) {
+        const int id = c.id0 + c_i * c.stride;
+        const int i0 = tile_i0<MODE, WIDE>(id - cen.first);
+        if (WIDE) {
+          // straight from the accumulators: token row 32wt + 16tt + r16; slot w < WNW/2 pairs with slot
+          // w + WNW/2 (gate with up rows; down: WHROWS features further on)
+#pragma unroll
+          for (int tt = 0; tt < 2; ++tt) {
+            const int j = 32 * wt + 16 * tt + r16;
+            if (j < cen.m) {
+#pragma unroll
+              for (int w = 0; w < WNW / 2; ++w)
+#pragma unroll
+                for (int rtl = 0; rtl < 2; ++rtl)
+                  store_out4<MODE>(cen.out, cen.out_n, (size_t)(cen.row0 + j),
+                                   i0 + 64 * w + 16 * (2 * wr + rtl) + 4 * q, WHROWS, accw[w][rtl][tt],
+                                   accw[w + WNW / 2][rtl][tt]);
+            }
+          }
+#pragma unroll
+          for (int w = 0; w < WNW; ++w)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) accw[w][i >> 1][i & 1] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        } else {
+          if (cen.nkb == 1) wg_barrier();  // the previous tile's sums may still be read from `red`
+          // lane (q, r16) holds features 4q..4q+3 of token row r16: one 16-byte store per half
+          *reinterpret_cast<f32x4 *>(red + (wave * 2 + 0) * RED_TILE + r16 * RED_ROW + 4 * q) = acc0[0];
+          *reinterpret_cast<f32x4 *>(red + (wave * 2 + 1) * RED_TILE + r16 * RED_ROW + 4 * q) = acc1[0];
+          pend = true;
+          pend_m = cen.m;
+          pend_row0 = cen.row0;
+          pend_i0 = i0;
+          pend_n = cen.out_n;
+          pend_out = cen.out;
+          acc0[0] = (f32x4){0.f, 0.f, 0.f, 0.f};
+          acc1[0] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        }
+        c_kb = 0;
+        if (++c_i == c.n_mine) break;
+        const int nid = c.id0 + c_i * c.stride;
+        if (nid - cen.first >= cen.tiles || nid < cen.first) cen = load_entry<MODE, WIDE>(a, tb_, c, nid);
+      }
     }
-  }
-  if (!WIDE && pend) {
-    wg_barrier();
-    flush_pending();
+    if (!WIDE && pend) {
+      wg_barrier();
+      flush_pending();
+    }
   }
   // nothing pending, every wave done reading the ring: the next class may reuse it
   wait_vm<0>();
@@ -655,7 +668,7 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
 }
 
 template <int MODE>
-__global__ __launch_bounds__(256) void expert_stream_kernel(StreamArgs a,
+__global__ __launch_bounds__(STREAM_THREADS) void expert_stream_kernel(StreamArgs a,
                                                             const int32_t *__restrict__ plan,
                                                             const int32_t *__restrict__ offsets,
                                                             const int32_t *__restrict__ row_token) {
@@ -746,10 +759,10 @@ static hipError_t launch_stream(int mode, const StreamArgs &a, hipStream_t s) {
     attr_set[mode] = true;
   }
   if (mode == MODE_GATE_UP)
-    hipLaunchKernelGGL(expert_stream_kernel<MODE_GATE_UP>, dim3(n_cu), dim3(256), STREAM_LDS_BYTES, s, a,
+    hipLaunchKernelGGL(expert_stream_kernel<MODE_GATE_UP>, dim3(n_cu), dim3(STREAM_THREADS), STREAM_LDS_BYTES, s, a,
                        a.plan, a.offsets, a.row_token);
   else
-    hipLaunchKernelGGL(expert_stream_kernel<MODE_DOWN>, dim3(n_cu), dim3(256), STREAM_LDS_BYTES, s, a,
+    hipLaunchKernelGGL(expert_stream_kernel<MODE_DOWN>, dim3(n_cu), dim3(STREAM_THREADS), STREAM_LDS_BYTES, s, a,
                        a.plan, a.offsets, a.row_token);
   return hipGetLastError();
 }
