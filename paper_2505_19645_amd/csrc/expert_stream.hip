@@ -73,7 +73,7 @@
 #endif                     // faster where tiles abound and much slower where they are few)
 #define WHROWS (32 * WNW)  // rows of each operand half in a wide tile
 // the schedule's cost model, in hundredths of a routed expert's small slot
-#define COST_WIDE_SLOT 120
+#define COST_WIDE_SLOT 100
 #define COST_CLASS_SWITCH 650
 #define COST_DISTINCT_ROWS 15
 
@@ -699,10 +699,10 @@ __global__ __launch_bounds__(STREAM_THREADS) void expert_stream_kernel(StreamArg
   {
     // Wide tiles are dealt round-robin; the small line is then cut so that every workgroup's
     // estimated time is the same.  Costs in hundredths of the time of one small slot of a routed
-    // expert, from per-workgroup timelines on the MI355X: a byte of a wide slot takes about 1.2x as
-    // long as one of a small slot (more LDS traffic per byte), moving from the wide to the
-    // small class drains and refills the ring (about 6 slots), and a small slot whose 16 token
-    // rows are all distinct (the shared expert at T = 16) takes 1.15x as long as one with a few.
+    // expert, from per-workgroup timelines on the MI355X: a byte of a wide slot takes as long as one
+    // of a small slot, moving from the wide to the small class drains and refills the ring (about 6
+    // slots), and a small slot whose 16 token rows are all distinct (the shared expert at T = 16)
+    // takes 1.15x as long as one with a few.
     const int kr = (MODE == MODE_GATE_UP) ? a.d : a.I;
     const long nkb_s = (kr + KB - 1) / KB, nkb_w = (kr + KBW - 1) / KBW;
     const long c_wide = nkb_w * (WNW + 1) * 2 * COST_WIDE_SLOT / 3;  // a wide slot is 2/3 of a small one
