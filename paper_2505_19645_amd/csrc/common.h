@@ -50,10 +50,13 @@ __device__ __forceinline__ float silu_f32(float z) {
 //   [1] n_big:   (expert, 64-row block) entries of the experts with 17..128 rows (17..64 when
 //                enough experts exceed 64 rows for the tiled kernels to be worth it)
 //   [2] n_large: (expert, 256-row block) entries of the experts with more rows than that
+//   [PLAN_CTR], [PLAN_CTR+1]  zero: the counters from which the gate/up and the down streaming
+//                kernel draw units of tiles
 //   [PLAN_HDR .. +E)        ids of the small experts, ascending
 //   [PLAN_HDR+E .. +4E)     n_big pairs (expert id, block index), ascending by expert, block
 //   [PLAN_HDR+5E .. )       n_large pairs (expert id, block index), ascending by expert, block
-#define PLAN_HDR 4
+#define PLAN_HDR 8
+#define PLAN_CTR 4
 #define PLAN_BIG_MAX_ROWS 128
 #define PLAN_LARGE_OFF(E) (PLAN_HDR + 5 * (E))
 #define PLAN_WORDS(E, TK) (PLAN_LARGE_OFF(E) + 2 * ((E) + (TK) / 256 + 2))

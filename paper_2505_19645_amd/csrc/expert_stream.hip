@@ -53,7 +53,7 @@
 #define RED_BYTES (8 * RED_TILE * 4)  // 4 waves x 2 halves x 16 rows
 #define SMALL_M 16
 #define BIG_TB 64
-#define STREAM_LDS_BYTES (RING * SLOT_BYTES + RED_BYTES)
+#define STREAM_LDS_BYTES (RING * SLOT_BYTES + RED_BYTES + 64)  // + the four words that carry drawn units
 #define STREAM_THREADS 512  // waves 0..3 multiply, waves 4..7 load
 // small tiles
 #define KB 512             // contraction elements per block
@@ -76,6 +76,15 @@
 #define COST_WIDE_SLOT 100
 #define COST_CLASS_SWITCH 650
 #define COST_DISTINCT_ROWS 15
+#ifndef DYN_STATIC_PCT
+#define DYN_STATIC_PCT 60  // share of a long small line that is dealt in fixed ranges (100: all of it)
+#endif
+#ifndef DYN_MIN_SLOTS
+#define DYN_MIN_SLOTS 72   // slots of small tiles per workgroup from which units are drawn at all
+#endif
+#ifndef DYN_MIN_TILES
+#define DYN_MIN_TILES 12   // and small tiles per workgroup (a few long tiles are better dealt evenly)
+#endif
 
 enum { MODE_GATE_UP = 0, MODE_DOWN = 1 };
 
@@ -215,7 +224,26 @@ struct ClassCfg {
   int per_s;   // row tiles per shared entry
   int per_r;   // row tiles per routed entry
   int parts;   // k-parts of the shared down projection (1 for gate/up)
+  // Small tiles only: after its own range (n_mine tiles from id0) the workgroup draws units of
+  // further tiles from a counter shared by all workgroups.  Units u < n_double hold 2 * ut tiles,
+  // the others ut, the last one also what is left of the line; all lie in [pool0, n_tiles).
+  int dyn;
+  int n_units, n_double, ut, pool0, n_tiles;
+  int32_t *ctr;
 };
+
+// tiles [t0, t1) of drawn unit u; empty when the counter has run past the last unit
+__device__ __forceinline__ void unit_range(const ClassCfg &c, int u, int &t0, int &t1) {
+  if (u < 0 || u >= c.n_units) {
+    t0 = t1 = 0;
+  } else if (u < c.n_double) {
+    t0 = c.pool0 + u * 2 * c.ut;
+    t1 = t0 + 2 * c.ut;
+  } else {
+    t0 = c.pool0 + c.n_double * 2 * c.ut + (u - c.n_double) * c.ut;
+    t1 = (u == c.n_units - 1) ? c.n_tiles : t0 + c.ut;
+  }
+}
 
 // entry that owns tile `id` of the class
 template <int MODE, bool WIDE>
@@ -425,12 +453,31 @@ __device__ __forceinline__ void store_out4(void *out, int out_n, size_t orow, in
 template <int MODE, bool WIDE>
 __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_, const ClassCfg &c,
                                           char *smem) {
-  if (c.n_mine <= 0) return;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = uni(tid >> 6);
   const int r16 = lane & 15, q = lane >> 4;
   const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
   float *red = reinterpret_cast<float *>(smem + RING * SLOT_BYTES);
+  // Units drawn from the counter travel from the multiplying waves (wave 0 draws) to the loading
+  // waves through four words of LDS: unit n of this workgroup in word n & 3.  (An LDS pointer by
+  // type, so that the accesses are ds operations, which no vector-memory wait guards; the barriers
+  // between a write and its reads are compiler memory fences as well.)
+  typedef __attribute__((address_space(3))) int lds_int;
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Wint-to-pointer-cast"
+  lds_int *mbox = (lds_int *)(lds0 + (uint32_t)(RING * SLOT_BYTES + RED_BYTES));
+#pragma clang diagnostic pop
+  const bool dyn = !WIDE && c.dyn;
+  // unit 0: the workgroup's own range; if that is empty and units can be drawn, the first drawn one
+  int first_t0 = c.id0, first_t1 = c.id0 + c.n_mine;
+  if (dyn && c.n_mine <= 0) {
+    if (tid == 0) mbox[0] = (int)atomicAdd(c.ctr, 1);
+    __syncthreads();
+    unit_range(c, mbox[0], first_t0, first_t1);
+    if (first_t0 >= first_t1) return;  // (the same for every wave)
+  } else if (c.n_mine <= 0) {
+    return;
+  }
   constexpr int NACC = 1;  // (small tiles; the wide tiles keep theirs in accw)
   constexpr int RG = WIDE ? WRING : RING, AH = WIDE ? WAHEAD : AHEAD, LWN = WIDE ? WLW : LW;
   constexpr int SLOTB = WIDE ? WSLOT_BYTES : SLOT_BYTES;
@@ -441,13 +488,34 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
     unsigned long long single = 0ull;  // bit s & 63: slot s is the only one of its tile
     int l_i = 0, l_kb = 0, l_slot = 0;
     int l_sub = 0;  // wide: 0 tokens, 1 first operand half, 2 second
-    Entry len = load_entry<MODE, WIDE>(a, tb_, c, c.id0);
+    int l_id = dyn ? first_t0 : c.id0, l_end = first_t1, l_n = 0;  // (dyn: tile, end of its unit, unit number)
+    bool l_need = false;  // dyn: the unit is used up, the next one is fetched when its first slot is due
+    Entry len = load_entry<MODE, WIDE>(a, tb_, c, l_id);
     LoadPtrs<WIDE> lp;
     setup_b<MODE, WIDE>(lp, len, tb_.row_token, lw, lane);
-    setup_a<MODE, WIDE>(lp, len, c.id0 - len.first, lw, lane);
+    setup_a<MODE, WIDE>(lp, len, l_id - len.first, lw, lane);
     bool l_live = true;
 
+    auto open_tile = [&](int id) __attribute__((always_inline)) {
+      if (id - len.first >= len.tiles || id < len.first) {
+        len = load_entry<MODE, WIDE>(a, tb_, c, id);
+        setup_b<MODE, WIDE>(lp, len, tb_.row_token, lw, lane);
+      }
+      setup_a<MODE, WIDE>(lp, len, id - len.first, lw, lane);
+    };
     auto advance_load = [&]() __attribute__((always_inline)) {
+      if (dyn && l_need) {
+        // Written by wave 0 during the first step of the unit just loaded, which lies at least one
+        // barrier back: every unit has at least three slots and this slot is due two steps ahead.
+        ++l_n;
+        unit_range(c, mbox[l_n & 3], l_id, l_end);
+        if (l_id >= l_end) {
+          l_live = false;
+          return;
+        }
+        l_need = false;
+        open_tile(l_id);
+      }
       issue_slot<MODE, WIDE>(lp, len, l_kb, l_sub, lds0 + (uint32_t)(l_slot % RG) * SLOTB, lw, lane);
       // a tile of one slot: the multiplying waves put one more barrier into that slot's step
       if (!WIDE) single = (single & ~(1ull << (l_slot & 63))) | ((unsigned long long)(len.nkb == 1) << (l_slot & 63));
@@ -459,16 +527,19 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
       l_sub = 0;
       if (++l_kb == len.nkb) {
         l_kb = 0;
-        if (++l_i == c.n_mine) {
-          l_live = false;
-          return;
+        if (dyn) {
+          if (++l_id == l_end) {
+            l_need = true;
+            return;
+          }
+        } else {
+          if (++l_i == c.n_mine) {
+            l_live = false;
+            return;
+          }
+          l_id = c.id0 + l_i * c.stride;
         }
-        const int id = c.id0 + l_i * c.stride;
-        if (id - len.first >= len.tiles || id < len.first) {
-          len = load_entry<MODE, WIDE>(a, tb_, c, id);
-          setup_b<MODE, WIDE>(lp, len, tb_.row_token, lw, lane);
-        }
-        setup_a<MODE, WIDE>(lp, len, id - len.first, lw, lane);
+        open_tile(l_id);
       }
     };
 
@@ -488,7 +559,9 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
     // ---- multiplying waves: the compute cursor -------------------------------------------
     int c_i = 0, c_kb = 0, c_slot = 0;
     int c_sub = 0;
-    Entry cen = load_entry<MODE, WIDE>(a, tb_, c, c.id0);
+    int c_id = dyn ? first_t0 : c.id0, c_end = first_t1, c_n = 0;
+    bool c_first = dyn;  // dyn: this is the first step of a unit
+    Entry cen = load_entry<MODE, WIDE>(a, tb_, c, c_id);
     f32x4 acc0[NACC], acc1[NACC];
 #pragma unroll
     for (int nt = 0; nt < NACC; ++nt) {
@@ -527,6 +600,20 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
     while (true) {
       wg_barrier();  // slot c_slot has landed (the loading waves waited for it)
       if (!WIDE && pend) flush_pending();
+      if (dyn && c_first) {
+        // First step of a unit: wave 0 draws the unit after this one and waits for the answer
+        // (the multiplying waves have time to spare: they wait for the loading waves at every
+        // barrier).  Keeping the answer pending in a register instead makes the compiler guard
+        // every later use of that register with a wait for all of the wave's stores.  The loading
+        // waves ask for the unit when this unit's last slot has been issued, at least one barrier
+        // later: a unit has three slots or more and slots are issued two steps ahead.
+        if (wave == 0) {
+          int u = 0;
+          if (lane == 0) u = (int)atomicAdd(c.ctr, 1);
+          if (lane == 0) mbox[(c_n + 1) & 3] = u;
+        }
+        c_first = false;
+      }
 
       const char *sb = smem + (size_t)(c_slot % RG) * SLOTB;
       bool tile_done = false;
@@ -615,7 +702,7 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
       ++c_slot;
 
       if (tile_done) {
-        const int id = c.id0 + c_i * c.stride;
+        const int id = c_id;
         const int i0 = tile_i0<MODE, WIDE>(id - cen.first);
         if (WIDE) {
           // straight from the accumulators: token row 32wt + 16tt + r16; slot w < WNW/2 pairs with slot
@@ -652,8 +739,18 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
           acc1[0] = (f32x4){0.f, 0.f, 0.f, 0.f};
         }
         c_kb = 0;
-        if (++c_i == c.n_mine) break;
-        const int nid = c.id0 + c_i * c.stride;
+        if (dyn) {
+          if (++c_id == c_end) {
+            ++c_n;
+            unit_range(c, mbox[c_n & 3], c_id, c_end);  // written at least one barrier ago
+            if (c_id >= c_end) break;
+            c_first = true;
+          }
+        } else {
+          if (++c_i == c.n_mine) break;
+          c_id = c.id0 + c_i * c.stride;
+        }
+        const int nid = c_id;
         if (nid - cen.first >= cen.tiles || nid < cen.first) cen = load_entry<MODE, WIDE>(a, tb_, c, nid);
       }
     }
@@ -667,7 +764,9 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
   wg_barrier();
 }
 
-template <int MODE>
+// DYN: the variant that can draw units of small tiles from the counter (the host launches the
+// other one, which is a little quicker to start, when the small line is certainly too short for it)
+template <int MODE, bool DYN>
 __global__ __launch_bounds__(STREAM_THREADS) void expert_stream_kernel(StreamArgs a,
                                                             const int32_t *__restrict__ plan,
                                                             const int32_t *__restrict__ offsets,
@@ -716,19 +815,49 @@ __global__ __launch_bounds__(STREAM_THREADS) void expert_stream_kernel(StreamArg
     cw.n_mine = k + (bid < rem ? 1 : 0);
     cw.id0 = bid;
     cw.stride = G;
+    cw.dyn = 0;
     // what is left of a workgroup's equal share for small tiles (all quantities scaled by G)
     const long r_hi = max(0L, C - ((k + 1) * c_wide + sw) * G);
     const long r_lo = max(0L, C - (k * c_wide + (k > 0 ? sw : 0)) * G);
     const long p_tot = (long)rem * r_hi + (long)(G - rem) * r_lo;
-    // first small tile of workgroup b: the tile at cost position S * p(b) / p_tot of the line
+    // A long small line is cut this way only over its first DYN_STATIC_PCT percent; the rest is
+    // drawn from a counter in units of at least three slots (a workgroup learns its next unit one
+    // unit ahead), two units' worth at a time until the last two per workgroup.  The workgroups'
+    // speeds differ by a few percent from launch to launch and between XCDs, which no fixed
+    // split can know; the ranges below then only set where each workgroup starts.
+    const int ut = (int)max(1L, (3 + nkb_s - 1) / nkb_s);
+    int n_stat = n_small;
+    cs.dyn = 0;
+    cs.n_units = cs.n_double = cs.pool0 = 0;
+    cs.ut = ut;
+    cs.n_tiles = n_small;
+    cs.ctr = const_cast<int32_t *>(plan) + PLAN_CTR + MODE;
+    if (DYN && DYN_STATIC_PCT < 100 && p_tot > 0) {
+      const int ns = (int)((long)n_small * DYN_STATIC_PCT / 100) / ut * ut;
+      const int nq = (n_small - ns) / ut;  // groups of ut tiles in the drawn part
+      if (ns >= G * ut && nq >= G && (long)n_small * nkb_s >= (long)DYN_MIN_SLOTS * G &&
+          n_small >= DYN_MIN_TILES * G) {
+        int n_single = min(nq, 2 * G);
+        if ((nq - n_single) & 1) ++n_single;
+        n_stat = ns;
+        cs.dyn = 1;
+        cs.n_double = (nq - n_single) / 2;
+        cs.n_units = cs.n_double + n_single;
+        cs.pool0 = ns;
+      }
+    }
+    const long n_shs_l = min(n_shs, (long)n_stat);
+    const long S_l = n_shs_l * c_sh + ((long)n_stat - n_shs_l) * c_r;  // the part of the line that is cut
+    // first small tile of workgroup b: the tile at cost position S_l * p(b) / p_tot of that part
     auto first_small = [&](int b) -> int {
       if (p_tot <= 0 || b <= 0) return 0;
-      if (b >= G) return n_small;
+      if (b >= G) return n_stat;
       const long pb = (long)min(b, rem) * r_hi + (long)max(0, b - rem) * r_lo;
-      const double x = (double)S * (double)pb / (double)p_tot;
-      const double head = (double)(n_shs * c_sh);
-      const double t = x <= head ? x / (double)c_sh : (double)n_shs + (x - head) / (double)c_r;
-      return min((int)t, n_small);
+      const double x = (double)S_l * (double)pb / (double)p_tot;
+      const double head = (double)(n_shs_l * c_sh);
+      const double t = x <= head ? x / (double)c_sh : (double)n_shs_l + (x - head) / (double)c_r;
+      const int ti = min((int)t, n_stat);
+      return cs.dyn ? ti / ut * ut : ti;
     };
     const int sb0 = p_tot > 0 ? first_small(bid) : 0, sb1 = p_tot > 0 ? first_small(bid + 1) : 0;
     cs.n_mine = sb1 - sb0;
@@ -741,7 +870,7 @@ __global__ __launch_bounds__(STREAM_THREADS) void expert_stream_kernel(StreamArg
 
 static hipError_t launch_stream(int mode, const StreamArgs &a, hipStream_t s) {
   static int n_cu = 0;
-  static bool attr_set[2] = {false, false};
+  static bool attr_set[4] = {false, false, false, false};
   if (n_cu == 0) {
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -751,19 +880,47 @@ static hipError_t launch_stream(int mode, const StreamArgs &a, hipStream_t s) {
     if (e != hipSuccess) return e;
     n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
   }
-  const void *fn = mode == MODE_GATE_UP ? reinterpret_cast<const void *>(expert_stream_kernel<MODE_GATE_UP>)
-                                        : reinterpret_cast<const void *>(expert_stream_kernel<MODE_DOWN>);
-  if (!attr_set[mode]) {
-    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, STREAM_LDS_BYTES);
+  // Upper bound of the small tiles (the plan is on the device): experts with rows x row tiles, plus
+  // the shared expert's when it has at most 16 rows.  Below the threshold the kernel would deal
+  // everything in fixed ranges anyway.
+  const long kr = mode == MODE_GATE_UP ? a.d : a.I;
+  const long nkb_s = (kr + KB - 1) / KB;
+  const long per_r = mode == MODE_GATE_UP ? (a.I + 15) / 16 : (a.d + 31) / 32;
+  const long per_s = mode == MODE_GATE_UP ? (a.S + 15) / 16 : (a.d + 31) / 32;
+  const long parts = (mode == MODE_DOWN && a.S > 0) ? (a.S + a.part_k - 1) / a.part_k : 1;
+  const long e_max = (long)a.T * a.K < a.E ? (long)a.T * a.K : a.E;
+  const long small_max = e_max * per_r + ((a.S > 0 && a.T <= SMALL_M) ? per_s * parts : 0);
+  const bool dyn = DYN_STATIC_PCT < 100 && small_max * nkb_s >= (long)DYN_MIN_SLOTS * n_cu &&
+                   small_max >= (long)DYN_MIN_TILES * n_cu;
+  const int which = mode * 2 + (dyn ? 1 : 0);
+  const void *fns[4] = {reinterpret_cast<const void *>(expert_stream_kernel<MODE_GATE_UP, false>),
+                        reinterpret_cast<const void *>(expert_stream_kernel<MODE_GATE_UP, true>),
+                        reinterpret_cast<const void *>(expert_stream_kernel<MODE_DOWN, false>),
+                        reinterpret_cast<const void *>(expert_stream_kernel<MODE_DOWN, true>)};
+  if (!attr_set[which]) {
+    hipError_t e = hipFuncSetAttribute(fns[which], hipFuncAttributeMaxDynamicSharedMemorySize, STREAM_LDS_BYTES);
     if (e != hipSuccess) return e;
-    attr_set[mode] = true;
+    attr_set[which] = true;
   }
-  if (mode == MODE_GATE_UP)
-    hipLaunchKernelGGL(expert_stream_kernel<MODE_GATE_UP>, dim3(n_cu), dim3(STREAM_THREADS), STREAM_LDS_BYTES, s, a,
-                       a.plan, a.offsets, a.row_token);
-  else
-    hipLaunchKernelGGL(expert_stream_kernel<MODE_DOWN>, dim3(n_cu), dim3(STREAM_THREADS), STREAM_LDS_BYTES, s, a,
-                       a.plan, a.offsets, a.row_token);
+  const dim3 grid(n_cu), block(STREAM_THREADS);
+  switch (which) {
+    case 0:
+      hipLaunchKernelGGL((expert_stream_kernel<MODE_GATE_UP, false>), grid, block, STREAM_LDS_BYTES, s, a, a.plan,
+                         a.offsets, a.row_token);
+      break;
+    case 1:
+      hipLaunchKernelGGL((expert_stream_kernel<MODE_GATE_UP, true>), grid, block, STREAM_LDS_BYTES, s, a, a.plan,
+                         a.offsets, a.row_token);
+      break;
+    case 2:
+      hipLaunchKernelGGL((expert_stream_kernel<MODE_DOWN, false>), grid, block, STREAM_LDS_BYTES, s, a, a.plan,
+                         a.offsets, a.row_token);
+      break;
+    default:
+      hipLaunchKernelGGL((expert_stream_kernel<MODE_DOWN, true>), grid, block, STREAM_LDS_BYTES, s, a, a.plan,
+                         a.offsets, a.row_token);
+      break;
+  }
   return hipGetLastError();
 }
 

@@ -148,6 +148,8 @@ __device__ __forceinline__ void permute_body(
       plan[0] = ns;
       plan[1] = nb;
       plan[2] = nl;
+      plan[PLAN_CTR] = 0;
+      plan[PLAN_CTR + 1] = 0;
     }
   }
   __syncthreads();
