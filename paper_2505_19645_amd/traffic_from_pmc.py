@@ -47,7 +47,7 @@ def main():
     w_copy = max(pick(write, "copyBuffer"))
     f_unit, w_unit = 2.0 ** 30 / f_copy, 2.0 ** 30 / w_copy
     out = {"fetch_unit_bytes": f_unit, "write_unit_bytes": w_unit}
-    for name, needle in (("gate_up", "expert_stream_kernel<0>"), ("down", "expert_stream_kernel<1>")):
+    for name, needle in (("gate_up", "expert_stream_kernel<0,"), ("down", "expert_stream_kernel<1,")):
         fv, wv = pick(fetch, needle), pick(write, needle)
         out[name] = {"fetch_bytes": sum(fv) / len(fv) * f_unit, "write_bytes": sum(wv) / len(wv) * w_unit,
                      "launches": len(fv)}
