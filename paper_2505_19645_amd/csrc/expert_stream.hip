@@ -5,7 +5,13 @@
 // Sec. 3.2 shows that sparser models stay in this regime for longer).  These
 // kernels are therefore built around the weight stream, not around the MFMA:
 //
-//  * One persistent workgroup (4 waves) per compute unit.
+//  * One persistent workgroup of 8 waves per compute unit, one pair per SIMD: waves 4..7
+//    only load (they issue every DMA instruction and wait for their own loads), waves 0..3
+//    only multiply (LDS reads, MFMAs, epilogues).  Issuing a DMA instruction blocks while
+//    the memory system's queues are full, which is most of the time here; in a wave that
+//    also multiplies, the MFMAs would start only after that.  The two sides meet at one
+//    s_barrier per slot: the loading waves arrive when slot k has landed, the multiplying
+//    waves when they are done with slot k-1, whose ring position is then refilled.
 //  * Two tile shapes, so that the token rows never cost more than half the
 //    weight bytes that travel with them:
 //      small: an expert (or token block) with 1..16 rows.  32 weight rows (16 of
@@ -17,7 +23,7 @@
 //             rows, 64 rows of the first operand half, 64 of the second.
 //    Experts with 65..128 rows run as two wide blocks (their weights stream twice);
 //    beyond that they belong to the MFMA-tiled kernel.
-//  * Every slot is exactly twelve (wide: eight) global_load_lds_dwordx4 per wave, each
+//  * Every slot is exactly twelve (wide: eight) global_load_lds_dwordx4 per loading wave, each
 //    moving 1 KB (one 1 KB row piece, wide: two 512-byte pieces, contiguous in HBM:
 //    256-byte pieces stream at three quarters of the rate, and the longer the blocks
 //    the fewer steps a byte costs) straight into LDS; the weights carry the
@@ -26,12 +32,15 @@
 //    (wide: three in a ring of four), across tile borders; the compiler sees no
 //    vector memory load in the loop and cannot serialise the prefetch.
 //  * Work split: wide tiles are dealt round-robin, then every workgroup gets a
-//    contiguous run of small tiles sized so that all finish together.
+//    contiguous run of small tiles sized so that all finish together.  When the line
+//    of small tiles is long, that covers its first 60 % only and the rest is drawn from
+//    a counter in units of a few tiles, which evens out the differences in speed
+//    between workgroups that no fixed split can know.
 //  * MFMA operands come from LDS.  The 16-byte pieces of a row are stored
 //    XOR-swizzled by (row & 15): the 16 rows that one quarter-wave reads then
 //    fall into 16 different 16-byte bank groups of the 64-bank LDS, while the DMA
 //    writes stay linear.
-//  * Small tiles: the four waves split the sixteen 32-element MFMA steps of a
+//  * Small tiles: the four multiplying waves split the sixteen 32-element MFMA steps of a
 //    block and add their partial 16x16 tiles through LDS in a fixed order.
 //    Wide tiles: the waves form 2 x 2: a wave multiplies 32 token rows, whose
 //    fragments of the whole block it keeps in registers (the token slot is free as
