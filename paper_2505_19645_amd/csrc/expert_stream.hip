@@ -89,7 +89,7 @@
 #define DYN_STATIC_PCT 60  // share of a long small line that is dealt in fixed ranges (100: all of it)
 #endif
 #ifndef DYN_MIN_SLOTS
-#define DYN_MIN_SLOTS 72   // slots of small tiles per workgroup from which units are drawn at all
+#define DYN_MIN_SLOTS 40   // slots of small tiles per workgroup from which units are drawn at all
 #endif
 #ifndef DYN_MIN_TILES
 #define DYN_MIN_TILES 12   // and small tiles per workgroup (a few long tiles are better dealt evenly)

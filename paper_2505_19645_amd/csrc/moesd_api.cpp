@@ -4,6 +4,11 @@
 
 #include "common.h"
 
+// up to this many tokens one workgroup picks every top-K and sorts (one launch instead of two)
+#ifndef MOESD_FUSED_TOPK_MAX_T
+#define MOESD_FUSED_TOPK_MAX_T 32
+#endif
+
 namespace {
 
 std::atomic<int32_t> g_last_hip_error{0};
@@ -210,7 +215,7 @@ int32_t moesd_moe_forward_staged(const moesd_layer_desc *desc, const moesd_weigh
   MOESD_TRY(launch_router_logits((const uint16_t *)x, (const uint16_t *)wt->w_router,
                                  wt->router_bias, gated ? (const uint16_t *)wt->w_shared_gate : nullptr,
                                  T, desc->d, desc->E, ws.logits, s))
-  if (T <= 32 && desc->E <= 256) {
+  if (T <= MOESD_FUSED_TOPK_MAX_T && desc->E <= 256) {
     MOESD_TRY(launch_topk_permute(ws.logits, T, desc->E, desc->top_k, desc->score_func,
                                   desc->renormalize, desc->routed_scale, groups_of(desc), gated ? 1 : 0, ids, w,
                                   ws.gate, cnt, off, pm, iv, na, ws.row_token, ws.plan, s))
