@@ -245,6 +245,25 @@ def test_qwen2_shape_full_size_sampled_tokens(gpu, oracle):
         assert np.array_equal(again["perm"], got["perm"]) and again["n_active"] == got["n_active"]
 
 
+@pytest.mark.parametrize("shape,T", [
+    # d = 512: one 512-element block per gate/up tile, so a unit is three tiles and every step carries the extra
+    # barrier of a one-slot tile; about 220 active experts x 52 row tiles = 11500 small tiles (45 per workgroup)
+    (LayerShape("drawn-1slot", d=512, E=256, top_k=8, inter=832, shared_inter=0, seed=31), 64),
+    # I = 1000: two blocks per down tile, the second ragged, units of two tiles (about 146 experts x 38 row tiles, 43 slots
+    # per workgroup); gate/up: three blocks, the last ragged; shared expert with a gate in the wide class
+    (LayerShape("drawn-2slot", d=1200, E=160, top_k=8, inter=1000, shared_inter=520, shared_gate=1, seed=32), 48),
+])
+def test_drawn_units_with_short_tiles(gpu, oracle, shape, T):
+    # Lines of small tiles long enough for the streaming kernels to hand out their tail from a counter (at least
+    # 12 tiles and 40 slots per workgroup on 256 CUs), with tiles of one and of two slots: the unit sizes, the
+    # mailbox between the multiplying and the loading waves and the one-slot tiles' extra barrier all take part.
+    w = synth.make_layer(shape, threads=16)
+    tokens = [0, T // 3, T - 1]
+    got, _ = run_case(gpu, oracle, shape, T, tokens=tokens, point=77, weights=w)
+    again = gpu.GpuLayer(shape, w).forward(synth.make_tokens(shape, T, point=77))
+    assert np.array_equal(again["out_f32"], got["out_f32"])
+
+
 def test_mixtral_shape_full_size_tiled_sampled_tokens(gpu, oracle):
     # benchmark config 3 at full size and its largest T (4096: about 1024 rows per expert, the MFMA-tiled
     # kernels with the persistent schedule the benchmark's compute-bound point times); routing bit-exact on
