@@ -13,7 +13,6 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 VALU forms
          "-Wall", "-Wno-unused-function"]
-EXTRA = {}  # per-file flags
 
 
 def build(force: bool = True, verbose: bool = False) -> str:
@@ -30,7 +29,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
     for s in srcs:
         o = os.path.join(bdir, os.path.basename(s) + ".o")
         objs.append(o)
-        cmd = [HIPCC] + FLAGS + EXTRA.get(os.path.basename(s), []) + ["-c", s, "-o", o]
+        cmd = [HIPCC] + FLAGS + ["-c", s, "-o", o]
         if verbose:
             print(" ".join(cmd))
         procs.append((s, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
