@@ -33,6 +33,14 @@ __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v)
   return best;
 }
 
+// value of lane `src` (wave-uniform) in every lane
+__device__ __forceinline__ double readlane_f64(double v, int src) {
+  const unsigned long long u = (unsigned long long)__double_as_longlong(v);
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)u, src);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(u >> 32), src);
+  return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+}
+
 __device__ __forceinline__ double wave_sum_f64(double v) {
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
@@ -54,12 +62,15 @@ __device__ __forceinline__ void topk_token(const double *__restrict__ logits, in
   const double *lrow = logits + (size_t)t * Etot;
 
   unsigned long long key[SLOTS];
+  double lval[SLOTS];  // the fp64 logits of this lane's experts
 #pragma unroll
   for (int j = 0; j < SLOTS; ++j) {
     const int e = lane + 64 * j;
     key[j] = 0ull;  // below every real key (real keys have a non-zero low word)
+    lval[j] = 0.0;
     if (e < E) {
-      const float kf = (float)lrow[e] + 0.0f;  // the one rounding; +0 folds -0 into +0
+      lval[j] = lrow[e];
+      const float kf = (float)lval[j] + 0.0f;  // the one rounding; +0 folds -0 into +0
       uint32_t u = __float_as_uint(kf);
       u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
       key[j] = ((unsigned long long)u << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)e);
@@ -142,11 +153,17 @@ __device__ __forceinline__ void topk_token(const double *__restrict__ logits, in
     for (int j = 0; j < SLOTS; ++j) best = key[j] > best ? key[j] : best;
     best = wave_max_u64(best);
     const int e = (int)(0xFFFFFFFFu - (uint32_t)(best & 0xFFFFFFFFull));
-    // owner removes it; everyone re-reads its fp64 logit (a broadcast load)
+    // owner removes it; everyone takes its fp64 logit from the owner's register (a read of memory
+    // here would put one load latency into each of the K rounds)
 #pragma unroll
     for (int j = 0; j < SLOTS; ++j)
       if (lane + 64 * j == e) key[j] = 0ull;
-    const double lv = lrow[e];
+    const int owner = __builtin_amdgcn_readfirstlane(e & 63), oslot = e >> 6;
+    double cand = lval[0];
+#pragma unroll
+    for (int j = 1; j < SLOTS; ++j)
+      if (j == oslot) cand = lval[j];
+    const double lv = readlane_f64(cand, owner);
     if (s == 0) first_logit = lv;
     if (lane == s) { my_id = e; my_logit = lv; }
   }
