@@ -228,6 +228,10 @@ def test_qwen15_shape_full_size_sampled_tokens(gpu, oracle):
     run_case(gpu, oracle, shape, 64, tokens=[0, 13, 31, 63], point=163, weights=w)
     # T = 256 (B=64, gamma=3): routed experts in 64-row wide tiles, the shared expert streamed in four token blocks
     run_case(gpu, oracle, shape, 256, tokens=[0, 77, 130, 255], point=164, weights=w)
+    # T = 320: the shared expert still streamed (five token blocks); T = 640 (B=160, gamma=3, the largest of this
+    # shape's sweep): routed experts in wide tiles, some beyond 64 rows, the shared expert in the MFMA-tiled kernels
+    run_case(gpu, oracle, shape, 320, tokens=[0, 150, 319], point=165, weights=w)
+    run_case(gpu, oracle, shape, 640, tokens=[0, 333, 639], point=166, weights=w)
 
 
 def test_qwen2_shape_full_size_sampled_tokens(gpu, oracle):
@@ -243,6 +247,8 @@ def test_qwen2_shape_full_size_sampled_tokens(gpu, oracle):
         again = layer.forward(x)
         assert np.array_equal(again["out_f32"], got["out_f32"]) and np.array_equal(again["out_bf16"], got["out_bf16"])
         assert np.array_equal(again["perm"], got["perm"]) and again["n_active"] == got["n_active"]
+    # the largest T of this shape's sweep (B=256, gamma=4): about 160 rows per expert, every kernel class at once
+    run_case(gpu, oracle, shape, 1280, tokens=[0, 641, 1279], point=264, weights=w)
 
 
 @pytest.mark.parametrize("shape,T", [
