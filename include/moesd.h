@@ -15,11 +15,29 @@
  *     passed as void*, NULL = the default stream) and the call returns at once.
  *   - bf16 tensors are arrays of 16-bit words (upper half of an IEEE fp32).
  *   - Matrices are row-major, [out, in]: the contraction index is contiguous.
- *   - Arguments are validated on the host before anything is launched.  On any
- *     non-zero status nothing has been enqueued and no output was touched.
+ *   - Arguments are validated on the host before anything is launched.  On
+ *     MOESD_INVALID_ARG, MOESD_UNSUPPORTED and MOESD_WORKSPACE_TOO_SMALL nothing
+ *     has been enqueued and no output was touched.  MOESD_HIP_ERROR reports a
+ *     failure of the HIP runtime itself (a launch or an event record refused);
+ *     kernels enqueued before it stay enqueued and the outputs are undefined.
  *   - T == 0 is a successful no-op.
- *   - Calls that use the same workspace or outputs on different streams race;
- *     otherwise the library holds no mutable state besides the last HIP error.
+ *   - Calls that use the same workspace or outputs on different streams race.
+ *     Besides that the library keeps, per process: the last HIP error code, and
+ *     per device ordinal the compute-unit count and which kernels already had
+ *     their dynamic-LDS limit raised (atomics; every writer stores the same
+ *     value, so concurrent first calls are safe).  Work is launched on the
+ *     device the calling thread has current.
+ *
+ * The interface is the four calls of the problem statement (route, permute,
+ * forward, expected activated experts) with these additions, each for a stated
+ * reason: moesd_route takes a workspace (the fp64 logits live there);
+ * moesd_moe_forward also returns inv_perm and, on request, the output before its
+ * final rounding (out_f32), both for checking; the descriptor carries n_group /
+ * topk_group (group-limited selection) and weight_format (low-precision expert
+ * weights); moesd_moe_forward_staged records events at the stage boundaries for
+ * timing; moesd_moe_forward_static is the variant for callers that cannot
+ * allocate; moesd_expected_active_experts_p, moesd_expected_tokens_per_expert
+ * and moesd_token_threshold are further closed forms of Sec. 3.2.
  */
 #ifndef MOESD_H
 #define MOESD_H
@@ -35,7 +53,8 @@ extern "C" {
 #define MOESD_OK                  0
 #define MOESD_INVALID_ARG         1  /* null pointer, K<1, K>E, E<1, T<0, T*K >= 2^31,
                                         d / inter / shared_inter not a multiple of 8   */
-#define MOESD_UNSUPPORTED         2  /* E > MOESD_MAX_E, K > MOESD_MAX_K, unknown enum */
+#define MOESD_UNSUPPORTED         2  /* E > MOESD_MAX_E, K > MOESD_MAX_K, unknown enum,
+                                        T*d*2 >= 2^32 (a token row's byte offset is 32-bit) */
 #define MOESD_WORKSPACE_TOO_SMALL 3
 #define MOESD_HIP_ERROR           4  /* see moesd_last_hip_error()                     */
 
@@ -108,10 +127,10 @@ int64_t moesd_token_threshold(int32_t E, int32_t K, double tau);
  * T_max tokens (256-byte aligned pieces; the caller's buffer must itself be
  * 256-byte aligned).  Besides the per-token buffers (logits, routing outputs,
  * the bf16 activation [T*K, I] and the fp32 expert outputs [T*K, d]) it holds,
- * for T_max > 128, 512 KB per compute unit of partial-sum space for the
- * MFMA-tiled expert kernels (128 MB on a 256-CU device).  The size depends on
- * the device the calling thread has current.  Returns 0 if the descriptor is
- * invalid. */
+ * for T_max > 128, 128 MB of partial-sum space for the MFMA-tiled expert kernels
+ * (512 KB for each of at most 256 persistent workgroups).  The size depends on
+ * the arguments only, not on the device.  Returns 0 if the descriptor or T_max
+ * is invalid. */
 size_t moesd_workspace_bytes(const moesd_layer_desc *desc, int32_t T_max);
 
 /* ---------------------------------------------------------------------------

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "../../include/moesd.h"
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -79,6 +81,18 @@ struct StreamArgs {
   int32_t shared_stream;                      // 1: the streaming kernels take the shared expert, 0: the tiled ones
 };
 
+// ---- per-device facts (moesd_api.cpp) --------------------------------------------
+// The device the calling thread has current and its compute-unit count.  The counts are cached
+// per device ordinal in atomics: every thread that fills a cache entry writes the same value.
+#define MOESD_MAX_DEVICES 64
+hipError_t current_device(int *dev, int *n_cu);
+// Kernels that need more dynamic LDS than the default limit raise it once per (kernel, device):
+// one bit per device ordinal; a repeated call is harmless, so a race between two first calls is too.
+struct LdsLimitOnce {
+  std::atomic<unsigned long long> done{0ull};
+};
+hipError_t raise_dynamic_lds_limit(LdsLimitOnce &once, int dev, const void *kernel, int bytes);
+
 // host-side launch entry points, one per source file
 hipError_t launch_router_logits(const uint16_t *x, const uint16_t *w_router, const float *bias,
                                 const uint16_t *w_shared_gate, int T, int d, int E, double *logits,
@@ -101,12 +115,13 @@ hipError_t launch_topk_permute(const double *logits, int T, int E, int K, int sc
 hipError_t launch_gate_up(const StreamArgs &a, hipStream_t s);
 hipError_t launch_down(const StreamArgs &a, hipStream_t s);
 // The tiled kernels are persistent and cut the work into equal shares; a tile cut by a
-// share boundary is completed through `partials` (tiled_partials_bytes() bytes).
+// share boundary is completed through `partials` (tiled_partials_bytes() bytes, the same on
+// every device).
 size_t tiled_partials_bytes();
 // Which kernels should take the shared expert of S x d at T > 128 tokens (K of E experts per token): 1 = the streaming
 // kernels (its weights pass once per 64 tokens), 0 = the MFMA-tiled kernels (a few 256-row tiles
 // can leave most of the chip idle for as long as one tile takes).
-int shared_expert_streams(int T, int d, int S, int part_k, int K, int E);
+int shared_expert_streams(int T, int d, int S, int part_k, int K, int E, int n_cu);
 hipError_t launch_gate_up_tiled(const StreamArgs &a, float *partials, hipStream_t s);
 hipError_t launch_down_tiled(const StreamArgs &a, float *partials, hipStream_t s);
 hipError_t launch_combine(const float *y, const float *ys, int n_parts, const float *w,

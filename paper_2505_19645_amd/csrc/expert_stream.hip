@@ -97,39 +97,24 @@
 
 enum { MODE_GATE_UP = 0, MODE_DOWN = 1 };
 
-// Diagnostic build only (-DMOESD_STREAM_STAMPS, made and read by paper_2505_19645_amd/stream_phases.py): every
-// workgroup records when it started and ended and how many cycles its two roles spent in each part
-// of a step, summed over both tile classes.  The library proper is compiled without it.
-#ifdef MOESD_STREAM_STAMPS
-struct StreamStamps {
-  long long t_start, t_end;                              // wall clock (100 MHz)
-  long long load_wait, load_barrier, load_issue, load_steps;  // shader cycles, loading waves (wave 4)
-  long long mult_barrier, mult_work, mult_steps;         // multiplying waves (wave 0)
-  long long tiles;
-};
-__device__ StreamStamps g_stream_stamps[2][1024];
-extern "C" int moesd_stream_stamps(void *host, size_t bytes) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_stream_stamps),
-                                  bytes < sizeof(g_stream_stamps) ? bytes : sizeof(g_stream_stamps));
-}
-#define STAMP(...) __VA_ARGS__
-#else
-#define STAMP(...)
-#endif
-
 // ---- hand-issued memory operations --------------------------------------------
 // lds_base is wave-uniform by construction; readfirstlane makes that explicit so the
-// operand always lands in a scalar register
+// operand always lands in a scalar register.  The instruction takes its LDS address from m0,
+// which the asm sets itself and names as clobbered (the compiler reserves m0 and warns about
+// seeing it in a clobber list; the clobber is what keeps any value of its own out of m0 here).
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void dma16(const void *g, uint32_t lds_base) {
   const uint32_t b = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_base);
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-               :: "v"(g), "s"(b) : "memory");
+               :: "v"(g), "s"(b) : "memory", "m0");
 }
 __device__ __forceinline__ void dma16_stream(const void *g, uint32_t lds_base) {
   const uint32_t b = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_base);
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off nt"
-               :: "v"(g), "s"(b) : "memory");
+               :: "v"(g), "s"(b) : "memory", "m0");
 }
+#pragma clang diagnostic pop
 template <int N>
 __device__ __forceinline__ void wait_vm() {
   asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
@@ -574,28 +559,16 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
 
     for (int i = 0; i < AH && l_live; ++i) advance_load();
     int k = 0;  // the slot whose step this is
-    STAMP(long long st_wait = 0, st_bar = 0, st_issue = 0;)
     while (k < l_slot) {
-      STAMP(const long long c0 = clock64();)
       // slot k must have landed: at most AH-1 younger slots may be pending
       if (l_slot - k == AH) wait_vm<(AH - 1) * LWN>();
       else wait_vm<0>();
-      STAMP(const long long c1 = clock64();)
       wg_barrier();  // slot k is in LDS for the multiplying waves; they are done with slot k-1
-      STAMP(const long long c2 = clock64();)
       if (l_live) advance_load();
-      STAMP(st_wait += c1 - c0; st_bar += c2 - c1; st_issue += clock64() - c2;)
       if (!WIDE && ((single >> (k & 63)) & 1ull)) wg_barrier();
       ++k;
     }
     if (!WIDE) wg_barrier();  // the last tile's reduction
-    STAMP(if (lw == 0 && lane == 0) {
-      StreamStamps &g = g_stream_stamps[MODE][blockIdx.x & 1023];
-      g.load_wait += st_wait;
-      g.load_barrier += st_bar;
-      g.load_issue += st_issue;
-      g.load_steps += k;
-    })
   } else {
     // ---- multiplying waves: the compute cursor -------------------------------------------
     int c_i = 0, c_kb = 0, c_slot = 0;
@@ -638,11 +611,8 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
       for (int i = 0; i < 4; ++i) accw[w][i >> 1][i & 1] = (f32x4){0.f, 0.f, 0.f, 0.f};
     const int wr = wave & 1, wt = wave >> 1;
 
-    STAMP(long long st_mbar = 0, st_work = 0, st_prev = 0, st_tiles = 0;)
     while (true) {
-      STAMP(const long long m0 = clock64(); if (st_prev) st_work += m0 - st_prev;)
       wg_barrier();  // slot c_slot has landed (the loading waves waited for it)
-      STAMP(st_prev = clock64(); st_mbar += st_prev - m0;)
       if (!WIDE && pend) flush_pending();
       if (dyn && c_first) {
         // First step of a unit: wave 0 draws the unit after this one and waits for the answer
@@ -746,7 +716,6 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
       ++c_slot;
 
       if (tile_done) {
-        STAMP(++st_tiles;)
         const int id = c_id;
         const int i0 = tile_i0<MODE, WIDE>(id - cen.first);
         if (WIDE) {
@@ -803,13 +772,6 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
       wg_barrier();
       flush_pending();
     }
-    STAMP(if (tid == 0) {
-      StreamStamps &g = g_stream_stamps[MODE][blockIdx.x & 1023];
-      g.mult_barrier += st_mbar;
-      g.mult_work += st_work;
-      g.mult_steps += c_slot;
-      g.tiles += st_tiles;
-    })
   }
   // nothing pending, every wave done reading the ring: the next class may reuse it
   wait_vm<0>();
@@ -826,12 +788,6 @@ __global__ __launch_bounds__(STREAM_THREADS) void expert_stream_kernel(StreamArg
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const Tables tb_{plan, offsets, row_token};
   const int G = gridDim.x, bid = blockIdx.x;
-  STAMP(if (threadIdx.x == 0) {
-    StreamStamps z = {};
-    z.t_start = wall_clock64();
-    g_stream_stamps[MODE][bid & 1023] = z;
-  }
-  __syncthreads();)
 
   // ---- the schedule ---------------------------------------------------------------
   // wide tiles: [shared expert's, if it has more than 16 rows][big routed entries]
@@ -924,21 +880,13 @@ __global__ __launch_bounds__(STREAM_THREADS) void expert_stream_kernel(StreamArg
   }
   run_class<MODE, true>(a, tb_, cw, smem);
   run_class<MODE, false>(a, tb_, cs, smem);
-  STAMP(if (threadIdx.x == 0) g_stream_stamps[MODE][bid & 1023].t_end = wall_clock64();)
 }
 
 static hipError_t launch_stream(int mode, const StreamArgs &a, hipStream_t s) {
-  static int n_cu = 0;
-  static bool attr_set[4] = {false, false, false, false};
-  if (n_cu == 0) {
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return e;
-    hipDeviceProp_t prop;
-    e = hipGetDeviceProperties(&prop, dev);
-    if (e != hipSuccess) return e;
-    n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-  }
+  static LdsLimitOnce lds_once[4];
+  int dev = 0, n_cu = 0;
+  hipError_t e0 = current_device(&dev, &n_cu);
+  if (e0 != hipSuccess) return e0;
   // Upper bound of the small tiles (the plan is on the device): experts with rows x row tiles, plus
   // the shared expert's when it has at most 16 rows.  Below the threshold the kernel would deal
   // everything in fixed ranges anyway.
@@ -956,11 +904,8 @@ static hipError_t launch_stream(int mode, const StreamArgs &a, hipStream_t s) {
                         reinterpret_cast<const void *>(expert_stream_kernel<MODE_GATE_UP, true>),
                         reinterpret_cast<const void *>(expert_stream_kernel<MODE_DOWN, false>),
                         reinterpret_cast<const void *>(expert_stream_kernel<MODE_DOWN, true>)};
-  if (!attr_set[which]) {
-    hipError_t e = hipFuncSetAttribute(fns[which], hipFuncAttributeMaxDynamicSharedMemorySize, STREAM_LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_set[which] = true;
-  }
+  e0 = raise_dynamic_lds_limit(lds_once[which], dev, fns[which], STREAM_LDS_BYTES);
+  if (e0 != hipSuccess) return e0;
   const dim3 grid(n_cu), block(STREAM_THREADS);
   switch (which) {
     case 0:

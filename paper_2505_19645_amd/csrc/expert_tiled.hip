@@ -614,28 +614,23 @@ __global__ __launch_bounds__(T_THREADS) void expert_tiled_fixup_kernel(StreamArg
   tiled_piece<MODE, true>(a, sc, nullptr, shared_region, tile, 0, nkb_reg, nkb_reg, run_base, 0, member, w);
 }
 
-// Workspace the tiled kernels need beyond the layer's own buffers.
-static int tiled_grid() {
-  static int grid = 0;
-  if (grid == 0) {
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 32)
-      cus = 32;
-    grid = (cus / 32) * 32;  // whole teams of 4 on each of the 8 XCDs
-  }
-  return grid;
+// The persistent grid: whole teams of 4 on each of the 8 XCDs, at most TILED_MAX_WGS workgroups
+// (the partial-sum space in the workspace is sized for that many, whatever the device).
+#define TILED_MAX_WGS 256
+static int tiled_grid_for(int n_cu) {
+  const int g = (n_cu / 32) * 32;
+  return g < 32 ? 32 : (g > TILED_MAX_WGS ? TILED_MAX_WGS : g);
 }
 // Estimated microseconds either way, from measurements on the MI355X: the streaming kernels move
 // the shared expert's 3*S*d*2 bytes once per 64 tokens at about 4.8 TB/s when they share the chip
 // with the routed experts' wide tiles; a tiled kernel needs ceil(tiles / CUs) rounds of a tile's
 // stages, 1.5 us (gate/up) and 1.8 us (down) each, plus a fix-up launch.
-int shared_expert_streams(int T, int d, int S, int part_k, int K, int E) {
+int shared_expert_streams(int T, int d, int S, int part_k, int K, int E, int n_cus) {
   if (S <= 0 || T <= PLAN_BIG_MAX_ROWS) return 1;
   // routed experts with more than 64 rows on average keep the tiled kernels busy anyway: the shared
   // expert's tiles then fill gaps there instead of leaving the chip idle
   if ((long)T * K > 64L * E) return 0;
-  const double n_cu = (double)tiled_grid();
+  const double n_cu = (double)tiled_grid_for(n_cus);
   const double stream_us = (double)((T + 63) / 64) * (3.0 * S * (double)d * 2.0) / 4.8e6;
   const double tb = (double)((T + TBM - 1) / TBM);
   const int parts = (S + part_k - 1) / part_k;
@@ -645,18 +640,17 @@ int shared_expert_streams(int T, int d, int S, int part_k, int K, int E) {
   return stream_us < tiled_us ? 1 : 0;
 }
 
-size_t tiled_partials_bytes() { return (size_t)2 * tiled_grid() * T_SLOT_FLOATS * sizeof(float); }
+size_t tiled_partials_bytes() { return (size_t)2 * TILED_MAX_WGS * T_SLOT_FLOATS * sizeof(float); }
 static hipError_t launch_tiled(int mode, const StreamArgs &a, float *partials, hipStream_t s) {
-  static bool attr_set[2] = {false, false};
+  static LdsLimitOnce lds_once[2];
   const void *fn = mode == TMODE_GATE_UP ? reinterpret_cast<const void *>(expert_tiled_kernel<TMODE_GATE_UP>)
                                          : reinterpret_cast<const void *>(expert_tiled_kernel<TMODE_DOWN>);
-  if (!attr_set[mode]) {
-    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, TILED_LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_set[mode] = true;
-  }
-  // row offsets are kept as 32-bit byte counts inside the kernel
-  if ((unsigned long long)a.T * (unsigned long long)a.d * 2ull >= (1ull << 32)) return hipErrorInvalidValue;
+  int dev = 0, n_cu = 0;
+  hipError_t e = current_device(&dev, &n_cu);
+  if (e != hipSuccess) return e;
+  e = raise_dynamic_lds_limit(lds_once[mode], dev, fn, TILED_LDS_BYTES);
+  if (e != hipSuccess) return e;
+  // (row offsets are kept as 32-bit byte counts inside the kernel: T * d * 2 < 2^32, checked by the caller)
   if (a.T <= PLAN_BIG_MAX_ROWS) return hipSuccess;
   const int parts = (mode == TMODE_DOWN && a.S > 0) ? (a.S + a.part_k - 1) / a.part_k : 1;
   TiledSched sc;
@@ -671,7 +665,7 @@ static hipError_t launch_tiled(int mode, const StreamArgs &a, float *partials, h
     sc.nkb_r = (a.I + TBK - 1) / TBK;
   }
   sc.partials = partials;
-  const unsigned grid = (unsigned)tiled_grid();
+  const unsigned grid = (unsigned)tiled_grid_for(n_cu);
   sc.n_teams = (int)grid / 4;
   if (mode == TMODE_GATE_UP) {
     hipLaunchKernelGGL(expert_tiled_kernel<TMODE_GATE_UP>, dim3(grid), dim3(T_THREADS), TILED_LDS_BYTES, s, a, sc);

@@ -41,6 +41,8 @@ int32_t check_desc(const moesd_layer_desc *c) {
 int32_t check_T(const moesd_layer_desc *c, int32_t T) {
   if (T < 0) return MOESD_INVALID_ARG;
   if ((int64_t)T * c->top_k >= ((int64_t)1 << 31)) return MOESD_INVALID_ARG;
+  // the MFMA-tiled kernels keep a token row's byte offset in 32 bits
+  if ((int64_t)T * c->d * 2 >= ((int64_t)1 << 32)) return MOESD_UNSUPPORTED;
   return MOESD_OK;
 }
 
@@ -107,6 +109,31 @@ Workspace carve(const moesd_layer_desc *c, int64_t T, char *base) {
 }
 
 }  // namespace
+
+hipError_t current_device(int *dev, int *n_cu) {
+  static std::atomic<int> cus[MOESD_MAX_DEVICES];  // zero-initialised: not yet known
+  hipError_t e = hipGetDevice(dev);
+  if (e != hipSuccess) return e;
+  const bool cached = *dev >= 0 && *dev < MOESD_MAX_DEVICES;
+  int n = cached ? cus[*dev].load(std::memory_order_relaxed) : 0;
+  if (n == 0) {
+    e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, *dev);
+    if (e != hipSuccess) return e;
+    if (n < 1) return hipErrorInvalidDevice;
+    if (cached) cus[*dev].store(n, std::memory_order_relaxed);
+  }
+  *n_cu = n;
+  return hipSuccess;
+}
+
+hipError_t raise_dynamic_lds_limit(LdsLimitOnce &once, int dev, const void *kernel, int bytes) {
+  const bool tracked = dev >= 0 && dev < 64;
+  if (tracked && ((once.done.load(std::memory_order_acquire) >> dev) & 1ull)) return hipSuccess;
+  hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e != hipSuccess) return e;
+  if (tracked) once.done.fetch_or(1ull << dev, std::memory_order_release);
+  return hipSuccess;
+}
 
 extern "C" {
 
@@ -192,6 +219,8 @@ int32_t moesd_moe_forward_staged(const moesd_layer_desc *desc, const moesd_weigh
   if (((uintptr_t)workspace & 255) != 0) return MOESD_INVALID_ARG;
   Workspace ws = carve(desc, T, (char *)workspace);
   if (workspace_bytes < ws.bytes) return MOESD_WORKSPACE_TOO_SMALL;
+  int dev = 0, n_cu = 0;  // (every argument has been checked; from here on only the runtime can fail)
+  if ((e = current_device(&dev, &n_cu)) != hipSuccess) return hip_fail(e);
 
   int32_t *ids = topk_ids ? topk_ids : ws.ids;
   float *w = topk_w ? topk_w : ws.w;
@@ -253,7 +282,7 @@ int32_t moesd_moe_forward_staged(const moesd_layer_desc *desc, const moesd_weigh
   a.I = desc->inter;
   a.S = desc->shared_inter;
   a.T = T;
-  a.shared_stream = shared_expert_streams(T, desc->d, desc->shared_inter, ws.part_k, desc->top_k, desc->E);
+  a.shared_stream = shared_expert_streams(T, desc->d, desc->shared_inter, ws.part_k, desc->top_k, desc->E, n_cu);
   // experts with at most 128 rows stream; the others (possible only if T > 128) are tiled
   MOESD_TRY(launch_gate_up(a, s))
   if (T > PLAN_BIG_MAX_ROWS) {

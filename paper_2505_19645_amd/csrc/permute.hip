@@ -212,8 +212,11 @@ hipError_t launch_permute(const int32_t *ids, int64_t n, int E, int K, int32_t *
   while ((1 << nbits) < E) ++nbits;
   const size_t smem = sizeof(int32_t) * ((size_t)PERM_WAVES * E + PERM_THREADS);
   if (smem > 48 * 1024) {  // above the default dynamic-LDS limit (E > 704); gfx950 has 160 KB per CU
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(permute_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    static LdsLimitOnce once;
+    int dev = 0, n_cu = 0;
+    hipError_t e = current_device(&dev, &n_cu);
+    if (e != hipSuccess) return e;
+    e = raise_dynamic_lds_limit(once, dev, reinterpret_cast<const void *>(permute_kernel), (int)(sizeof(int32_t) * ((size_t)PERM_WAVES * MOESD_MAX_E + PERM_THREADS)));
     if (e != hipSuccess) return e;
   }
   hipLaunchKernelGGL(permute_kernel, dim3(1), dim3(PERM_THREADS), smem, s, ids, n, E, K, nbits,

@@ -1,5 +1,7 @@
 """Helpers for the GPU parity tests: upload numpy inputs, call the C-ABI through
 the binding, bring every output back as numpy."""
+import os
+
 import numpy as np
 import torch
 
@@ -7,6 +9,7 @@ import paper_2505_19645_amd as moesd
 from paper_2505_19645_amd.synth import bf16_bits_to_f32
 
 DEV = "cuda:0"
+torch = torch  # (re-exported for the tests)
 
 
 def to_dev_bf16(a):
@@ -30,6 +33,15 @@ class GpuLayer:
             else:
                 self.t[k] = to_dev_bf16(v)
         self.weights = moesd.make_weights(self.t)
+
+    def with_router_bias(self, bias_np):
+        """The same device weights with another (or no) router bias: nothing else is uploaded again."""
+        other = GpuLayer.__new__(GpuLayer)
+        other.shape, other.desc = self.shape, self.desc
+        other.t = dict(self.t)
+        other.t["router_bias"] = None if bias_np is None else to_dev(bias_np.astype(np.float32))
+        other.weights = moesd.make_weights(other.t)
+        return other
 
     def forward(self, x_np, stream=None):
         s = self.shape
@@ -57,14 +69,35 @@ class GpuLayer:
                     n_active=int(na.item()))
 
 
+PARITY_LOG = os.environ.get("MOESD_PARITY_LOG",
+                            os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))),
+                                         "gpurun_out", "parity_cases.tsv"))
+FLOOR_GATE = 1.5e-2
+
+
+def _log_case(label, n_tok, stats):
+    try:
+        os.makedirs(os.path.dirname(PARITY_LOG), exist_ok=True)
+        new = not os.path.exists(PARITY_LOG)
+        with open(PARITY_LOG, "a") as f:
+            if new:
+                f.write("case\ttokens_compared\trel_l2\trounding_floor\tmaxabs_bf16\tmaxabs_f32\tmaxabs_checked_on\n")
+            f.write(f"{label}\t{n_tok}\t{stats['rel_l2']:.3e}\t{stats['floor']:.3e}\t{stats['maxabs_bf16']:.3e}\t"
+                    f"{stats['maxabs_f32']:.3e}\t{stats['maxabs_checked_on']}\n")
+    except OSError:
+        pass
+
+
 def check_outputs(ref, got, tokens=None, label=""):
     """The output bar: relative L2 <= 5e-3 on the bf16 output and max-abs <=
     2e-2 * RMS(out).  Rounding the output to bf16 alone moves an element by up to
-    2^-8 of its magnitude, which on a large element (above ~5 RMS) uses up the
-    whole max-abs budget by itself; the oracle's own rounding floor is reported.
-    So the max-abs bound is tried on the bf16 output first and, if that fails,
-    must hold on the fp32 output (the value before the final rounding); in every
-    case the bf16 output must be bit for bit that fp32 output rounded once."""
+    2^-8 of its magnitude, which on an element above 5.12 RMS uses up the whole
+    max-abs budget by itself.  So the oracle's own rounding floor
+    max|bf16(oracle) - oracle| / RMS is computed first: while it is below 1.5e-2
+    the bound must hold on the bf16 output as it is; above that it must hold on
+    the fp32 output (the value before the final rounding).  In every case the
+    bf16 output must be bit for bit that fp32 output rounded once.  One line per
+    case goes to the parity log."""
     o = ref["out"]
     gb = bf16_bits_to_f32(got["out_bf16"]).astype(np.float64)
     g32 = got["out_f32"].astype(np.float64)
@@ -75,20 +108,20 @@ def check_outputs(ref, got, tokens=None, label=""):
         assert (gb == 0).all() and (g32 == 0).all(), label
         return dict(rel_l2=0.0, maxabs=0.0)
     rel = float(np.linalg.norm(gb - o) / np.linalg.norm(o))
-    assert rel <= 5e-3, (label, "rel_l2", rel)
     ob = bf16_bits_to_f32(ref["out_bf16"]).astype(np.float64)
     floor = float(np.max(np.abs(ob - o)) / rms)
     ma_b = float(np.max(np.abs(gb - o)) / rms)
     ma_f = float(np.max(np.abs(g32 - o)) / rms)
-    on = "bf16"
-    if ma_b > 2e-2:
-        on = "f32"
-        assert ma_f <= 2e-2, (label, "maxabs", dict(bf16=ma_b, f32=ma_f, rounding_floor=floor))
+    on = "bf16" if floor < FLOOR_GATE else "f32"
+    stats = dict(rel_l2=rel, maxabs_bf16=ma_b, maxabs_f32=ma_f, floor=floor, maxabs_checked_on=on)
+    _log_case(label, o.shape[0], stats)
+    assert rel <= 5e-3, (label, "rel_l2", rel)
+    assert (ma_b if on == "bf16" else ma_f) <= 2e-2, (label, "maxabs", stats)
     # the bf16 output is the fp32 output rounded once
     import torch
     want = torch.from_numpy(got["out_f32"]).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
     assert (want == got["out_bf16"]).all(), (label, "bf16 != rne(f32)")
-    return dict(rel_l2=rel, maxabs_bf16=ma_b, maxabs_f32=ma_f, floor=floor, maxabs_checked_on=on)
+    return stats
 
 
 def check_routing(ref, got, label=""):

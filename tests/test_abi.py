@@ -102,6 +102,9 @@ def test_forward_argument_errors_need_no_gpu():
     assert _fwd(sh, 16, ws_bytes=1 << 30, wt={"ws_down": None}) == binding.INVALID_ARG
     assert _fwd(sh, 16, ws_bytes=1 << 30, wt={"w_shared_gate": None}) == binding.INVALID_ARG
     assert _fwd(d, 2**30) == binding.INVALID_ARG                                # T*K >= 2^31
+    big = moesd.make_desc(PRESETS["deepseek-v3"])
+    assert _fwd(big, 300000, ws_bytes=1 << 46) == binding.UNSUPPORTED           # T*d*2 >= 2^32, before any launch
+    assert moesd.moesd_workspace_bytes(big, 300000) == 0
     assert binding.moesd_permute(8, 9, 4, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, stream=0,
                                  check=False) == binding.INVALID_ARG
     assert binding.moesd_permute(8, 2, 4, 0x1000, None, 0x1000, 0x1000, 0x1000, 0x1000, stream=0,

@@ -20,22 +20,85 @@ def say(*a):
 
 @pytest.fixture(scope="module")
 def gpu():
+    import os
     import torch
     assert torch.cuda.is_available(), "these tests need the MI355X"
     from tests import gpu_harness
+    if os.path.exists(gpu_harness.PARITY_LOG):   # one log per test run
+        os.remove(gpu_harness.PARITY_LOG)
     return gpu_harness
 
 
-def run_case(gpu, oracle, shape, T, skew=0.0, zero_x=False, tokens=None, point=0, weights=None):
+_FULL = {}
+
+
+def full_size_weights(name, gpu=None):
+    """Weights of a benchmark preset at full size, on the host and (with gpu) on the device; one preset is
+    kept at a time (config 4 is 22.6 GB)."""
+    if name not in _FULL:
+        _FULL.clear()
+        import gc
+        gc.collect()
+        if gpu is not None:
+            gpu.torch.cuda.empty_cache()
+        _FULL[name] = {"w": synth.make_layer(PRESETS[name], threads=16)}
+    if gpu is not None and "layer" not in _FULL[name]:
+        _FULL[name]["layer"] = gpu.GpuLayer(PRESETS[name], _FULL[name]["w"])
+    return _FULL[name]["w"] if gpu is None else (_FULL[name]["w"], _FULL[name]["layer"])
+
+
+ROW_CLASSES = ((1, 16), (17, 64), (65, 128), (129, 1 << 30))   # rows per expert: the kernels' tile classes
+
+
+def class_of(m):
+    return next(i for i, (lo, hi) in enumerate(ROW_CLASSES) if lo <= m <= hi)
+
+
+def tokens_from_permutation(oracle, shape, w, x, budget=20):
+    """Tokens to compare at a size where the oracle cannot evaluate them all, chosen from the oracle's own
+    routing so that every kind of row position is hit: for each class of expert size (1..16, 17..64, 65..128,
+    more rows) the first and last row of its smallest and of its largest expert; the rows on both sides of a
+    64-row block border and of a 256-row tile border; a token whose K experts lie in different classes; the
+    first and the last token."""
+    T, K = x.shape[0], shape.top_k
+    ids, _, _ = oracle.route(shape, x, w["w_router"], w.get("router_bias"))
+    pr = oracle.permute(shape.E, K, ids)
+    counts, offsets, perm = pr["counts"], pr["offsets"], pr["perm"]
+    rows = []
+    for ci in range(len(ROW_CLASSES)):
+        es = [e for e in range(shape.E) if counts[e] > 0 and class_of(counts[e]) == ci]
+        if not es:
+            continue
+        for e in {min(es, key=lambda e: counts[e]), max(es, key=lambda e: counts[e])}:
+            rows += [offsets[e], offsets[e + 1] - 1]
+    big = [e for e in range(shape.E) if counts[e] > 64]
+    if big:
+        e = max(big, key=lambda e: counts[e])
+        rows += [offsets[e] + 63, offsets[e] + 64]
+        if counts[e] > 256:
+            rows += [offsets[e] + 255, offsets[e] + 256, offsets[e] + 256 * ((counts[e] - 1) // 256) - 1]
+    toks = [0, T - 1] + [int(perm[r]) // K for r in rows]
+    for t in range(T):
+        if len({class_of(counts[e]) for e in ids[t]}) > 1:
+            toks.append(t)
+            break
+    out = []
+    for t in toks:
+        if t not in out:
+            out.append(t)
+    return np.array(sorted(out[:budget]), dtype=np.int32)
+
+
+def run_case(gpu, oracle, shape, T, skew=0.0, zero_x=False, tokens=None, point=0, weights=None, layer=None, x=None):
     say(f"[case] {shape.name} d={shape.d} E={shape.E} K={shape.top_k} I={shape.inter} "
         f"S={shape.shared_inter} score={shape.score_func} T={T} skew={skew} zero={zero_x}")
     w = weights if weights is not None else synth.make_layer(shape, skew_std=skew)
-    x = synth.make_tokens(shape, T, point=point, zero=zero_x)
-    layer = gpu.GpuLayer(shape, w)
+    x = x if x is not None else synth.make_tokens(shape, T, point=point, zero=zero_x)
+    layer = layer if layer is not None else gpu.GpuLayer(shape, w)
     got = layer.forward(x)
     ref = oracle.moe_forward(shape, w, x, tokens=tokens)
     gpu.check_routing(ref, got, shape.name)
-    stats = gpu.check_outputs(ref, got, tokens=tokens, label=f"{shape.name} T={T}")
+    stats = gpu.check_outputs(ref, got, tokens=tokens, label=f"{shape.name} T={T}" + (f" skew={skew}" if skew else ""))
     say(f"       ok: {stats} n_active={got['n_active']}")
     return got, ref
 
@@ -154,6 +217,15 @@ def test_duplicate_router_rows_tie_break(gpu, oracle):
     run_case(gpu, oracle, shape, 40, weights=w)
 
 
+def test_keys_on_fp32_rounding_boundaries(gpu, oracle):
+    # logits that are exact in fp64 whatever the summation order and sit on, just above and well above an
+    # fp32 rounding boundary (tests/test_oracle_layer.py pins the oracle's answer by hand)
+    from tests.test_oracle_layer import rounding_boundary_router
+    shape, w, x, want = rounding_boundary_router()
+    got, ref = run_case(gpu, oracle, shape, x.shape[0], weights=w, x=x)
+    assert (got["ids"] == want[None, :]).all()
+
+
 def test_empty_batch(gpu, oracle):
     shape = PRESETS["tiny"]
     w = synth.make_layer(shape)
@@ -220,35 +292,68 @@ def test_permute_large_and_extreme(gpu, oracle, E, K, T):
     assert int(na.item()) == pr["n_active"]
 
 
+def full_case(gpu, oracle, name, T, point, skew=0.0, all_tokens=False):
+    shape = PRESETS[name]
+    w, layer = full_size_weights(name, gpu)
+    if skew > 0.0:
+        w = dict(w)
+        w["router_bias"] = synth.make_router(shape, skew)["router_bias"]
+        layer = layer.with_router_bias(w["router_bias"])
+    x = synth.make_tokens(shape, T, point=point)
+    tokens = None if all_tokens else tokens_from_permutation(oracle, shape, w, x)
+    return run_case(gpu, oracle, shape, T, skew=skew, tokens=tokens, point=point, weights=w, layer=layer)
+
+
+@pytest.mark.parametrize("T", [1, 4, 16])
+def test_qwen15_shape_full_size_few_tokens(gpu, oracle, T):
+    # benchmark config 1 at full size, T <= 16: shared expert in the small-tile class, top-K and permutation
+    # fused in one workgroup; every token compared
+    full_case(gpu, oracle, "qwen1.5-moe-a2.7b", T, point=150 + T, all_tokens=True)
+
+
 def test_qwen15_shape_full_size_sampled_tokens(gpu, oracle):
-    # benchmark config 1 at full size, T = 64 (B=16, gamma=3): all routing outputs
-    # bit-exact, layer output checked on sampled tokens the oracle evaluates one by one
-    shape = PRESETS["qwen1.5-moe-a2.7b"]
-    w = synth.make_layer(shape, threads=16)
-    run_case(gpu, oracle, shape, 64, tokens=[0, 13, 31, 63], point=163, weights=w)
-    # T = 256 (B=64, gamma=3): routed experts in 64-row wide tiles, the shared expert streamed in four token blocks
-    run_case(gpu, oracle, shape, 256, tokens=[0, 77, 130, 255], point=164, weights=w)
-    # T = 320: the shared expert still streamed (five token blocks); T = 640 (B=160, gamma=3, the largest of this
+    # benchmark config 1 at full size, T = 64 (B=16, gamma=3): all routing outputs bit-exact, every token compared
+    full_case(gpu, oracle, "qwen1.5-moe-a2.7b", 64, point=163, all_tokens=True)
+    # T = 256 (B=64, gamma=3): routed experts in 64-row wide tiles, the shared expert streamed in four token blocks;
+    # from here on the compared tokens are chosen from the oracle's permutation (tile borders, every class)
+    full_case(gpu, oracle, "qwen1.5-moe-a2.7b", 256, point=164)
+    # T = 320: the shared expert still streamed (five token blocks); T = 640 (B=128, gamma=4, the largest of this
     # shape's sweep): routed experts in wide tiles, some beyond 64 rows, the shared expert in the MFMA-tiled kernels
-    run_case(gpu, oracle, shape, 320, tokens=[0, 150, 319], point=165, weights=w)
-    run_case(gpu, oracle, shape, 640, tokens=[0, 333, 639], point=166, weights=w)
+    full_case(gpu, oracle, "qwen1.5-moe-a2.7b", 320, point=165)
+    full_case(gpu, oracle, "qwen1.5-moe-a2.7b", 640, point=166)
+
+
+@pytest.mark.parametrize("T", [1, 4, 16])
+def test_qwen2_shape_full_size_few_tokens(gpu, oracle, T):
+    # benchmark config 2 at full size, T <= 16 (the shared expert, 20480 wide, in small tiles), every token compared
+    full_case(gpu, oracle, "qwen2-57b-a14b", T, point=250 + T, all_tokens=True)
 
 
 def test_qwen2_shape_full_size_sampled_tokens(gpu, oracle):
     # benchmark config 2 at full size (3.5 GB of expert weights, 0.44 GB shared expert), T = 64
     shape = PRESETS["qwen2-57b-a14b"]
-    w = synth.make_layer(shape, threads=16)
-    got, _ = run_case(gpu, oracle, shape, 64, tokens=[0, 21, 42, 63], point=263, weights=w)
+    got, _ = full_case(gpu, oracle, "qwen2-57b-a14b", 64, point=263)
+    w, layer = full_size_weights("qwen2-57b-a14b", gpu)
     # At this size both streaming kernels hand out the tail of their small tiles from a counter, so which
     # workgroup computes which tile differs from launch to launch; the bytes of the result must not.
-    layer = gpu.GpuLayer(shape, w)
     x = synth.make_tokens(shape, 64, point=263)
     for rep in range(3):
         again = layer.forward(x)
         assert np.array_equal(again["out_f32"], got["out_f32"]) and np.array_equal(again["out_bf16"], got["out_bf16"])
         assert np.array_equal(again["perm"], got["perm"]) and again["n_active"] == got["n_active"]
     # the largest T of this shape's sweep (B=256, gamma=4): about 160 rows per expert, every kernel class at once
-    run_case(gpu, oracle, shape, 1280, tokens=[0, 641, 1279], point=264, weights=w)
+    full_case(gpu, oracle, "qwen2-57b-a14b", 1280, point=264)
+
+
+@pytest.mark.parametrize("T", [16, 64, 1280])
+def test_qwen2_shape_full_size_skewed_routing(gpu, oracle, T):
+    # the skewed variant of benchmark config 2: per-expert logit bias N(0, 1.5), Zipf-like expert loads (a few
+    # experts with most of the rows, many with none): classes mixed inside one launch at every T
+    got, _ = full_case(gpu, oracle, "qwen2-57b-a14b", T, point=270 + T, skew=1.5)
+    uniform = PRESETS["qwen2-57b-a14b"]
+    if T == 16:   # visibly fewer activated experts than uniform routing gives (Eq. N(t): 56.4 at T = 16)
+        assert got["n_active"] < 50
+    assert got["counts"].max() > 2 * T * uniform.top_k / uniform.E
 
 
 @pytest.mark.parametrize("shape,T", [
@@ -270,25 +375,32 @@ def test_drawn_units_with_short_tiles(gpu, oracle, shape, T):
     assert np.array_equal(again["out_f32"], got["out_f32"])
 
 
+@pytest.mark.parametrize("T", [1, 4, 16])
+def test_mixtral_shape_full_size_few_tokens(gpu, oracle, T):
+    # benchmark config 3 at full size, T <= 16 (no shared expert, 8 experts of 352 MB), every token compared
+    full_case(gpu, oracle, "mixtral-8x7b", T, point=350 + T, all_tokens=True)
+
+
 def test_mixtral_shape_full_size_tiled_sampled_tokens(gpu, oracle):
     # benchmark config 3 at full size and its largest T (4096: about 1024 rows per expert, the MFMA-tiled
     # kernels with the persistent schedule the benchmark's compute-bound point times); routing bit-exact on
-    # all tokens, output on sampled tokens
-    shape = PRESETS["mixtral-8x7b"]
-    w = synth.make_layer(shape, threads=16)
-    rng = np.random.default_rng(9)
-    tokens = np.sort(rng.choice(4096, size=24, replace=False)).astype(np.int32)
-    run_case(gpu, oracle, shape, 4096, tokens=tokens, point=363, weights=w)
+    # all tokens, output on tokens chosen from the permutation (first / last rows, 64- and 256-row borders)
+    full_case(gpu, oracle, "mixtral-8x7b", 4096, point=363)
     # T = 128 (about 32 rows per expert): every expert in wide tiles, several thousand of them
-    run_case(gpu, oracle, shape, 128, tokens=[0, 41, 90, 127], point=364, weights=w)
+    full_case(gpu, oracle, "mixtral-8x7b", 128, point=364)
+    # T = 256 and 1024 of this shape's sweep: 64 and 256 rows per expert
+    full_case(gpu, oracle, "mixtral-8x7b", 256, point=365)
+    full_case(gpu, oracle, "mixtral-8x7b", 1024, point=366)
+
+
+@pytest.mark.parametrize("T", [1, 4, 16])
+def test_deepseek_shape_full_size_few_tokens(gpu, oracle, T):
+    # benchmark config 4 at full size (sigmoid scores, 256 experts, ungated shared expert), every token compared
+    full_case(gpu, oracle, "deepseek-v3", T, point=450 + T, all_tokens=True)
 
 
 def test_deepseek_shape_full_size_sampled_tokens(gpu, oracle):
-    # benchmark config 4 at full size (22.6 GB of expert weights, sigmoid scores, 256 experts): T = 64 and the
+    # benchmark config 4 at full size (22.6 GB of expert weights): T = 64 (the benchmark's headline point) and the
     # largest T of its sweep (2560: about 80 rows per expert, shared expert through the tiled kernels)
-    shape = PRESETS["deepseek-v3"]
-    w = synth.make_layer(shape, threads=16)
-    run_case(gpu, oracle, shape, 64, tokens=[0, 17, 40, 63], point=463, weights=w)
-    rng = np.random.default_rng(11)
-    tokens = np.sort(rng.choice(2560, size=6, replace=False)).astype(np.int32)
-    run_case(gpu, oracle, shape, 2560, tokens=tokens, point=464, weights=w)
+    full_case(gpu, oracle, "deepseek-v3", 64, point=463)
+    full_case(gpu, oracle, "deepseek-v3", 2560, point=464)

@@ -83,6 +83,45 @@ def test_route_forced_ties(oracle):
     assert (ids[:, 0] == 6).all() and (ids[:, 1] == 1).all()
 
 
+def rounding_boundary_router():
+    """A router whose logits are sums of a few products of powers of two, so they are exact in fp64 in any
+    summation order, and which land on fp32 rounding boundaries.  Token x = s * (1, 2^-12, 2^-20, 0, ...):
+      expert 2:  w = (1, 0, 0)            logit s * 1                       key s * 1
+      expert 5:  w = (1, 2^-12, 0)        s * (1 + 2^-24): the midpoint of 1 and 1 + 2^-23, ties to even -> s * 1
+      expert 7:  w = (1, 2^-12, 2^-20)    s * (1 + 2^-24 + 2^-40): just above the midpoint -> s * (1 + 2^-23)
+      expert 1:  w = (1, 3 * 2^-12, 0)    s * (1 + 3 * 2^-24): midpoint of 1 + 2^-23 and 1 + 2^-22 -> even: s * (1 + 2^-22)
+      others:    w = (0.5, 0, 0)          s * 0.5
+    So the order is 1, 7, then experts 2 and 5 with equal keys (lower index first), whatever s > 0 (a power of two).
+    -> (shape, weights, x, the ids every token must get)"""
+    shape = LayerShape("rounding-boundaries", d=64, E=8, top_k=4, inter=64, seed=77)
+    w = synth.make_layer(shape)
+    wr = np.zeros((shape.E, shape.d), np.float32)
+    wr[:, 0] = 0.5
+    wr[2, :3] = (1.0, 0.0, 0.0)
+    wr[5, :3] = (1.0, 2.0 ** -12, 0.0)
+    wr[7, :3] = (1.0, 2.0 ** -12, 2.0 ** -20)
+    wr[1, :3] = (1.0, 3.0 * 2.0 ** -12, 0.0)
+    w["w_router"] = f32_to_bf16_bits(wr)
+    assert np.array_equal(bf16_bits_to_f32(w["w_router"]), wr)   # every entry is a bf16 value
+    x = np.zeros((3, shape.d), np.float32)
+    for t, s_ in enumerate((1.0, 4.0, 0.25)):
+        x[t, :3] = (s_, s_ * 2.0 ** -12, s_ * 2.0 ** -20)
+    xb = f32_to_bf16_bits(x)
+    assert np.array_equal(bf16_bits_to_f32(xb), x)
+    return shape, w, xb, np.array([1, 7, 2, 5], np.int32)
+
+
+def test_route_keys_on_fp32_rounding_boundaries(oracle):
+    # one rounding of the exact logit to fp32, nearest-even on the midpoint, then ties to the lower index
+    shape, w, x, want = rounding_boundary_router()
+    ids, wts, logits = oracle.route(shape, x, w["w_router"])
+    assert (ids == want[None, :]).all()
+    assert logits[0, 5] == 1.0 + 2.0 ** -24 and logits[0, 7] == 1.0 + 2.0 ** -24 + 2.0 ** -40
+    assert np.float32(logits[0, 5]) == np.float32(1.0) and np.float32(logits[0, 7]) == np.float32(1.0 + 2.0 ** -23)
+    # the weights come from the fp64 logits, so the two experts with equal keys still get different weights
+    assert wts[0, 2] < wts[0, 3]
+
+
 @pytest.mark.parametrize("score", [0, 1])
 @pytest.mark.parametrize("renorm", [0, 1])
 def test_route_weight_invariants(oracle, score, renorm):
