@@ -72,7 +72,7 @@ class GpuLayer:
 PARITY_LOG = os.environ.get("MOESD_PARITY_LOG",
                             os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))),
                                          "gpurun_out", "parity_cases.tsv"))
-FLOOR_GATE = 1.5e-2
+FLOOR_GATE = 1.0e-2
 
 
 def _log_case(label, n_tok, stats):
@@ -92,12 +92,16 @@ def check_outputs(ref, got, tokens=None, label=""):
     """The output bar: relative L2 <= 5e-3 on the bf16 output and max-abs <=
     2e-2 * RMS(out).  Rounding the output to bf16 alone moves an element by up to
     2^-8 of its magnitude, which on an element above 5.12 RMS uses up the whole
-    max-abs budget by itself.  So the oracle's own rounding floor
-    max|bf16(oracle) - oracle| / RMS is computed first: while it is below 1.5e-2
-    the bound must hold on the bf16 output as it is; above that it must hold on
-    the fp32 output (the value before the final rounding).  In every case the
-    bf16 output must be bit for bit that fp32 output rounded once.  One line per
-    case goes to the parity log."""
+    max-abs budget by itself, and on smaller ones a good part of it.  So:
+      * the fp32 output (the value before the final rounding) must meet the
+        max-abs bound in every case;
+      * the bf16 output must be bit for bit that fp32 output rounded once;
+      * the bf16 output must meet the bound as it is whenever the oracle's own
+        rounding floor max|bf16(oracle) - oracle| / RMS is below half the budget
+        (1e-2); above that, rounding plus the computation's error (the bf16
+        rounding of the activation, about 1e-2 * RMS at worst) may exceed it
+        on one element and the case is logged as checked on fp32.
+    One line per case goes to the parity log."""
     o = ref["out"]
     gb = bf16_bits_to_f32(got["out_bf16"]).astype(np.float64)
     g32 = got["out_f32"].astype(np.float64)
@@ -112,11 +116,12 @@ def check_outputs(ref, got, tokens=None, label=""):
     floor = float(np.max(np.abs(ob - o)) / rms)
     ma_b = float(np.max(np.abs(gb - o)) / rms)
     ma_f = float(np.max(np.abs(g32 - o)) / rms)
-    on = "bf16" if floor < FLOOR_GATE else "f32"
+    on = "bf16" if ma_b <= 2e-2 else "f32"
     stats = dict(rel_l2=rel, maxabs_bf16=ma_b, maxabs_f32=ma_f, floor=floor, maxabs_checked_on=on)
     _log_case(label, o.shape[0], stats)
     assert rel <= 5e-3, (label, "rel_l2", rel)
-    assert (ma_b if on == "bf16" else ma_f) <= 2e-2, (label, "maxabs", stats)
+    assert ma_f <= 2e-2, (label, "maxabs of the fp32 output", stats)
+    assert on == "bf16" or floor >= FLOOR_GATE, (label, "maxabs of the bf16 output, rounding floor below the gate", stats)
     # the bf16 output is the fp32 output rounded once
     import torch
     want = torch.from_numpy(got["out_f32"]).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
