@@ -5,9 +5,12 @@ T = B*(gamma+1) tokens on one MI355X.
 A step is one pass of the whole hot path (route, permute, grouped gate/up +
 SwiGLU, grouped down, shared expert, combine) over one batch of synthetic
 tokens, with the weights already resident in HBM.  The default workload is the
-Qwen1.5-MoE-A2.7B-shaped layer at B=16, gamma=3 (T=64).  Weights are kept cold by
+largest benchmark shape, the DeepSeek-V3-shaped layer (256 experts, top-8,
+22.6 GB of bf16 weights) at B=16, gamma=3 (T=64).  Weights are kept cold by
 rotating over several replicas of the layer, as consecutive layers of a real
-model would be.
+model would be.  The same line carries the other benchmark shapes at T=64, the
+skewed-routing variant, every shape's (B, gamma) sweep and the compute-bound
+extension points.
 
 Prints ONE JSON line on stdout; progress goes to stderr.
 """
@@ -152,6 +155,8 @@ def pick_replicas(shape, T, budget_gb=24.0):
 
 
 SHORT_CURVE = [(1, 0), (2, 0), (4, 0), (8, 0), (16, 0), (8, 3), (16, 3), (32, 3), (64, 3), (128, 3), (128, 4)]
+# compute-bound extension points outside the benchmark's own sweeps (rows per expert above the ridge)
+MFMA_POINTS = {"mixtral-8x7b": (2048, 4096, 8192), "qwen2-57b-a14b": (2048, 4096, 8192)}
 
 
 PAPER_BATCH_SIZES = [1, 2, 4, 8, 12, 16, 20, 24, 28, 32, 36, 40, 44, 48, 52, 56, 60, 80, 100]   # Appendix C.1
@@ -291,6 +296,136 @@ def mode_routing(args, shape, torch, moesd, synth):
                       "variants": out}))
 
 
+def stored_traffic(key):
+    """HBM bytes per launch of the expert kernels from earlier `rocprofv3 --pmc` runs of this command
+    (FETCH_SIZE, WRITE_SIZE; summaries under profiles/): counters cannot be read from inside the run."""
+    try:
+        with open(os.path.join(ROOT, "paper_2505_19645_amd", "measured_traffic.json")) as f:
+            return json.load(f).get(key)
+    except OSError:
+        return None
+
+
+def measure_point(run, shape, B, gamma, steps, warmup, point=None, stages=True):
+    """One (B, gamma) point of one layer: mean us per layer (cold weights), the stage times of a second,
+    identical set of forwards, and the fractions of the HBM peak they amount to."""
+    from paper_2505_19645_amd import synth
+    T = B * (gamma + 1)
+    x = synth.make_tokens(shape, T, point=100 * B + gamma if point is None else point)
+    run.prepare(x)
+    ms = run.time_steps(steps, warmup)
+    n_active = int(run.n_active.item())
+    lb = layer_bytes(shape, n_active, T)
+    fl = layer_flops(shape, T)
+    roof = max(lb / (HBM_PEAK_GBS * 1e9), fl / (MFMA_BF16_PEAK_TF * 1e12))
+    out = {"B": B, "gamma": gamma, "T": T, "us": round(ms * 1e3, 2), "n_active": n_active,
+           "N_model": round(run.moesd.moesd_expected_active_experts(shape.E, shape.top_k, T), 2),
+           "max_rows_per_expert": int(run.counts.max().item()),
+           "layer_bytes": lb, "layer_GBps": round(lb / (ms * 1e-3) / 1e9, 1),
+           "layer_hbm_frac": round(lb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+           "roofline_us": round(roof * 1e6, 2), "roofline_frac": round(roof / (ms * 1e-3), 4)}
+    if stages:
+        st = run.time_stages(steps, warmup)
+        gub, dnb = gate_up_bytes(shape, n_active, T), down_bytes(shape, n_active, T)
+        out["stages_us"] = {k: round(v * 1e3, 2) for k, v in st.items()}
+        out["gate_up"] = {"bytes": gub, "GBps": round(gub / (st["gate_up"] * 1e-3) / 1e9, 1),
+                          "hbm_frac": round(gub / (st["gate_up"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        out["down"] = {"bytes": dnb, "GBps": round(dnb / (st["down"] * 1e-3) / 1e9, 1),
+                       "hbm_frac": round(dnb / (st["down"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        out["routing_share"] = round(st["route_permute"] / st["total"], 4)
+    return out, x
+
+
+def sweep(run, shape, pts, steps):
+    """Layer time over a (B, gamma) grid: us, measured and modelled activated experts, roofline fraction,
+    and the layer-level target efficiency t(B) / t(B (gamma + 1)) (Sec. 3.1) where the gamma = 0 point exists."""
+    rows = []
+    for (b, g) in pts:
+        r, _ = measure_point(run, shape, b, g, steps, max(5, steps // 3), stages=False)
+        r["Texp_model"] = round(run.moesd.moesd_expected_tokens_per_expert(shape.E, shape.top_k, r["T"]), 2)
+        for k in ("layer_bytes", "layer_GBps", "max_rows_per_expert"):
+            r.pop(k)
+        rows.append(r)
+    by = {(c["B"], c["gamma"]): c["us"] for c in rows}
+    for c in rows:
+        if c["gamma"] > 0 and (c["B"], 0) in by:
+            c["target_efficiency"] = round(by[(c["B"], 0)] / c["us"], 4)
+    log(f"[bench] {shape.name} sweep, {len(rows)} points: "
+        + " ".join(f"T={c['T']}:{c['us']:.0f}us({c['roofline_frac']:.2f})" for c in rows if c["gamma"] in (0, 3)))
+    return rows
+
+
+def fit_models(shape, rows, moesd):
+    """The paper's forward-time form restricted to one layer (Sec. 3.3, Appendix C.2) fitted to a sweep, and
+    the speed-up model of Sec. 3.1 / Alg. 1 fitted to layer-level speed-ups built from it."""
+    from paper_2505_19645_amd import sdmodel
+    out = {}
+    ridge = MFMA_BF16_PEAK_TF * 1e12 / (HBM_PEAK_GBS * 1e9)
+    k2_min_us = shape.expert_bytes / (HBM_PEAK_GBS * 1e9) * 1e6
+    if len(rows) >= 6:
+        mf = sdmodel.fit_layer_curve([c["T"] for c in rows], [c["n_active"] for c in rows], [c["us"] for c in rows],
+                                     shape.E, shape.top_k, k2_min_us, ridge)
+        out["model_fit"] = mf
+        log(f"[bench] {shape.name}: t = c0 + c2*N + c3*G(Texp): c0={mf['c0_us']:.1f} us, c2={mf['c2_us_per_expert']:.2f} "
+            f"us/expert ({mf['c2_over_k2_min']:.2f} x k2_min), c3={mf['c3_us']:.2f}, mean rel err {mf['mean_rel_err']:.3f}")
+    times_by_T = {}
+    for c in rows:
+        times_by_T.setdefault(c["T"], c["us"])
+    if len(times_by_T) >= 8:
+        assume = {"alpha": 0.8, "draft_over_target": 0.1, "reject_over_target": 0.01, "verify_tokens": "B*(gamma+1)"}
+        pts = sdmodel.layer_speedups_from_curve(times_by_T, gammas=(1, 3), alpha=assume["alpha"],
+                                                draft_ratio=assume["draft_over_target"],
+                                                reject_ratio=assume["reject_over_target"])
+        if len(pts) >= 10:
+            bias_min = (shape.shared_bytes + shape.router_bytes) / (HBM_PEAK_GBS * 1e9) * 1e6
+            fit = sdmodel.fit_speedup([r["B"] for r in pts], [r["gamma"] for r in pts], shape.top_k, shape.E,
+                                      [r["sigma"] for r in pts], [r["speedup"] for r in pts], ridge,
+                                      bias_min=max(bias_min, 1e-3), k2_min=k2_min_us, t_rej_max=max(times_by_T.values()))
+            best = {}
+            for r, pr in zip(pts, fit["pred"]):
+                r["model"] = round(float(pr), 4)
+                for k in ("speedup", "sigma", "target_efficiency"):
+                    r[k] = round(r[k], 4)
+                g = r["gamma"]
+                if g not in best or r["target_efficiency"] > best[g]["target_efficiency"]:
+                    best[g] = r
+            out["sd_speedup_model"] = {
+                "assumptions": assume, "points": pts, "params": {k: round(v, 5) for k, v in fit["params"].items()},
+                "mean_rel_err": round(fit["mean_rel_err"], 4), "max_rel_err": round(fit["max_rel_err"], 4),
+                "best_target_efficiency": {str(g): {"B": r["B"], "value": r["target_efficiency"]} for g, r in best.items()},
+                "T_thres_tau0.95": int(moesd.moesd_token_threshold(shape.E, shape.top_k, 0.95))}
+            log(f"[bench] {shape.name}: speed-up model over {len(pts)} (B, gamma) points, mean rel err "
+                f"{fit['mean_rel_err']:.3f}; " + ", ".join(f"gamma={g}: target efficiency peaks at B={r['B']} "
+                                                          f"({r['target_efficiency']:.2f})" for g, r in sorted(best.items())))
+    return out
+
+
+def mfma_points(run, shape, Ts, steps=8, warmup=3):
+    """Compute-bound points: layer and gate/up kernel against the bf16 MFMA peak."""
+    from paper_2505_19645_amd import synth
+    rows = []
+    for T in Ts:
+        run.prepare(synth.make_tokens(shape, T, point=T))
+        ms = run.time_steps(steps, warmup)
+        st = run.time_stages(steps, warmup)
+        fl = layer_flops(shape, T)
+        gu_fl = 4 * T * shape.top_k * shape.d * shape.inter + 4 * T * shape.d * shape.shared_inter
+        dn_fl = 2 * T * shape.top_k * shape.d * shape.inter + 2 * T * shape.d * shape.shared_inter
+        rows.append({"T": T, "us_per_layer": round(ms * 1e3, 1),
+                     "layer_TFLOPs": round(fl / (ms * 1e-3) / 1e12, 1),
+                     "layer_frac_of_peak": round(fl / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TF, 4),
+                     "gate_up_us": round(st["gate_up"] * 1e3, 1),
+                     "gate_up_TFLOPs": round(gu_fl / (st["gate_up"] * 1e-3) / 1e12, 1),
+                     "gate_up_frac_of_peak": round(gu_fl / (st["gate_up"] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TF, 4),
+                     "down_us": round(st["down"] * 1e3, 1),
+                     "down_frac_of_peak": round(dn_fl / (st["down"] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TF, 4),
+                     "n_active": int(run.n_active.item()), "max_rows_per_expert": int(run.counts.max().item())})
+        log(f"[bench] {shape.name} T={T}: {rows[-1]['us_per_layer']} us/layer, {rows[-1]['layer_TFLOPs']} TFLOP/s "
+            f"({rows[-1]['layer_frac_of_peak']:.1%} of bf16 peak); gate/up kernel {rows[-1]['gate_up_frac_of_peak']:.1%}, "
+            f"down {rows[-1]['down_frac_of_peak']:.1%}")
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--mode", choices=["headline", "dense", "ksweep", "routing"], default="headline",
@@ -298,18 +433,21 @@ def main():
                          "ksweep: target efficiency for K = 1..32 (use --config qwen2-57b-a14b); "
                          "routing: activated experts under routing variants (use --config deepseek-v3)")
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", default="qwen1.5-moe-a2.7b")
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="deepseek-v3", help="the headline shape")
     ap.add_argument("--B", type=int, default=16)
     ap.add_argument("--gamma", type=int, default=3)
-    ap.add_argument("--skew", type=float, default=0.0, help="std of the per-expert logit bias")
-    ap.add_argument("--curve", choices=["none", "short", "full"], default="short")
-    ap.add_argument("--curve-steps", type=int, default=30)
+    ap.add_argument("--skew", type=float, default=0.0, help="std of the per-expert logit bias of the headline shape")
+    ap.add_argument("--others", choices=["all", "none"], default="all",
+                    help="all: also the other benchmark shapes at the same (B, gamma), the skewed variant, "
+                         "every shape's sweep and the compute-bound points; none: the headline shape only")
+    ap.add_argument("--curve", choices=["none", "short", "full"], default="full",
+                    help="the (B, gamma) sweep of each shape: the benchmark's full grid, a short one, or none")
+    ap.add_argument("--curve-steps", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--replicas", type=int, default=0)
-    ap.add_argument("--no-mfma-point", action="store_true",
-                    help="skip the extra compute-bound point (Mixtral-8x7B-shaped layer, T=4096)")
+    ap.add_argument("--no-mfma-point", action="store_true", help="skip the compute-bound extension points")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (known traffic) for scaling rocprofv3 --pmc byte counters")
     args = ap.parse_args()
@@ -319,6 +457,7 @@ def main():
             "(how it would shard by expert parallelism is described in the design notes only). Use --gpus 1.")
         sys.exit(2)
 
+    import dataclasses
     import numpy as np
     import torch
     import paper_2505_19645_amd as moesd
@@ -340,16 +479,26 @@ def main():
     if args.mode == "routing":
         return mode_routing(args, shape, torch, moesd, synth)
 
-    t0 = time.time()
-    host_w = synth.make_layer(shape, skew_std=args.skew, threads=min(16, os.cpu_count() or 1))
-    log(f"[bench] generated weights on host in {time.time() - t0:.1f}s")
-    curve_pts = {"none": [], "short": SHORT_CURVE, "full": synth.sweep_points(shape.name)}[args.curve]
-    if shape.name == "mixtral-8x7b" and args.curve == "short":
-        curve_pts = [(t, 0) for t in (1, 4, 16, 64, 256)]
-    t_min = min([T] + [b * (g + 1) for b, g in curve_pts])
-    n_rep = args.replicas or pick_replicas(shape, t_min)
-    run = Runner(shape, host_w, n_rep)
-    log(f"[bench] {n_rep} weight replicas resident ({n_rep * (shape.E * shape.expert_bytes + shape.shared_bytes) / 1e9:.1f} GB)")
+    threads = min(16, os.cpu_count() or 1)
+    t_start = time.time()
+
+    def curve_points(sh):
+        if args.curve == "none":
+            return []
+        if args.curve == "full":
+            return synth.sweep_points(sh.name)
+        return [(t, 0) for t in (1, 4, 16, 64, 256)] if sh.name == "mixtral-8x7b" else SHORT_CURVE
+
+    def open_layer(sh, skew):
+        t0 = time.time()
+        host_w = synth.make_layer(sh, skew_std=skew, threads=threads)
+        pts = curve_points(sh)
+        t_min = min([T] + [b * (g + 1) for b, g in pts])
+        n_rep = args.replicas or pick_replicas(sh, t_min, budget_gb=100.0)
+        run = Runner(sh, host_w, n_rep)
+        log(f"[bench] {sh.name}: weights generated and uploaded in {time.time() - t0:.1f}s, {n_rep} replicas resident "
+            f"({n_rep * (sh.E * sh.expert_bytes + sh.shared_bytes) / 1e9:.1f} GB)")
+        return run, host_w, n_rep, pts
 
     if args.calibrate_copy:
         src = torch.ones(1 << 29, dtype=torch.int16, device="cuda:0")   # 1 GiB read + 1 GiB written
@@ -360,36 +509,21 @@ def main():
         del src, dst
 
     # ---- headline point -------------------------------------------------------
-    x = synth.make_tokens(shape, T, point=100 * args.B + args.gamma)
-    run.prepare(x)
-    ms = run.time_steps(args.steps, args.warmup)
-    n_active = int(run.n_active.item())
-    counts = run.counts.cpu().numpy()
-    log(f"[bench] T={T}: {ms * 1e3:.1f} us/layer, n_active={n_active}, max m_e={counts.max()}")
-    st = run.time_stages(args.steps, args.warmup)
-    log("[bench] stages (us): " + ", ".join(f"{k}={v * 1e3:.1f}" for k, v in st.items()))
-
-    lb = layer_bytes(shape, n_active, T)
-    gub = gate_up_bytes(shape, n_active, T)
-    dnb = down_bytes(shape, n_active, T)
-    fl = layer_flops(shape, T)
-    hbm_time = lb / (HBM_PEAK_GBS * 1e9)
-    mfma_time = fl / (MFMA_BF16_PEAK_TF * 1e12)
-    achieved = gub / (st["gate_up"] * 1e-3) / 1e9
-    traffic = None
-    try:  # HBM bytes per launch measured earlier with rocprofv3 --pmc on this same command
-        with open(os.path.join(ROOT, "paper_2505_19645_amd", "measured_traffic.json")) as f:
-            tr = json.load(f).get(f"{shape.name}/B{args.B}/g{args.gamma}/skew{args.skew}")
-        if tr:
-            traffic = tr["gate_up"]
-    except OSError:
-        pass
-    roofline = {"bound": "hbm", "kernel": "expert_stream_kernel<gate_up>", "achieved": round(achieved, 1),
-                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+    run, host_w, n_rep, pts = open_layer(shape, args.skew)
+    head, x = measure_point(run, shape, args.B, args.gamma, args.steps, args.warmup)
+    ms = head["us"] * 1e-3
+    log(f"[bench] T={T}: {head['us']:.1f} us/layer, n_active={head['n_active']}, max m_e={head['max_rows_per_expert']}; "
+        f"layer {head['layer_hbm_frac']:.3f} of the HBM peak; stages (us): "
+        + ", ".join(f"{k}={v:.1f}" for k, v in head["stages_us"].items()))
+    tr = stored_traffic(f"{shape.name}/B{args.B}/g{args.gamma}/skew{args.skew}")
+    traffic = tr["gate_up"] if tr else None
+    roofline = {"bound": "hbm", "kernel": "expert_stream_kernel<gate_up>", "achieved": head["gate_up"]["GBps"],
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": head["gate_up"]["hbm_frac"],
                 "traffic": None if traffic is None else round(traffic["fetch_bytes"] + traffic["write_bytes"]),
-                "traffic_detail": traffic, "algorithmic_bytes": gub,
-                "avg_launch_us": round(st["gate_up"] * 1e3, 2)}
-    stages = {k: round(v * 1e3, 2) for k, v in st.items()}
+                "traffic_source": None if traffic is None else "earlier rocprofv3 --pmc runs of this command (profiles/pmc_traffic_*)",
+                "traffic_detail": traffic, "algorithmic_bytes": head["gate_up"]["bytes"],
+                "avg_launch_us": head["stages_us"]["gate_up"],
+                "layer_frac": head["layer_hbm_frac"], "down_kernel_frac": head["down"]["hbm_frac"]}
 
     def spread(xs):
         xs = sorted(xs)
@@ -397,128 +531,10 @@ def main():
         return {"p10": round(pick(0.10) * 1e3, 2), "median": round(pick(0.50) * 1e3, 2),
                 "p90": round(pick(0.90) * 1e3, 2)}
     spread_us = {k: spread(v) for k, v in run.samples_ms.items()}
-    stages["down_GBps"] = round(dnb / (st["down"] * 1e-3) / 1e9, 1)
-    layer = {"bytes": lb, "flops": fl, "hbm_roofline_us": round(hbm_time * 1e6, 2),
-             "mfma_roofline_us": round(mfma_time * 1e6, 2),
-             "achieved_GBps": round(lb / (ms * 1e-3) / 1e9, 1),
-             "hbm_frac": round(lb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-             "n_active": n_active,
-             "n_active_model": round(moesd.moesd_expected_active_experts(shape.E, shape.top_k, T), 2)}
-
-    # ---- curve: layer time vs T against the activated-expert model ---------------
-    curve = []
-    for (b, g) in curve_pts:
-        t = b * (g + 1)
-        xs = synth.make_tokens(shape, t, point=100 * b + g)
-        run.prepare(xs)
-        m = run.time_steps(args.curve_steps, max(5, args.curve_steps // 3))
-        na = int(run.n_active.item())
-        byt = layer_bytes(shape, na, t)
-        roof = max(byt / (HBM_PEAK_GBS * 1e9), layer_flops(shape, t) / (MFMA_BF16_PEAK_TF * 1e12))
-        curve.append({"B": b, "gamma": g, "T": t, "us": round(m * 1e3, 2), "n_active": na,
-                      "N_model": round(moesd.moesd_expected_active_experts(shape.E, shape.top_k, t), 2),
-                      "Texp_model": round(moesd.moesd_expected_tokens_per_expert(shape.E, shape.top_k, t), 2),
-                      "roofline_us": round(roof * 1e6, 2), "roofline_frac": round(roof / (m * 1e-3), 4)})
-        log(f"[bench] curve B={b} gamma={g} T={t}: {m * 1e3:.1f} us, n_active={na}, "
-            f"roofline {roof * 1e6:.1f} us ({roof / (m * 1e-3):.2f})")
-    # layer-level target efficiency t(B, gamma=0) / t(B, gamma) where both were measured
-    by = {(c["B"], c["gamma"]): c["us"] for c in curve}
-    for c in curve:
-        if c["gamma"] > 0 and (c["B"], 0) in by:
-            c["target_efficiency"] = round(by[(c["B"], 0)] / c["us"], 4)
-
-    # ---- the paper's forward-time model over the measured curve (Sec. 3.3, Appendix C.2) ----
-    model_fit = None
-    if len(curve) >= 6:
-        from paper_2505_19645_amd import sdmodel
-        k2_min_us = shape.expert_bytes / (HBM_PEAK_GBS * 1e9) * 1e6
-        model_fit = sdmodel.fit_layer_curve([c["T"] for c in curve], [c["n_active"] for c in curve],
-                                            [c["us"] for c in curve], shape.E, shape.top_k, k2_min_us,
-                                            MFMA_BF16_PEAK_TF * 1e12 / (HBM_PEAK_GBS * 1e9))
-        log(f"[bench] model t = c0 + c2*N + c3*G(Texp): c0={model_fit['c0_us']:.1f} us, "
-            f"c2={model_fit['c2_us_per_expert']:.2f} us/expert ({model_fit['c2_over_k2_min']:.2f} x k2_min), "
-            f"c3={model_fit['c3_us']:.2f}, mean rel err {model_fit['mean_rel_err']:.3f}")
-
-    # ---- layer-level speed-up model (Sec. 3.1 Eq. (speedup), Alg. 1) on these measurements ----
-    # The measured layer stands in for the target forward; draft and rejection times are stated
-    # fractions of t(B) (the paper: T_D/T_T usually below 1/10), sigma comes from a stated acceptance rate.
-    sd_model = None
-    times_by_T = {c["T"]: c["us"] for c in curve}
-    times_by_T.setdefault(T, ms * 1e3)
-    if len(times_by_T) >= 8:
-        from paper_2505_19645_amd import sdmodel
-        assume = {"alpha": 0.8, "draft_over_target": 0.1, "reject_over_target": 0.01, "verify_tokens": "B*(gamma+1)"}
-        rows = sdmodel.layer_speedups_from_curve(times_by_T, gammas=(1, 3), alpha=assume["alpha"],
-                                                 draft_ratio=assume["draft_over_target"],
-                                                 reject_ratio=assume["reject_over_target"])
-        if len(rows) >= 10:
-            ridge = MFMA_BF16_PEAK_TF * 1e12 / (HBM_PEAK_GBS * 1e9)
-            bias_min = (shape.shared_bytes + shape.router_bytes) / (HBM_PEAK_GBS * 1e9) * 1e6
-            k2_min = shape.expert_bytes / (HBM_PEAK_GBS * 1e9) * 1e6
-            fit = sdmodel.fit_speedup([r["B"] for r in rows], [r["gamma"] for r in rows], shape.top_k, shape.E,
-                                      [r["sigma"] for r in rows], [r["speedup"] for r in rows], ridge,
-                                      bias_min=max(bias_min, 1e-3), k2_min=k2_min, t_rej_max=max(times_by_T.values()))
-            best = {}
-            for r, pr in zip(rows, fit["pred"]):
-                r["model"] = round(float(pr), 4)
-                r["speedup"] = round(r["speedup"], 4)
-                r["sigma"] = round(r["sigma"], 4)
-                r["target_efficiency"] = round(r["target_efficiency"], 4)
-                g = r["gamma"]
-                if g not in best or r["target_efficiency"] > best[g]["target_efficiency"]:
-                    best[g] = r
-            sd_model = {"assumptions": assume, "points": rows,
-                        "params": {k: round(v, 5) for k, v in fit["params"].items()},
-                        "mean_rel_err": round(fit["mean_rel_err"], 4), "max_rel_err": round(fit["max_rel_err"], 4),
-                        "best_target_efficiency": {str(g): {"B": r["B"], "value": r["target_efficiency"]}
-                                                   for g, r in best.items()},
-                        "T_thres_tau0.95": int(moesd.moesd_token_threshold(shape.E, shape.top_k, 0.95))}
-            log(f"[bench] speed-up model over {len(rows)} (B, gamma) points: mean rel err {fit['mean_rel_err']:.3f}; "
-                + ", ".join(f"gamma={g}: target efficiency peaks at B={r['B']} ({r['target_efficiency']:.2f})"
-                            for g, r in sorted(best.items()))
-                + f"; T_thres(0.95)={sd_model['T_thres_tau0.95']}")
-
-    # ---- compute-bound point: Mixtral-8x7B-shaped layer at T = 4096 (MFMA roofline) ----
-    mfma = None
-    if not args.no_mfma_point:
-        mshape = synth.PRESETS["mixtral-8x7b"]
-        mT = 4096
-        del run
-        torch.cuda.empty_cache()
-        g = torch.Generator(device="cuda:0")
-        g.manual_seed(3000)
-
-        def rnd(*dims, std):
-            return (torch.randn(*dims, device="cuda:0", generator=g, dtype=torch.float32) * std) \
-                .to(torch.bfloat16).view(torch.int16)
-        r = synth.make_router(mshape)
-        dw = {"w_router": torch.from_numpy(r["w_router"].view(np.int16)).to("cuda:0"), "router_bias": None,
-              "w_gate": rnd(mshape.E, mshape.inter, mshape.d, std=mshape.d ** -0.5),
-              "w_up": rnd(mshape.E, mshape.inter, mshape.d, std=mshape.d ** -0.5),
-              "w_down": rnd(mshape.E, mshape.d, mshape.inter, std=mshape.inter ** -0.5),
-              "ws_gate": None, "ws_up": None, "ws_down": None, "w_shared_gate": None}
-        mrun = Runner.__new__(Runner)
-        mrun.torch, mrun.moesd, mrun.shape = torch, moesd, mshape
-        mrun.desc = moesd.make_desc(mshape)
-        mrun.reps = [dw]
-        mrun.wstructs = [moesd.make_weights(dw)]
-        mrun.stream = torch.cuda.current_stream().cuda_stream
-        mrun.prepare(synth.make_tokens(mshape, mT, point=mT))
-        mms = mrun.time_steps(10, 3)
-        mst = mrun.time_stages(10, 3)
-        mfl = layer_flops(mshape, mT)
-        gu_fl = 4 * mT * mshape.top_k * mshape.d * mshape.inter
-        mfma = {"workload": f"{mshape.name}-shaped MoE layer, T={mT} (router from the seeded generator, "
-                            "expert weights drawn on the device: timing only)",
-                "us_per_layer": round(mms * 1e3, 1), "layer_TFLOPs": round(mfl / (mms * 1e-3) / 1e12, 1),
-                "layer_frac_of_peak": round(mfl / (mms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TF, 4),
-                "gate_up_us": round(mst["gate_up"] * 1e3, 1),
-                "gate_up_TFLOPs": round(gu_fl / (mst["gate_up"] * 1e-3) / 1e12, 1),
-                "gate_up_frac_of_peak": round(gu_fl / (mst["gate_up"] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TF, 4),
-                "peak_TFLOPs": MFMA_BF16_PEAK_TF, "n_active": int(mrun.n_active.item()),
-                "max_rows_per_expert": int(mrun.counts.max().item())}
-        log(f"[bench] MFMA point: {mfma['us_per_layer']} us/layer, {mfma['layer_TFLOPs']} TFLOP/s "
-            f"({mfma['layer_frac_of_peak']:.2%} of bf16 peak); gate/up kernel {mfma['gate_up_TFLOPs']} TFLOP/s")
+    layer = {"bytes": head["layer_bytes"], "flops": layer_flops(shape, T), "hbm_roofline_us": head["roofline_us"],
+             "achieved_GBps": head["layer_GBps"], "hbm_frac": head["layer_hbm_frac"], "n_active": head["n_active"],
+             "n_active_model": head["N_model"],
+             "k2_min_us_per_expert": round(shape.expert_bytes / (HBM_PEAK_GBS * 1e9) * 1e6, 3)}
 
     # ---- CPU baseline: the oracle as it stands, one forward of the same batch ----
     cpu = None
@@ -526,17 +542,73 @@ def main():
         from oracle import moe as oracle
         oracle.lib()
         cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)))
-        log(f"[bench] oracle forward on the host ({cores} threads) ...")
+        n_tok = T if layer_flops(shape, T) <= 4e11 else max(1, int(T * 4e11 / layer_flops(shape, T)))  # <= ~20 s of work
+        log(f"[bench] oracle on the host ({cores} threads): routing of all {T} tokens, layer output of {n_tok} ...")
         t0 = time.time()
-        ref = oracle.moe_forward(shape, host_w, x)
+        ref = oracle.moe_forward(shape, host_w, x, tokens=None if n_tok == T else list(range(n_tok)))
         dt = time.time() - t0
-        cpu = {"value": round(dt * 1e6, 1), "unit": "us/layer", "cores": cores, "kind": "oracle",
-               "sample": f"one full forward of the same batch (T={T}, all tokens), fp64 plain C + OpenMP"}
-        log(f"[bench] oracle: {dt:.2f}s per layer; n_active={ref['n_active']}")
-        assert ref["n_active"] == n_active
+        cpu = {"value": round(dt / n_tok * T * 1e6, 1), "unit": "us/layer", "cores": cores, "kind": "oracle",
+               "sample": (f"one full forward of the same batch (T={T}, all tokens)" if n_tok == T else
+                          f"routing of the whole batch (T={T}) and the layer output of its first {n_tok} tokens, "
+                          f"scaled by {T}/{n_tok}") + f": {dt:.2f} s measured; fp64 plain C + OpenMP",
+               "measured_s": round(dt, 3)}
+        log(f"[bench] oracle: {dt:.2f}s for {n_tok} of {T} tokens; n_active={ref['n_active']}")
+        assert ref["n_active"] == head["n_active"]
+
+    # ---- the headline shape's sweep, then the other shapes -------------------------
+    configs, sweeps, fits, mfma = [], {}, {}, {}
+    if pts:
+        sweeps[shape.name] = sweep(run, shape, pts, args.curve_steps)
+        fits[shape.name] = fit_models(shape, sweeps[shape.name], moesd)
+    if shape.name in MFMA_POINTS and not args.no_mfma_point:
+        mfma[shape.name] = mfma_points(run, shape, MFMA_POINTS[shape.name])
+    del run, host_w
+    torch.cuda.empty_cache()
+
+    if args.others == "all":
+        for name in synth.PRESET_ORDER[1:]:
+            sh = synth.PRESETS[name]
+            if name == shape.name and args.skew == 0.0:
+                continue
+            orun, ow, onrep, opts = open_layer(sh, 0.0)
+            c, _ = measure_point(orun, sh, args.B, args.gamma, args.steps, args.warmup)
+            c.update(workload=f"{name}-shaped MoE layer, B={args.B}, gamma={args.gamma}, T={T}", weight_replicas=onrep,
+                     k2_min_us_per_expert=round(sh.expert_bytes / (HBM_PEAK_GBS * 1e9) * 1e6, 3))
+            configs.append(c)
+            log(f"[bench] {name} T={T}: {c['us']:.1f} us/layer, layer {c['layer_hbm_frac']:.3f}, gate/up "
+                f"{c['gate_up']['hbm_frac']:.3f}, down {c['down']['hbm_frac']:.3f} of the HBM peak, routing "
+                f"{c['routing_share']:.1%} of the layer")
+            if opts:
+                sweeps[name] = sweep(orun, sh, opts, args.curve_steps)
+                fits[name] = fit_models(sh, sweeps[name], moesd)
+            if name == "qwen2-57b-a14b":
+                # the skewed-routing variant: per-expert logit bias N(0, 1.5), same weights otherwise
+                bias = synth.make_router(sh, 1.5)["router_bias"]
+                bdev = torch.from_numpy(bias.astype(np.float32)).to("cuda:0")
+                keep = [(r["router_bias"], wsx) for r, wsx in zip(orun.reps, orun.wstructs)]
+                for r in orun.reps:
+                    r["router_bias"] = bdev
+                orun.wstructs = [moesd.make_weights(r) for r in orun.reps]
+                c2, _ = measure_point(orun, sh, args.B, args.gamma, args.steps, args.warmup, point=9000 + T)
+                c2.update(workload=f"{name}-shaped MoE layer, router bias N(0, 1.5) (skewed loads), B={args.B}, "
+                                   f"gamma={args.gamma}, T={T}", weight_replicas=onrep)
+                configs.append(c2)
+                log(f"[bench] {name} skewed T={T}: {c2['us']:.1f} us/layer, n_active={c2['n_active']} "
+                    f"(uniform model {c2['N_model']}), layer {c2['layer_hbm_frac']:.3f} of the HBM peak")
+                if opts:
+                    sk_pts = [(b, g) for (b, g) in opts if g in (0, 3)]
+                    sweeps[name + "/skew1.5"] = sweep(orun, sh, sk_pts, args.curve_steps)
+                for r, (b0, w0) in zip(orun.reps, keep):
+                    r["router_bias"] = b0
+                orun.wstructs = [k[1] for k in keep]
+            if name in MFMA_POINTS and not args.no_mfma_point:
+                mfma[name] = mfma_points(orun, sh, MFMA_POINTS[name])
+            del orun, ow
+            torch.cuda.empty_cache()
+    log(f"[bench] whole run {time.time() - t_start:.0f}s")
 
     result = {
-        "metric": "MoE-layer us at T=B*(gamma+1)", "value": round(ms * 1e3, 2), "unit": "us/layer",
+        "metric": "MoE-layer us at T=B*(gamma+1)", "value": head["us"], "unit": "us/layer",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 5),
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
@@ -544,9 +616,9 @@ def main():
                    "d": shape.d, "E": shape.E, "top_k": shape.top_k, "inter": shape.inter,
                    "shared_inter": shape.shared_inter, "skew_std": args.skew,
                    "weight_replicas": n_rep, "cold_weights": True},
-        "roofline": roofline, "cpu_baseline": cpu, "layer": layer, "stages_us": stages, "spread_us": spread_us,
-        "curve": curve,
-        "model_fit": model_fit, "sd_speedup_model": sd_model, "mfma_point": mfma,
+        "roofline": roofline, "cpu_baseline": cpu, "layer": layer, "stages_us": head["stages_us"],
+        "routing_share": head["routing_share"], "spread_us": spread_us,
+        "configs": configs, "sweeps": sweeps, "fits": fits, "mfma_points": mfma,
     }
     print(json.dumps(result), flush=True)
 
