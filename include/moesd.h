@@ -206,6 +206,26 @@ int32_t moesd_moe_forward_staged(const moesd_layer_desc *desc, const moesd_weigh
                                  int32_t *offsets, int32_t *perm, int32_t *inv_perm,
                                  int32_t *n_active, void *stream, void *const *events);
 
+/* For callers that cannot allocate device memory around the call (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc):
+ * moesd_moe_forward without the workspace arguments.  The scratch is a
+ * MOESD_STATIC_SCRATCH_BYTES array inside the library's device image; every GPU
+ * the library runs on holds its own copy until the process ends.  The call
+ * allocates nothing and frees nothing.  It returns MOESD_WORKSPACE_TOO_SMALL
+ * (nothing enqueued) when moesd_workspace_bytes(desc, T) exceeds
+ * MOESD_STATIC_SCRATCH_BYTES: 32 MB hold every benchmark shape up to T = 64
+ * (config 1 up to T = 128); T > 128 never fits, the MFMA-tiled kernels' 128 MB of
+ * partial-sum space alone exceed it.  All calls on one GPU share the one array:
+ * calls that overlap in time on one GPU race, also on different streams.  Nothing
+ * in the array needs clearing between calls (the permutation kernel zeroes the two
+ * counters the expert kernels draw from, as it does in a caller's workspace).
+ * Inputs, outputs and the optional outputs are as in moesd_moe_forward. */
+#define MOESD_STATIC_SCRATCH_BYTES (32u << 20)
+int32_t moesd_moe_forward_static(const moesd_layer_desc *desc, const moesd_weights *weights,
+                                 const void *x, int32_t T, void *out, float *out_f32,
+                                 int32_t *topk_ids, float *topk_w, int32_t *counts, int32_t *offsets,
+                                 int32_t *perm, int32_t *inv_perm, int32_t *n_active, void *stream);
+
 /* ---------------------------------------------------------------------------
  * Diagnostics
  * ------------------------------------------------------------------------- */

@@ -12,11 +12,13 @@ LIB_PATH = os.path.join(HERE, "libmoesd.so")
 
 OK, INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP_ERROR = 0, 1, 2, 3, 4
 N_STAGE_EVENTS = 5
+STATIC_SCRATCH_BYTES = 32 << 20
 
 EXPORTS = ["moesd_expected_active_experts", "moesd_expected_active_experts_p",
            "moesd_expected_tokens_per_expert",
            "moesd_token_threshold", "moesd_workspace_bytes", "moesd_route", "moesd_permute",
-           "moesd_moe_forward", "moesd_moe_forward_staged", "moesd_status_string",
+           "moesd_moe_forward", "moesd_moe_forward_staged", "moesd_moe_forward_static",
+           "moesd_status_string",
            "moesd_last_hip_error"]
 
 
@@ -72,6 +74,9 @@ def lib():
         L.moesd_moe_forward.argtypes = fwd
         L.moesd_moe_forward_staged.restype = C.c_int32
         L.moesd_moe_forward_staged.argtypes = fwd + [C.POINTER(C.c_void_p)]
+        L.moesd_moe_forward_static.restype = C.c_int32
+        L.moesd_moe_forward_static.argtypes = [C.POINTER(LayerDesc), C.POINTER(Weights), C.c_void_p, C.c_int32,
+                                               C.c_void_p, C.c_void_p] + [C.c_void_p] * 7 + [C.c_void_p]
         L.moesd_status_string.restype = C.c_char_p
         L.moesd_status_string.argtypes = [C.c_int32]
         L.moesd_last_hip_error.restype = C.c_int32
@@ -186,4 +191,15 @@ def moesd_moe_forward(desc, weights, x, T, out, workspace, out_f32=None, workspa
         st = lib().moesd_moe_forward_staged(*args, arr)
     if check and st != OK:
         raise MoesdError(st, "moesd_moe_forward")
+    return st
+
+
+def moesd_moe_forward_static(desc, weights, x, T, out, out_f32=None, topk_ids=None, topk_w=None, counts=None,
+                             offsets=None, perm=None, inv_perm=None, n_active=None, stream=None, check=True):
+    """moesd_moe_forward on the library's own static scratch array (no workspace argument)."""
+    st = lib().moesd_moe_forward_static(C.byref(desc), C.byref(weights) if weights is not None else None, _ptr(x), T,
+                                        _ptr(out), _ptr(out_f32), _ptr(topk_ids), _ptr(topk_w), _ptr(counts),
+                                        _ptr(offsets), _ptr(perm), _ptr(inv_perm), _ptr(n_active), _stream(stream))
+    if check and st != OK:
+        raise MoesdError(st, "moesd_moe_forward_static")
     return st

@@ -190,12 +190,14 @@ int32_t moesd_permute(int32_t E, int32_t K, int32_t T, const int32_t *topk_ids, 
   return MOESD_OK;
 }
 
-int32_t moesd_moe_forward_staged(const moesd_layer_desc *desc, const moesd_weights *wt,
-                                 const void *x, int32_t T, void *out, float *out_f32,
-                                 void *workspace, size_t workspace_bytes, int32_t *topk_ids,
-                                 float *topk_w, int32_t *counts, int32_t *offsets, int32_t *perm,
-                                 int32_t *inv_perm, int32_t *n_active, void *stream,
-                                 void *const *events) {
+}  // extern "C"
+
+namespace {
+
+// Everything that can be checked without the runtime, in the order the header documents.
+// need_bytes: the scratch the call needs (0 for T == 0).
+int32_t check_forward(const moesd_layer_desc *desc, const moesd_weights *wt, const void *x, int32_t T,
+                      const void *out, size_t *need_bytes) {
   int32_t st = check_desc(desc);
   if (st) return st;
   if ((st = check_T(desc, T))) return st;
@@ -204,6 +206,20 @@ int32_t moesd_moe_forward_staged(const moesd_layer_desc *desc, const moesd_weigh
   if (!wt->w_router || !wt->w_gate || !wt->w_up || !wt->w_down) return MOESD_INVALID_ARG;
   if (has_shared && (!wt->ws_gate || !wt->ws_up || !wt->ws_down)) return MOESD_INVALID_ARG;
   if (has_shared && desc->shared_gate && !wt->w_shared_gate) return MOESD_INVALID_ARG;
+  *need_bytes = 0;
+  if (T == 0) return MOESD_OK;
+  if (!x || !out) return MOESD_INVALID_ARG;
+  *need_bytes = carve(desc, T, nullptr).bytes;
+  return MOESD_OK;
+}
+
+// The launches of one forward; every argument has been checked, `workspace` is 256-byte aligned and
+// large enough.  From here on only the runtime can fail.
+int32_t run_forward(const moesd_layer_desc *desc, const moesd_weights *wt, const void *x, int32_t T,
+                    void *out, float *out_f32, void *workspace, int32_t *topk_ids, float *topk_w,
+                    int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv_perm,
+                    int32_t *n_active, void *stream, void *const *events) {
+  const bool has_shared = desc->shared_inter > 0;
   hipStream_t s = (hipStream_t)stream;
   hipError_t e;
   if (T == 0) {
@@ -215,11 +231,8 @@ int32_t moesd_moe_forward_staged(const moesd_layer_desc *desc, const moesd_weigh
     }
     return MOESD_OK;
   }
-  if (!x || !out || !workspace) return MOESD_INVALID_ARG;
-  if (((uintptr_t)workspace & 255) != 0) return MOESD_INVALID_ARG;
   Workspace ws = carve(desc, T, (char *)workspace);
-  if (workspace_bytes < ws.bytes) return MOESD_WORKSPACE_TOO_SMALL;
-  int dev = 0, n_cu = 0;  // (every argument has been checked; from here on only the runtime can fail)
+  int dev = 0, n_cu = 0;
   if ((e = current_device(&dev, &n_cu)) != hipSuccess) return hip_fail(e);
 
   int32_t *ids = topk_ids ? topk_ids : ws.ids;
@@ -300,6 +313,54 @@ int32_t moesd_moe_forward_staged(const moesd_layer_desc *desc, const moesd_weigh
   return MOESD_OK;
 }
 
+}  // namespace
+
+// Scratch of moesd_moe_forward_static: one array per GPU, held until the process ends.  In host
+// code the array's name is only a handle for hipGetSymbolAddress; kernels get the address it returns.
+static __device__ __align__(256) unsigned char scratch[MOESD_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+// The device address of `scratch` on the device the calling thread has current, looked up once per
+// device ordinal (every thread that fills an entry stores the same address).
+hipError_t static_scratch(void **ptr) {
+  static std::atomic<void *> addr[MOESD_MAX_DEVICES];
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MOESD_MAX_DEVICES) return hipErrorInvalidDevice;
+  void *p = addr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p || ((uintptr_t)p & 255) != 0) return hipErrorInvalidSymbol;
+    addr[dev].store(p, std::memory_order_release);
+  }
+  *ptr = p;
+  return hipSuccess;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t moesd_moe_forward_staged(const moesd_layer_desc *desc, const moesd_weights *wt,
+                                 const void *x, int32_t T, void *out, float *out_f32,
+                                 void *workspace, size_t workspace_bytes, int32_t *topk_ids,
+                                 float *topk_w, int32_t *counts, int32_t *offsets, int32_t *perm,
+                                 int32_t *inv_perm, int32_t *n_active, void *stream,
+                                 void *const *events) {
+  size_t need = 0;
+  int32_t st = check_forward(desc, wt, x, T, out, &need);
+  if (st) return st;
+  if (T > 0) {
+    if (!workspace || ((uintptr_t)workspace & 255) != 0) return MOESD_INVALID_ARG;
+    if (workspace_bytes < need) return MOESD_WORKSPACE_TOO_SMALL;
+  }
+  return run_forward(desc, wt, x, T, out, out_f32, workspace, topk_ids, topk_w, counts, offsets, perm,
+                     inv_perm, n_active, stream, events);
+}
+
 int32_t moesd_moe_forward(const moesd_layer_desc *desc, const moesd_weights *weights, const void *x,
                           int32_t T, void *out, float *out_f32, void *workspace,
                           size_t workspace_bytes, int32_t *topk_ids, float *topk_w, int32_t *counts,
@@ -308,6 +369,23 @@ int32_t moesd_moe_forward(const moesd_layer_desc *desc, const moesd_weights *wei
   return moesd_moe_forward_staged(desc, weights, x, T, out, out_f32, workspace, workspace_bytes,
                                   topk_ids, topk_w, counts, offsets, perm, inv_perm, n_active,
                                   stream, nullptr);
+}
+
+int32_t moesd_moe_forward_static(const moesd_layer_desc *desc, const moesd_weights *weights,
+                                 const void *x, int32_t T, void *out, float *out_f32,
+                                 int32_t *topk_ids, float *topk_w, int32_t *counts, int32_t *offsets,
+                                 int32_t *perm, int32_t *inv_perm, int32_t *n_active, void *stream) {
+  size_t need = 0;
+  int32_t st = check_forward(desc, weights, x, T, out, &need);
+  if (st) return st;
+  if (need > (size_t)MOESD_STATIC_SCRATCH_BYTES) return MOESD_WORKSPACE_TOO_SMALL;
+  void *ws = nullptr;
+  if (T > 0) {
+    hipError_t e = static_scratch(&ws);
+    if (e != hipSuccess) return hip_fail(e);
+  }
+  return run_forward(desc, weights, x, T, out, out_f32, ws, topk_ids, topk_w, counts, offsets, perm,
+                     inv_perm, n_active, stream, nullptr);
 }
 
 }  // extern "C"

@@ -111,6 +111,16 @@ def test_forward_argument_errors_need_no_gpu():
                                  check=False) == binding.INVALID_ARG
     assert binding.moesd_route(d, None, 0x1000, None, 4, 0x1000, 0x1000, 0x1000, 1 << 20, stream=0,
                                check=False) == binding.INVALID_ARG
+    # the entry point on the library's static scratch array: the same checks, and sizes beyond the array
+    wq = binding.Weights()
+    for n, _ in binding.Weights._fields_:
+        setattr(wq, n, 0x1000)
+    assert binding.moesd_moe_forward_static(sh, wq, 0x1000, 2000, 0x1000, stream=0, check=False) == binding.WORKSPACE_TOO_SMALL
+    assert binding.moesd_moe_forward_static(sh, wq, None, 16, 0x1000, stream=0, check=False) == binding.INVALID_ARG
+    assert binding.moesd_moe_forward_static(sh, wq, 0x1000, -1, 0x1000, stream=0, check=False) == binding.INVALID_ARG
+    assert moesd.moesd_workspace_bytes(sh, 64) <= binding.STATIC_SCRATCH_BYTES < moesd.moesd_workspace_bytes(sh, 2000)
+    hdr = open(os.path.join(ROOT, "include", "moesd.h")).read()
+    assert int(re.search(r"MOESD_STATIC_SCRATCH_BYTES \((\d+)u << 20\)", hdr).group(1)) << 20 == binding.STATIC_SCRATCH_BYTES
     assert binding.status_string(binding.WORKSPACE_TOO_SMALL) == "workspace too small"
     with pytest.raises(binding.MoesdError):
         binding.moesd_moe_forward(d, binding.Weights(), 0x1000, -1, 0x1000, 0x1000,
