@@ -47,26 +47,54 @@ def t_exp(E: int, K: int, t: float) -> float:
     return t * K / n if n > 0.0 else 0.0
 
 
+PARAM_NAMES = ("bias", "k1", "k2", "k3", "draft_bias", "draft_k", "reject_bias", "reject_k", "lam", "s")
+
+
+def _named(params):
+    """The ten fitted parameters by name (accepts a mapping or a sequence in PARAM_NAMES order)."""
+    return dict(params) if hasattr(params, "keys") else dict(zip(PARAM_NAMES, params))
+
+
 def target_time(bias, k1, k2, k3, lam, s, RP, E, K, t):
-    """bias + k1*G(t) + k2*N(t) + k3*G(T_exp(t))."""
+    """T_T over t tokens, Sec. 3.3: a fixed part, a dense part that follows the roofline in t, the
+    loading of the N(t) activated experts, and the expert computation that follows the roofline in
+    the per-expert load T_exp(t)."""
     knee = lam * RP
     return bias + k1 * G(t, knee, s) + k2 * n_active(E, K, t) + k3 * G(t_exp(E, K, t), knee, s)
 
 
+def T_target(p, RP, E, K, t):
+    return target_time(p["bias"], p["k1"], p["k2"], p["k3"], p["lam"], p["s"], RP, E, K, t)
+
+
+def T_draft(p, RP, B):
+    """One forward of the (dense) draft model over B tokens: fixed part + roofline in B."""
+    return p["draft_bias"] + p["draft_k"] * G(B, p["lam"] * RP, p["s"])
+
+
+def T_reject(p, B):
+    """Rejection sampling: linear in the batch size."""
+    return p["reject_bias"] + p["reject_k"] * B
+
+
+def verified_tokens(B, gamma, bonus):
+    return B * (gamma + 1) if bonus else B * gamma
+
+
+def T_SD_round(p, B, gamma, K, E, RP, bonus):
+    """Eq. (T_SD): one round = gamma draft forwards, one verification forward, one rejection step."""
+    return gamma * T_draft(p, RP, B) + T_target(p, RP, E, K, verified_tokens(B, gamma, bonus)) + T_reject(p, B)
+
+
 def compute_speedup(params, B, gamma, K, E, sig, RP, bonus=False):
-    """params = (bias, k1, k2, k3, draft_bias, draft_k, reject_bias, reject_k, lambda, s)."""
-    bias, k1, k2, k3, draft_bias, draft_k, reject_bias, reject_k, lam, s = params
-    ar_time = target_time(bias, k1, k2, k3, lam, s, RP, E, K, B)
-    t_verify = B * (gamma + 1) if bonus else B * gamma
-    verify_time = target_time(bias, k1, k2, k3, lam, s, RP, E, K, t_verify)
-    draft_time = draft_bias + draft_k * G(B, lam * RP, s)
-    reject_time = reject_bias + reject_k * B
-    return sig * (gamma + 1) * ar_time / (gamma * draft_time + verify_time + reject_time)
+    """Eq. (speedup): a round yields sigma * (gamma + 1) tokens per request in T_SD_round, against one
+    token per autoregressive forward T_T(B)."""
+    p = _named(params)
+    tokens_per_round = sig * (gamma + 1)
+    return tokens_per_round * T_target(p, RP, E, K, B) / T_SD_round(p, B, gamma, K, E, RP, bonus)
 
 
 def target_efficiency(params, B, gamma, K, E, RP, bonus=False):
     """T_T(B, 1) / T_T(B, gamma) (Sec. 3.1)."""
-    bias, k1, k2, k3, _, _, _, _, lam, s = params
-    t_verify = B * (gamma + 1) if bonus else B * gamma
-    return (target_time(bias, k1, k2, k3, lam, s, RP, E, K, B) /
-            target_time(bias, k1, k2, k3, lam, s, RP, E, K, t_verify))
+    p = _named(params)
+    return T_target(p, RP, E, K, B) / T_target(p, RP, E, K, verified_tokens(B, gamma, bonus))

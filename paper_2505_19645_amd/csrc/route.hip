@@ -3,8 +3,12 @@
 // The paper's Sec. 3.2 counts how many of the E experts t tokens activate when
 // each token picks K of them; this file is the picking.  The logits are
 // accumulated in fp64 (products of two bf16 values are exact there) and rounded
-// once to fp32: that fp32 value is the selection key, so any summation order
-// gives the same expert ids.
+// once to fp32: that fp32 value is the selection key.  Two summation orders give
+// fp64 sums that differ by about 1e-16 relative, so the key, and with it the
+// expert ids, can differ only when a logit lies within that distance of an fp32
+// rounding boundary: the ids are order-independent by margin, not by construction
+// (logits built from a few powers of two are exact in any order; a test puts such
+// logits on and next to rounding boundaries).
 #include "common.h"
 #include "route_device.h"
 
