@@ -48,18 +48,21 @@ __device__ __forceinline__ float silu_f32(float z) {
 // ---- launch descriptors (host fills, passed by value) ------------------------
 
 // Plan written by the permutation kernel for the expert kernels (int32 words):
-//   [0] n_small: experts with 1..16 rows
-//   [1] n_big:   (expert, 64-row block) entries of the experts with 17..128 rows (17..64 when
-//                enough experts exceed 64 rows for the tiled kernels to be worth it)
-//   [2] n_large: (expert, 256-row block) entries of the experts with more rows than that
+//   [0] n_small:  experts with 1..16 rows
+//   [1] n_big64:  experts with 17..64 rows
+//   [2] n_large:  (expert, 256-row block) entries of the experts with more than 128 rows
+//   [3] n_big128: experts with 65..128 rows
 //   [PLAN_CTR], [PLAN_CTR+1]  zero: the counters from which the gate/up and the down streaming
 //                kernel draw units of tiles
 //   [PLAN_HDR .. +E)        ids of the small experts, ascending
-//   [PLAN_HDR+E .. +4E)     n_big pairs (expert id, block index), ascending by expert, block
+//   [PLAN_HDR+E .. +2E)     ids of the experts with 17..64 rows, ascending
+//   [PLAN_HDR+2E .. +3E)    ids of the experts with 65..128 rows, ascending
 //   [PLAN_HDR+5E .. )       n_large pairs (expert id, block index), ascending by expert, block
 #define PLAN_HDR 8
 #define PLAN_CTR 4
 #define PLAN_BIG_MAX_ROWS 128
+#define PLAN_BIG64_OFF(E) (PLAN_HDR + (E))
+#define PLAN_BIG128_OFF(E) (PLAN_HDR + 2 * (E))
 #define PLAN_LARGE_OFF(E) (PLAN_HDR + 5 * (E))
 #define PLAN_WORDS(E, TK) (PLAN_LARGE_OFF(E) + 2 * ((E) + (TK) / 256 + 2))
 
@@ -101,12 +104,12 @@ hipError_t launch_router_logits(const uint16_t *x, const uint16_t *w_router, con
 hipError_t launch_topk(const double *logits, int T, int E, int K, int score_func, int renorm,
                        float scale, int groups, int has_shared_gate, int32_t *ids, float *w,
                        float *gate, hipStream_t s);
-// row_token / plan may be NULL (standalone permutation).  tiled_min: experts with 65..128 rows
-// go to the tiled kernels' list if at least that many experts have more than 64 rows
-// (INT_MAX: never).
+// row_token / plan may be NULL (standalone permutation).  wide_fill_min: experts with 65..128 rows
+// go to the tiled kernels' list if some expert has more than 128 rows and fewer than that many
+// experts have 17..128 rows (0: never).
 hipError_t launch_permute(const int32_t *ids, int64_t n, int E, int K, int32_t *counts,
                           int32_t *offsets, int32_t *perm, int32_t *inv, int32_t *n_active,
-                          int32_t *row_token, int32_t *plan, int tiled_min, hipStream_t s);
+                          int32_t *row_token, int32_t *plan, int wide_fill_min, hipStream_t s);
 // top-K and permutation in one launch; only for E <= 256 and few tokens
 hipError_t launch_topk_permute(const double *logits, int T, int E, int K, int score_func, int renorm,
                                float scale, int groups, int has_shared_gate, int32_t *ids, float *w,

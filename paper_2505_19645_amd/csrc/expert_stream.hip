@@ -12,8 +12,8 @@
 //    also multiplies, the MFMAs would start only after that.  The two sides meet at one
 //    s_barrier per slot: the loading waves arrive when slot k has landed, the multiplying
 //    waves when they are done with slot k-1, whose ring position is then refilled.
-//  * Two tile shapes, so that the token rows never cost more than half the
-//    weight bytes that travel with them:
+//  * Three tile shapes, so that the token rows never cost more than the weight
+//    bytes that travel with them and every expert's weights stream once:
 //      small: an expert (or token block) with 1..16 rows.  32 weight rows (16 of
 //             w_gate + the same 16 of w_up, or 32 rows of w_down), contraction
 //             blocks of 512 elements; a block is one 48 KB slot: 32 KB of
@@ -21,8 +21,8 @@
 //      wide:  17..64 rows.  128 weight rows (64 + 64, or 128 of w_down), contraction
 //             blocks of 256 elements; a block is three 32 KB slots: the 64 token
 //             rows, 64 rows of the first operand half, 64 of the second.
-//    Experts with 65..128 rows run as two wide blocks (their weights stream twice);
-//    beyond that they belong to the MFMA-tiled kernel.
+//      wide, 65..128 rows: the same with two token slots per block (four slots).
+//    Experts beyond 128 rows belong to the MFMA-tiled kernel.
 //  * Every slot is exactly twelve (wide: eight) global_load_lds_dwordx4 per loading wave, each
 //    moving 1 KB (one 1 KB row piece, wide: two 512-byte pieces, contiguous in HBM:
 //    256-byte pieces stream at three quarters of the rate, and the longer the blocks
@@ -42,9 +42,10 @@
 //    writes stay linear.
 //  * Small tiles: the four multiplying waves split the sixteen 32-element MFMA steps of a
 //    block and add their partial 16x16 tiles through LDS in a fixed order.
-//    Wide tiles: the waves form 2 x 2: a wave multiplies 32 token rows, whose
-//    fragments of the whole block it keeps in registers (the token slot is free as
-//    soon as it has been read), by 32 rows of every weight slot; no reduction.
+//    Wide tiles: a wave multiplies 32 token rows, whose fragments of the whole block
+//    it keeps in registers (a token slot is free as soon as it has been read), by 32
+//    rows of every weight slot (64-row class: the waves form 2 x 2) or by all 64
+//    (128-row class: one wave per 32 token rows); no reduction.
 //    Results never depend on scheduling.
 //
 // MFMA operand use (v_mfma_f32_16x16x32_bf16): lane l = 16*q + r supplies 8
@@ -52,6 +53,7 @@
 // as A and of token row r as B; it receives, for token r, output features
 // 4*q .. 4*q+3.
 #include "common.h"
+#include "stream_sched.h"
 
 #define SLOT_BYTES 49152   // one ring slot
 #define RING 3             // slots in the ring
@@ -60,42 +62,30 @@
 #define RED_ROW 20         // floats per token row of a partial tile: 16 features + 4 of padding (bank spread)
 #define RED_TILE (16 * RED_ROW)
 #define RED_BYTES (8 * RED_TILE * 4)  // 4 waves x 2 halves x 16 rows
-#define SMALL_M 16
-#define BIG_TB 64
 #define STREAM_LDS_BYTES (RING * SLOT_BYTES + RED_BYTES + 64)  // + the four words that carry drawn units
 #define STREAM_THREADS 512  // waves 0..3 multiply, waves 4..7 load
 // small tiles
-#define KB 512             // contraction elements per block
 #define SROW_BYTES 1024
 #define A_BYTES 32768      // 2 halves x 16 rows x 1 KB
 #define ROW_BYTES 512      // (wide tiles)
 // wide tiles: 512-byte row pieces as well (256-byte pieces stream from HBM at about three quarters of
 // the rate), three 32 KB slots per block: the 64 token rows, 64 rows of the first operand half, 64
 // of the second
-#define KBW 256
 #define WSLOT_BYTES 32768
 #define WRING 4            // every slot is consumed in the step it arrives in
 #define WAHEAD 3
 #define WLW 8              // loads per wave per slot
-#ifndef WNW
-#define WNW 2              // weight slots per block: a wide tile has 64 * WNW weight rows (4 measured no
-#endif                     // faster where tiles abound and much slower where they are few)
-#define WHROWS (32 * WNW)  // rows of each operand half in a wide tile
-// the schedule's cost model, in hundredths of a routed expert's small slot
-#define COST_WIDE_SLOT 100
-#define COST_CLASS_SWITCH 650
-#define COST_DISTINCT_ROWS 15
-#ifndef DYN_STATIC_PCT
-#define DYN_STATIC_PCT 60  // share of a long small line that is dealt in fixed ranges (100: all of it)
+#ifndef W128_FRAG_DEPTH
+#define W128_FRAG_DEPTH 2  // chunks of weight fragments in flight in the 128-row class
 #endif
-#ifndef DYN_MIN_SLOTS
-#define DYN_MIN_SLOTS 40   // slots of small tiles per workgroup from which units are drawn at all
-#endif
-#ifndef DYN_MIN_TILES
-#define DYN_MIN_TILES 12   // and small tiles per workgroup (a few long tiles are better dealt evenly)
-#endif
+// token slots per block of a class (the small class keeps its tokens inside the one slot)
+template <int CLS> struct ClsGeo {
+  static constexpr bool WIDE = CLS != CLS_SMALL;
+  static constexpr int NTS = CLS == CLS_W128 ? 2 : 1;
+  static constexpr int NSUB = WIDE ? NTS + WNW : 1;  // slots per block
+  static constexpr int ROWS = CLS == CLS_SMALL ? SMALL_M : (CLS == CLS_W64 ? W64_TB : W128_TB);
+};
 
-enum { MODE_GATE_UP = 0, MODE_DOWN = 1 };
 
 // ---- hand-issued memory operations --------------------------------------------
 // lds_base is wave-uniform by construction; readfirstlane makes that explicit so the
@@ -229,42 +219,13 @@ __device__ __forceinline__ void fill_group(Entry &en, const StreamArgs &a, bool 
   }
 }
 
-// The tiles of one class (wide or small) that a workgroup processes: ids
-// id0, id0 + stride, ...  The class's tile ids run over [shared expert's tiles]
-// [routed entries x row tiles].
-struct ClassCfg {
-  int n_mine, id0, stride;
-  int n_sh;    // shared-expert tiles at the head of the class
-  int per_s;   // row tiles per shared entry
-  int per_r;   // row tiles per routed entry
-  int parts;   // k-parts of the shared down projection (1 for gate/up)
-  // Small tiles only: after its own range (n_mine tiles from id0) the workgroup draws units of
-  // further tiles from a counter shared by all workgroups.  Units u < n_double hold 2 * ut tiles,
-  // the others ut, the last one also what is left of the line; all lie in [pool0, n_tiles).
-  int dyn;
-  int n_units, n_double, ut, pool0, n_tiles;
-  int32_t *ctr;
-};
-
-// tiles [t0, t1) of drawn unit u; empty when the counter has run past the last unit
-__device__ __forceinline__ void unit_range(const ClassCfg &c, int u, int &t0, int &t1) {
-  if (u < 0 || u >= c.n_units) {
-    t0 = t1 = 0;
-  } else if (u < c.n_double) {
-    t0 = c.pool0 + u * 2 * c.ut;
-    t1 = t0 + 2 * c.ut;
-  } else {
-    t0 = c.pool0 + c.n_double * 2 * c.ut + (u - c.n_double) * c.ut;
-    t1 = (u == c.n_units - 1) ? c.n_tiles : t0 + c.ut;
-  }
-}
-
 // entry that owns tile `id` of the class
-template <int MODE, bool WIDE>
+template <int MODE, int CLS>
 __device__ __forceinline__ Entry load_entry(const StreamArgs &a, const Tables &tb_, const ClassCfg &c,
                                             int id) {
   Entry en;
-  constexpr int rows = WIDE ? BIG_TB : SMALL_M;
+  constexpr bool WIDE = ClsGeo<CLS>::WIDE;
+  constexpr int rows = ClsGeo<CLS>::ROWS;
   if (id < c.n_sh) {
     const int per = c.per_s;
     const int blk = id / per;  // gate/up: token block; down: (token block, part)
@@ -278,16 +239,13 @@ __device__ __forceinline__ Entry load_entry(const StreamArgs &a, const Tables &t
   } else {
     const int per = c.per_r;
     const int entry = (id - c.n_sh) / per;
-    int e, tbk = 0;
-    if (WIDE) {
-      sload2(tb_.plan, PLAN_HDR + a.E + 2 * entry, PLAN_HDR + a.E + 2 * entry + 1, e, tbk);
-    } else {
-      e = sload(tb_.plan, PLAN_HDR + entry);
-    }
+    // the class's list of expert ids in the plan; an expert is one block of its class
+    const int list = CLS == CLS_SMALL ? PLAN_HDR : (CLS == CLS_W64 ? PLAN_BIG64_OFF(a.E) : PLAN_BIG128_OFF(a.E));
+    const int e = sload(tb_.plan, list + entry);
     int beg, end;
     sload2(tb_.offsets, e, e + 1, beg, end);
-    en.row0 = beg + tbk * rows;
-    en.m = min(end - en.row0, rows);
+    en.row0 = beg;
+    en.m = min(end - beg, rows);
     en.tiles = per;
     en.first = c.n_sh + entry * per;
     fill_group<MODE>(en, a, false, e, 0);
@@ -305,19 +263,19 @@ __device__ __forceinline__ int tile_i0(int rt) {
 
 // Per-lane source pointers of the DMA instructions this wave issues.
 //   small: a[0..7] weights, b[0..3] tokens (one 1 KB row per instruction)
-//   wide:  b[0..7] tokens; the weight rows' addresses are formed when a slot is issued (i0: the
-//          tile's first weight row)
-template <bool WIDE>
+//   wide:  b[0..8*NTS) tokens, eight per token slot; the weight rows' addresses are formed when a
+//          slot is issued (i0: the tile's first weight row)
+template <int CLS>
 struct LoadPtrs {
-  const uint16_t *a[WIDE ? 1 : 8];
-  const uint16_t *b[WIDE ? 8 : 4];
+  const uint16_t *a[ClsGeo<CLS>::WIDE ? 1 : 8];
+  const uint16_t *b[ClsGeo<CLS>::WIDE ? 8 * ClsGeo<CLS>::NTS : 4];
   int i0;
 };
 
-template <int MODE, bool WIDE>
-__device__ __forceinline__ void setup_b(LoadPtrs<WIDE> &lp, const Entry &en,
+template <int MODE, int CLS>
+__device__ __forceinline__ void setup_b(LoadPtrs<CLS> &lp, const Entry &en,
                                         const int32_t *__restrict__ row_token, int wave, int lane) {
-  if (!WIDE) {
+  if (!ClsGeo<CLS>::WIDE) {
     int tok[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) tok[i] = en.row0 + min(wave * 4 + i, en.m - 1);  // token rows of the tile
@@ -330,24 +288,28 @@ __device__ __forceinline__ void setup_b(LoadPtrs<WIDE> &lp, const Entry &en,
   } else {
     const int half = lane >> 5, pos = lane & 31;
 #pragma unroll
-    for (int i = 0; i < 8; i += 2) {
-      const int pair = wave * 8 + i;  // token rows 2*pair .. 2*pair+3 of this and the next instruction
-      int t4[4];
+    for (int ts = 0; ts < ClsGeo<CLS>::NTS; ++ts) {  // token slot ts holds token rows 64 ts .. 64 ts + 63
 #pragma unroll
-      for (int j = 0; j < 4; ++j) t4[j] = en.row0 + min(2 * pair + j, en.m - 1);
-      if (en.use_map) sload4(row_token, t4[0], t4[1], t4[2], t4[3], t4[0], t4[1], t4[2], t4[3]);
+      for (int i = 0; i < 8; i += 2) {
+        const int pair = wave * 8 + i;  // rows 2*pair .. 2*pair+3 of the slot: this and the next instruction
+        int t4[4];
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int tok = half ? t4[2 * j + 1] : t4[2 * j];
-        const int r = 2 * (pair + j) + half;
-        lp.b[i + j] = en.b + (size_t)tok * en.b_stride + ((pos ^ (r & 15)) << 3);
+        for (int j = 0; j < 4; ++j) t4[j] = en.row0 + min(64 * ts + 2 * pair + j, en.m - 1);
+        if (en.use_map) sload4(row_token, t4[0], t4[1], t4[2], t4[3], t4[0], t4[1], t4[2], t4[3]);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const int tok = half ? t4[2 * j + 1] : t4[2 * j];
+          const int r = 2 * (pair + j) + half;
+          lp.b[8 * ts + i + j] = en.b + (size_t)tok * en.b_stride + ((pos ^ (r & 15)) << 3);
+        }
       }
     }
   }
 }
 
-template <int MODE, bool WIDE>
-__device__ __forceinline__ void setup_a(LoadPtrs<WIDE> &lp, const Entry &en, int rt, int wave, int lane) {
+template <int MODE, int CLS>
+__device__ __forceinline__ void setup_a(LoadPtrs<CLS> &lp, const Entry &en, int rt, int wave, int lane) {
+  constexpr bool WIDE = ClsGeo<CLS>::WIDE;
   const int i0 = tile_i0<MODE, WIDE>(rt);
   if (!WIDE) {
     // valid rows in each 16-row half of this tile (at least 1 after clamping)
@@ -369,9 +331,11 @@ __device__ __forceinline__ void setup_a(LoadPtrs<WIDE> &lp, const Entry &en, int
 
 // Issue one slot: exactly LW loads per wave.  Pieces past the end of a row are
 // pulled back inside it; their products are masked in the MFMA loop.
-template <int MODE, bool WIDE>
-__device__ __forceinline__ void issue_slot(const LoadPtrs<WIDE> &lp, const Entry &en, int kb, int sub,
+template <int MODE, int CLS>
+__device__ __forceinline__ void issue_slot(const LoadPtrs<CLS> &lp, const Entry &en, int kb, int sub,
                                            uint32_t slot_base, int wave, int lane) {
+  constexpr bool WIDE = ClsGeo<CLS>::WIDE;
+  constexpr int NTS = ClsGeo<CLS>::NTS;
   const int klen = en.klen;
   if (!WIDE) {
     const int k0 = kb * KB;
@@ -392,8 +356,8 @@ __device__ __forceinline__ void issue_slot(const LoadPtrs<WIDE> &lp, const Entry
       dma16(lp.b[i] + koff(r), slot_base + A_BYTES + (uint32_t)r * 1024u);
     }
   } else {
-    // sub 0: the 64 token rows; sub 1 .. WNW: 64 weight rows each (gate/up: the first WNW/2 slots
-    // hold w_gate rows, the others the same rows of w_up; down: consecutive rows).
+    // sub 0 .. NTS-1: 64 token rows each; then WNW slots of 64 weight rows each (gate/up: the first
+    // WNW/2 hold w_gate rows, the others the same rows of w_up; down: consecutive rows).
     // Wave w moves rows 16w .. 16w+15 of the slot, two per instruction.
     const int k0 = kb * KBW;
     const bool full = k0 + KBW <= klen;
@@ -409,8 +373,14 @@ __device__ __forceinline__ void issue_slot(const LoadPtrs<WIDE> &lp, const Entry
         const int pair = wave * 8 + i;
         dma16(lp.b[i] + koff(2 * pair + half), slot_base + (uint32_t)pair * 1024u);
       }
+    } else if (NTS == 2 && sub == 1) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int pair = wave * 8 + i;
+        dma16(lp.b[(NTS == 2 ? 8 : 0) + i] + koff(2 * pair + half), slot_base + (uint32_t)pair * 1024u);
+      }
     } else {
-      const int w = sub - 1;
+      const int w = sub - NTS;
       const uint16_t *base = (MODE == MODE_GATE_UP && w >= WNW / 2) ? en.a1 : en.a0;
       const int first = (MODE == MODE_GATE_UP) ? 64 * (w % (WNW / 2)) : 64 * w;  // of the tile's rows in this matrix
       const int rv = min((MODE == MODE_GATE_UP) ? WHROWS : 2 * WHROWS, en.n_rows - lp.i0);  // valid ones
@@ -464,9 +434,11 @@ __device__ __forceinline__ void store_out4(void *out, int out_n, size_t orow, in
 }
 
 // All tiles of one class for this workgroup: the software pipeline.
-template <int MODE, bool WIDE>
+template <int MODE, int CLS>
 __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_, const ClassCfg &c,
                                           char *smem) {
+  constexpr bool WIDE = ClsGeo<CLS>::WIDE;
+  constexpr int NTS = ClsGeo<CLS>::NTS, NSUB = ClsGeo<CLS>::NSUB;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = uni(tid >> 6);
   const int r16 = lane & 15, q = lane >> 4;
@@ -501,21 +473,21 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
     const int lw = wave - 4;
     unsigned long long single = 0ull;  // bit s & 63: slot s is the only one of its tile
     int l_i = 0, l_kb = 0, l_slot = 0;
-    int l_sub = 0;  // wide: 0 tokens, 1 first operand half, 2 second
+    int l_sub = 0;  // wide: 0 .. NTS-1 token slots, then the WNW weight slots
     int l_id = dyn ? first_t0 : c.id0, l_end = first_t1, l_n = 0;  // (dyn: tile, end of its unit, unit number)
     bool l_need = false;  // dyn: the unit is used up, the next one is fetched when its first slot is due
-    Entry len = load_entry<MODE, WIDE>(a, tb_, c, l_id);
-    LoadPtrs<WIDE> lp;
-    setup_b<MODE, WIDE>(lp, len, tb_.row_token, lw, lane);
-    setup_a<MODE, WIDE>(lp, len, l_id - len.first, lw, lane);
+    Entry len = load_entry<MODE, CLS>(a, tb_, c, l_id);
+    LoadPtrs<CLS> lp;
+    setup_b<MODE, CLS>(lp, len, tb_.row_token, lw, lane);
+    setup_a<MODE, CLS>(lp, len, l_id - len.first, lw, lane);
     bool l_live = true;
 
     auto open_tile = [&](int id) __attribute__((always_inline)) {
       if (id - len.first >= len.tiles || id < len.first) {
-        len = load_entry<MODE, WIDE>(a, tb_, c, id);
-        setup_b<MODE, WIDE>(lp, len, tb_.row_token, lw, lane);
+        len = load_entry<MODE, CLS>(a, tb_, c, id);
+        setup_b<MODE, CLS>(lp, len, tb_.row_token, lw, lane);
       }
-      setup_a<MODE, WIDE>(lp, len, id - len.first, lw, lane);
+      setup_a<MODE, CLS>(lp, len, id - len.first, lw, lane);
     };
     auto advance_load = [&]() __attribute__((always_inline)) {
       if (dyn && l_need) {
@@ -530,11 +502,11 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
         l_need = false;
         open_tile(l_id);
       }
-      issue_slot<MODE, WIDE>(lp, len, l_kb, l_sub, lds0 + (uint32_t)(l_slot % RG) * SLOTB, lw, lane);
+      issue_slot<MODE, CLS>(lp, len, l_kb, l_sub, lds0 + (uint32_t)(l_slot % RG) * SLOTB, lw, lane);
       // a tile of one slot: the multiplying waves put one more barrier into that slot's step
       if (!WIDE) single = (single & ~(1ull << (l_slot & 63))) | ((unsigned long long)(len.nkb == 1) << (l_slot & 63));
       ++l_slot;
-      if (WIDE && l_sub < WNW) {
+      if (WIDE && l_sub < NSUB - 1) {
         ++l_sub;
         return;
       }
@@ -572,10 +544,9 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
   } else {
     // ---- multiplying waves: the compute cursor -------------------------------------------
     int c_i = 0, c_kb = 0, c_slot = 0;
-    int c_sub = 0;
     int c_id = dyn ? first_t0 : c.id0, c_end = first_t1, c_n = 0;
     bool c_first = dyn;  // dyn: this is the first step of a unit
-    Entry cen = load_entry<MODE, WIDE>(a, tb_, c, c_id);
+    Entry cen = load_entry<MODE, CLS>(a, tb_, c, c_id);
     f32x4 acc0[NACC], acc1[NACC];
 #pragma unroll
     for (int nt = 0; nt < NACC; ++nt) {
@@ -601,37 +572,42 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
       pend = false;
     };
 
-    // wide: waves as 2 (row halves of a slot) x 2 (token halves); the wave's 2 x 16 token rows of the
-    // current block, all 8 steps, stay in registers
+    // Wide tiles: a wave keeps the fragments of its 2 x 16 token rows of the current block, all 8 steps,
+    // in registers.  64-row class: the waves form 2 (row halves of a weight slot) x 2 (token halves) and a
+    // wave multiplies 2 row tiles of every weight slot; 128-row class: wave w owns token rows 32w .. 32w+31
+    // (token slot w >> 1) and multiplies all 4 row tiles of every weight slot.
+    constexpr int NRT = CLS == CLS_W128 ? 4 : 2;  // row tiles of a weight slot per wave
     u32x4 fbw[WIDE ? 2 : 1][WIDE ? 8 : 1];
-    f32x4 accw[WIDE ? WNW : 1][2][2];  // [weight slot][row tile of the wave][token tile of the wave]
+    f32x4 accw[WIDE ? WNW : 1][WIDE ? NRT : 1][2];  // [weight slot][row tile of the wave][token tile of the wave]
 #pragma unroll
     for (int w = 0; w < (WIDE ? WNW : 1); ++w)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) accw[w][i >> 1][i & 1] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    const int wr = wave & 1, wt = wave >> 1;
+      for (int i = 0; i < (WIDE ? NRT : 1) * 2; ++i) accw[w][i >> 1][i & 1] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    const int wr = CLS == CLS_W128 ? 0 : (wave & 1);           // first row tile of the wave: NRT * wr
+    const int wt = CLS == CLS_W128 ? wave : (wave >> 1);       // token rows 32 wt .. 32 wt + 31 of the tile
+    const int tok_sub = CLS == CLS_W128 ? (wave >> 1) : 0;     // the token slot they arrive in
+    const int tok_row = CLS == CLS_W128 ? 32 * (wave & 1) : 32 * wt;  // their first row inside that slot
 
     while (true) {
-      wg_barrier();  // slot c_slot has landed (the loading waves waited for it)
-      if (!WIDE && pend) flush_pending();
-      if (dyn && c_first) {
-        // First step of a unit: wave 0 draws the unit after this one and waits for the answer
-        // (the multiplying waves have time to spare: they wait for the loading waves at every
-        // barrier).  Keeping the answer pending in a register instead makes the compiler guard
-        // every later use of that register with a wait for all of the wave's stores.  The loading
-        // waves ask for the unit when this unit's last slot has been issued, at least one barrier
-        // later: a unit has three slots or more and slots are issued two steps ahead.
-        if (wave == 0) {
-          int u = 0;
-          if (lane == 0) u = (int)atomicAdd(c.ctr, 1);
-          if (lane == 0) mbox[(c_n + 1) & 3] = u;
-        }
-        c_first = false;
-      }
-
-      const char *sb = smem + (size_t)(c_slot % RG) * SLOTB;
       bool tile_done = false;
       if (!WIDE) {
+        wg_barrier();  // slot c_slot has landed (the loading waves waited for it)
+        if (pend) flush_pending();
+        if (dyn && c_first) {
+          // First step of a unit: wave 0 draws the unit after this one and waits for the answer
+          // (the multiplying waves have time to spare: they wait for the loading waves at every
+          // barrier).  Keeping the answer pending in a register instead makes the compiler guard
+          // every later use of that register with a wait for all of the wave's stores.  The loading
+          // waves ask for the unit when this unit's last slot has been issued, at least one barrier
+          // later: a unit has three slots or more and slots are issued two steps ahead.
+          if (wave == 0) {
+            int u = 0;
+            if (lane == 0) u = (int)atomicAdd(c.ctr, 1);
+            if (lane == 0) mbox[(c_n + 1) & 3] = u;
+          }
+          c_first = false;
+        }
+        const char *sb = smem + (size_t)(c_slot % RG) * SLOTB;
         const int kbase = c_kb * KB;
         // waves split the 16 steps
         if (kbase + KB <= cen.klen) {  // whole block: no masks, reads issued back to back
@@ -667,17 +643,22 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
         }
         tile_done = (c_kb == cen.nkb - 1);
         ++c_kb;
+        ++c_slot;
       } else {
-        // Wave (wr, wt) multiplies token rows 32wt .. 32wt+31 by rows 32wr .. 32wr+31 of every weight
-        // slot.  The token fragments of a block stay in registers, so the token slot is free again as
-        // soon as it has been read, like every weight slot; nothing is added across waves.
+        // One block per turn of the loop: its NTS token slots, then its WNW weight slots, one barrier
+        // each (the slot has landed: the loading waves waited for it).  The token fragments of a block
+        // stay in registers, so a token slot is free again as soon as it has been read, like every
+        // weight slot; nothing is added across waves.
         const bool busy = 32 * wt < cen.m;  // (a wave without token rows only keeps the barriers)
-        if (c_sub == 0) {
-          if (busy) {
-            const int kbase = c_kb * KBW;
+        const int kbase = c_kb * KBW;
+#pragma unroll
+        for (int ts = 0; ts < NTS; ++ts) {
+          wg_barrier();
+          const char *sb = smem + (size_t)(c_slot % RG) * SLOTB;
+          if (busy && ts == tok_sub) {
 #pragma unroll
             for (int tt = 0; tt < 2; ++tt) {
-              const char *pb = sb + (size_t)(32 * wt + 16 * tt + r16) * ROW_BYTES;
+              const char *pb = sb + (size_t)(tok_row + 16 * tt + r16) * ROW_BYTES;
 #pragma unroll
               for (int st = 0; st < 8; ++st) {
                 const int piece = 4 * st + q;
@@ -687,13 +668,49 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
               }
             }
           }
-        } else if (busy) {
+          ++c_slot;
+        }
 #pragma unroll
-          for (int w = 0; w < WNW; ++w)
-            if (c_sub == w + 1) {
+        for (int w = 0; w < WNW; ++w) {
+          wg_barrier();
+          const char *sb = smem + (size_t)(c_slot % RG) * SLOTB;
+          if (busy) {
+            if constexpr (CLS == CLS_W128) {
+              // 8 chunks of (2 row tiles) x (2 steps): the fragments of the next chunks are read while this
+              // one is multiplied, and consecutive MFMAs go to 4 different accumulators.  All 8 steps of 2
+              // row tiles at once would not fit the registers beside 64 accumulator and 64 token-fragment
+              // registers.
+              constexpr int DEPTH = W128_FRAG_DEPTH;  // chunks in flight
+              u32x4 fa[DEPTH][4];  // [buffer][2 * row tile + step]
+              auto read_chunk = [&](int ch, u32x4 (&f)[4]) __attribute__((always_inline)) {
+                // chunk ch: row tiles 2 (ch >> 2), +1; steps 2 (ch & 3), +1
 #pragma unroll
-              for (int rtl = 0; rtl < 2; ++rtl) {
-                const char *pa = sb + (size_t)(16 * (2 * wr + rtl) + r16) * ROW_BYTES;
+                for (int i = 0; i < 4; ++i) {
+                  const int rt = 2 * (ch >> 2) + (i >> 1), st = 2 * (ch & 3) + (i & 1);
+                  f[i] = *reinterpret_cast<const u32x4 *>(sb + (size_t)(16 * rt + r16) * ROW_BYTES +
+                                                         (((4 * st + q) ^ r16) << 4));
+                }
+              };
+#pragma unroll
+              for (int ch = 0; ch < DEPTH - 1; ++ch) read_chunk(ch, fa[ch]);
+#pragma unroll
+              for (int ch = 0; ch < 8; ++ch) {
+                if (ch + DEPTH - 1 < 8) read_chunk(ch + DEPTH - 1, fa[(ch + DEPTH - 1) % DEPTH]);
+#pragma unroll
+                for (int si = 0; si < 2; ++si)
+#pragma unroll
+                  for (int ri = 0; ri < 2; ++ri) {
+                    const int rt = 2 * (ch >> 2) + ri, st = 2 * (ch & 3) + si;
+#pragma unroll
+                    for (int tt = 0; tt < 2; ++tt)
+                      accw[w][rt][tt] = mfma16(fa[ch % DEPTH][2 * ri + si], fbw[tt][st], accw[w][rt][tt]);
+                  }
+                __builtin_amdgcn_sched_barrier(0);  // keeps the reads DEPTH - 1 chunks ahead, not more
+              }
+            } else {
+#pragma unroll
+              for (int rtl = 0; rtl < NRT; ++rtl) {
+                const char *pa = sb + (size_t)(16 * (NRT * wr + rtl) + r16) * ROW_BYTES;
                 u32x4 fa[8];
 #pragma unroll
                 for (int st = 0; st < 8; ++st)
@@ -704,16 +721,12 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
                   for (int st = 0; st < 8; ++st) accw[w][rtl][tt] = mfma16(fa[st], fbw[tt][st], accw[w][rtl][tt]);
               }
             }
+          }
+          ++c_slot;
         }
-        if (c_sub == WNW) {
-          tile_done = (c_kb == cen.nkb - 1);
-          ++c_kb;
-          c_sub = 0;
-        } else {
-          ++c_sub;
-        }
+        tile_done = (c_kb == cen.nkb - 1);
+        ++c_kb;
       }
-      ++c_slot;
 
       if (tile_done) {
         const int id = c_id;
@@ -728,16 +741,16 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
 #pragma unroll
               for (int w = 0; w < WNW / 2; ++w)
 #pragma unroll
-                for (int rtl = 0; rtl < 2; ++rtl)
+                for (int rtl = 0; rtl < NRT; ++rtl)
                   store_out4<MODE>(cen.out, cen.out_n, (size_t)(cen.row0 + j),
-                                   i0 + 64 * w + 16 * (2 * wr + rtl) + 4 * q, WHROWS, accw[w][rtl][tt],
+                                   i0 + 64 * w + 16 * (NRT * wr + rtl) + 4 * q, WHROWS, accw[w][rtl][tt],
                                    accw[w + WNW / 2][rtl][tt]);
             }
           }
 #pragma unroll
           for (int w = 0; w < WNW; ++w)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) accw[w][i >> 1][i & 1] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            for (int i = 0; i < NRT * 2; ++i) accw[w][i >> 1][i & 1] = (f32x4){0.f, 0.f, 0.f, 0.f};
         } else {
           if (cen.nkb == 1) wg_barrier();  // the previous tile's sums may still be read from `red`
           // lane (q, r16) holds features 4q..4q+3 of token row r16: one 16-byte store per half
@@ -765,7 +778,7 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
           c_id = c.id0 + c_i * c.stride;
         }
         const int nid = c_id;
-        if (nid - cen.first >= cen.tiles || nid < cen.first) cen = load_entry<MODE, WIDE>(a, tb_, c, nid);
+        if (nid - cen.first >= cen.tiles || nid < cen.first) cen = load_entry<MODE, CLS>(a, tb_, c, nid);
       }
     }
     if (!WIDE && pend) {
@@ -789,97 +802,21 @@ __global__ __launch_bounds__(STREAM_THREADS) void expert_stream_kernel(StreamArg
   const Tables tb_{plan, offsets, row_token};
   const int G = gridDim.x, bid = blockIdx.x;
 
-  // ---- the schedule ---------------------------------------------------------------
-  // wide tiles: [shared expert's, if it has more than 16 rows][big routed entries]
-  // small tiles: [shared expert's, if it has at most 16 rows][small routed entries]
-  int n_small_e, n_big_e;
-  sload2(plan, 0, 1, n_small_e, n_big_e);
-  const bool has_shared = a.S > 0;
-  const bool shared_wide = a.T > SMALL_M && a.shared_stream;   // otherwise the tiled kernel takes it
-  const bool shared_small = a.T <= SMALL_M;
-  const int parts = (MODE == MODE_DOWN && has_shared) ? (a.S + a.part_k - 1) / a.part_k : 1;
-  ClassCfg cw, cs;
-  cw.parts = cs.parts = parts;
-  cs.per_r = (MODE == MODE_GATE_UP) ? (a.I + 15) / 16 : (a.d + 31) / 32;
-  cs.per_s = (MODE == MODE_GATE_UP) ? (a.S + 15) / 16 : (a.d + 31) / 32;
-  cw.per_r = (MODE == MODE_GATE_UP) ? (a.I + WHROWS - 1) / WHROWS : (a.d + 2 * WHROWS - 1) / (2 * WHROWS);
-  cw.per_s = (MODE == MODE_GATE_UP) ? (a.S + WHROWS - 1) / WHROWS : (a.d + 2 * WHROWS - 1) / (2 * WHROWS);
-  const int n_tb = (a.T + BIG_TB - 1) / BIG_TB;
-  cw.n_sh = (has_shared && shared_wide) ? cw.per_s * parts * n_tb : 0;
-  cs.n_sh = (has_shared && shared_small) ? cs.per_s * parts : 0;
-  const int n_wide = cw.n_sh + n_big_e * cw.per_r;
-  const int n_small = cs.n_sh + n_small_e * cs.per_r;
-  {
-    // Wide tiles are dealt round-robin; the small line is then cut so that every workgroup's
-    // estimated time is the same.  Costs in hundredths of the time of one small slot of a routed
-    // expert, from per-workgroup timelines on the MI355X: a byte of a wide slot takes as long as one
-    // of a small slot, moving from the wide to the small class drains and refills the ring (about 6
-    // slots), and a small slot whose 16 token rows are all distinct (the shared expert at T = 16)
-    // takes 1.15x as long as one with a few.
-    const int kr = (MODE == MODE_GATE_UP) ? a.d : a.I;
-    const long nkb_s = (kr + KB - 1) / KB, nkb_w = (kr + KBW - 1) / KBW;
-    const long c_wide = nkb_w * (WNW + 1) * 2 * COST_WIDE_SLOT / 3;  // a wide slot is 2/3 of a small one
-    const long c_sh = nkb_s * (100 + COST_DISTINCT_ROWS * min(a.T, SMALL_M) / SMALL_M);
-    const long c_r = nkb_s * 100;
-    const long n_shs = cs.n_sh, n_rs = n_small - cs.n_sh;
-    const long S = n_shs * c_sh + n_rs * c_r;  // the small line
-    const int k = n_wide / G, rem = n_wide % G;
-    const long sw = S > 0 ? COST_CLASS_SWITCH : 0;
-    const long C = n_wide * c_wide + (k > 0 ? G : rem) * sw + S;
-    cw.n_mine = k + (bid < rem ? 1 : 0);
-    cw.id0 = bid;
-    cw.stride = G;
-    cw.dyn = 0;
-    // what is left of a workgroup's equal share for small tiles (all quantities scaled by G)
-    const long r_hi = max(0L, C - ((k + 1) * c_wide + sw) * G);
-    const long r_lo = max(0L, C - (k * c_wide + (k > 0 ? sw : 0)) * G);
-    const long p_tot = (long)rem * r_hi + (long)(G - rem) * r_lo;
-    // A long small line is cut this way only over its first DYN_STATIC_PCT percent; the rest is
-    // drawn from a counter in units of at least three slots (a workgroup learns its next unit one
-    // unit ahead), two units' worth at a time until the last two per workgroup.  The workgroups'
-    // speeds differ by a few percent from launch to launch and between XCDs, which no fixed
-    // split can know; the ranges below then only set where each workgroup starts.
-    const int ut = (int)max(1L, (3 + nkb_s - 1) / nkb_s);
-    int n_stat = n_small;
-    cs.dyn = 0;
-    cs.n_units = cs.n_double = cs.pool0 = 0;
-    cs.ut = ut;
-    cs.n_tiles = n_small;
-    cs.ctr = const_cast<int32_t *>(plan) + PLAN_CTR + MODE;
-    if (DYN && DYN_STATIC_PCT < 100 && p_tot > 0) {
-      const int ns = (int)((long)n_small * DYN_STATIC_PCT / 100) / ut * ut;
-      const int nq = (n_small - ns) / ut;  // groups of ut tiles in the drawn part
-      if (ns >= G * ut && nq >= G && (long)n_small * nkb_s >= (long)DYN_MIN_SLOTS * G &&
-          n_small >= DYN_MIN_TILES * G) {
-        int n_single = min(nq, 2 * G);
-        if ((nq - n_single) & 1) ++n_single;
-        n_stat = ns;
-        cs.dyn = 1;
-        cs.n_double = (nq - n_single) / 2;
-        cs.n_units = cs.n_double + n_single;
-        cs.pool0 = ns;
-      }
-    }
-    const long n_shs_l = min(n_shs, (long)n_stat);
-    const long S_l = n_shs_l * c_sh + ((long)n_stat - n_shs_l) * c_r;  // the part of the line that is cut
-    // first small tile of workgroup b: the tile at cost position S_l * p(b) / p_tot of that part
-    auto first_small = [&](int b) -> int {
-      if (p_tot <= 0 || b <= 0) return 0;
-      if (b >= G) return n_stat;
-      const long pb = (long)min(b, rem) * r_hi + (long)max(0, b - rem) * r_lo;
-      const double x = (double)S_l * (double)pb / (double)p_tot;
-      const double head = (double)(n_shs_l * c_sh);
-      const double t = x <= head ? x / (double)c_sh : (double)n_shs_l + (x - head) / (double)c_r;
-      const int ti = min((int)t, n_stat);
-      return cs.dyn ? ti / ut * ut : ti;
-    };
-    const int sb0 = p_tot > 0 ? first_small(bid) : 0, sb1 = p_tot > 0 ? first_small(bid + 1) : 0;
-    cs.n_mine = sb1 - sb0;
-    cs.id0 = sb0;
-    cs.stride = 1;
-  }
-  run_class<MODE, true>(a, tb_, cw, smem);
-  run_class<MODE, false>(a, tb_, cs, smem);
+  // ---- the schedule (stream_sched.h) -------------------------------------------------
+  int n_small_e, n_b64_e, n_large_e, n_b128_e;
+  sload4(plan, 0, 1, 2, 3, n_small_e, n_b64_e, n_large_e, n_b128_e);
+  SchedIn in;
+  in.mode = MODE;
+  in.d = a.d; in.I = a.I; in.S = a.S; in.T = a.T; in.part_k = a.part_k;
+  in.shared_stream = a.shared_stream;
+  in.n_small_e = n_small_e; in.n_b64_e = n_b64_e; in.n_b128_e = n_b128_e;
+  in.G = G; in.bid = bid;
+  in.dyn_allowed = DYN ? 1 : 0;
+  StreamSched sc;
+  stream_schedule(in, const_cast<int32_t *>(plan) + PLAN_CTR + MODE, sc);
+  run_class<MODE, CLS_W128>(a, tb_, sc.c128, smem);
+  run_class<MODE, CLS_W64>(a, tb_, sc.c64, smem);
+  run_class<MODE, CLS_SMALL>(a, tb_, sc.cs, smem);
 }
 
 static hipError_t launch_stream(int mode, const StreamArgs &a, hipStream_t s) {

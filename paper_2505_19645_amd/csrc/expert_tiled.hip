@@ -622,16 +622,16 @@ static int tiled_grid_for(int n_cu) {
   return g < 32 ? 32 : (g > TILED_MAX_WGS ? TILED_MAX_WGS : g);
 }
 // Estimated microseconds either way, from measurements on the MI355X: the streaming kernels move
-// the shared expert's 3*S*d*2 bytes once per 64 tokens at about 4.8 TB/s when they share the chip
+// the shared expert's 3*S*d*2 bytes once per 128 tokens at about 4.8 TB/s when they share the chip
 // with the routed experts' wide tiles; a tiled kernel needs ceil(tiles / CUs) rounds of a tile's
 // stages, 1.5 us (gate/up) and 1.8 us (down) each, plus a fix-up launch.
 int shared_expert_streams(int T, int d, int S, int part_k, int K, int E, int n_cus) {
   if (S <= 0 || T <= PLAN_BIG_MAX_ROWS) return 1;
-  // routed experts with more than 64 rows on average keep the tiled kernels busy anyway: the shared
+  // routed experts with more than 128 rows on average keep the tiled kernels busy anyway: the shared
   // expert's tiles then fill gaps there instead of leaving the chip idle
-  if ((long)T * K > 64L * E) return 0;
+  if ((long)T * K > 128L * E) return 0;
   const double n_cu = (double)tiled_grid_for(n_cus);
-  const double stream_us = (double)((T + 63) / 64) * (3.0 * S * (double)d * 2.0) / 4.8e6;
+  const double stream_us = (double)((T + 127) / 128) * (3.0 * S * (double)d * 2.0) / 4.8e6;
   const double tb = (double)((T + TBM - 1) / TBM);
   const int parts = (S + part_k - 1) / part_k;
   const double gu_rounds = ceil(tb * ((S + 127) / 128) / n_cu), dn_rounds = ceil(tb * parts * ((d + 255) / 256) / n_cu);

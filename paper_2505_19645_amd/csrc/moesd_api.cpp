@@ -185,7 +185,7 @@ int32_t moesd_permute(int32_t E, int32_t K, int32_t T, const int32_t *topk_ids, 
   if (!counts || !offsets || !n_active) return MOESD_INVALID_ARG;
   if (T > 0 && (!topk_ids || !perm || !inv_perm)) return MOESD_INVALID_ARG;
   hipError_t e = launch_permute(topk_ids, (int64_t)T * K, E, K, counts, offsets, perm, inv_perm,
-                                n_active, nullptr, nullptr, 0x7fffffff, (hipStream_t)stream);
+                                n_active, nullptr, nullptr, 0, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e);
   return MOESD_OK;
 }
@@ -226,7 +226,7 @@ int32_t run_forward(const moesd_layer_desc *desc, const moesd_weights *wt, const
     // nothing to compute; keep the counting outputs well defined if asked for
     if (counts && offsets && n_active) {
       e = launch_permute(nullptr, 0, desc->E, desc->top_k, counts, offsets, nullptr, nullptr,
-                         n_active, nullptr, nullptr, 0x7fffffff, s);
+                         n_active, nullptr, nullptr, 0, s);
       if (e != hipSuccess) return hip_fail(e);
     }
     return MOESD_OK;
@@ -264,12 +264,12 @@ int32_t run_forward(const moesd_layer_desc *desc, const moesd_weights *wt, const
   } else {
     MOESD_TRY(launch_topk(ws.logits, T, desc->E, desc->top_k, desc->score_func, desc->renormalize,
                           desc->routed_scale, groups_of(desc), gated ? 1 : 0, ids, w, ws.gate, s))
-    // Experts with 65..128 rows join the tiled kernels' list when at least enough of them exist
-    // for about three quarters of the CUs to get a gate/up tile (128 weight rows each).
-    int tiled_min = 0x7fffffff;
-    if (T > PLAN_BIG_MAX_ROWS) tiled_min = (192 + (desc->inter + 127) / 128 - 1) / ((desc->inter + 127) / 128);
+    // the wide classes of the streaming kernels fill the chip when their tiles of the down projection
+    // (128 output rows each), the shorter of the two lists, number at least one per compute unit
+    const int wide_rt = (desc->d + 127) / 128;
+    const int wide_fill_min = T > PLAN_BIG_MAX_ROWS ? (n_cu + wide_rt - 1) / wide_rt : 0;
     MOESD_TRY(launch_permute(ids, (int64_t)T * desc->top_k, desc->E, desc->top_k, cnt, off, pm, iv, na,
-                             ws.row_token, ws.plan, tiled_min, s))
+                             ws.row_token, ws.plan, wide_fill_min, s))
   }
   MOESD_EVENT(1)
 

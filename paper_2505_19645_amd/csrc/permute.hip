@@ -27,11 +27,11 @@ __device__ __forceinline__ void permute_body(
     const int32_t *ids, int64_t n, int E, int K, int nbits, int32_t *__restrict__ counts,
     int32_t *__restrict__ offsets, int32_t *__restrict__ perm, int32_t *__restrict__ inv,
     int32_t *__restrict__ n_active, int32_t *__restrict__ row_token, int32_t *__restrict__ plan,
-    int tiled_min, int32_t *smem) {
+    int wide_fill_min, int32_t *smem) {
   int32_t *hist = smem;                     // [PERM_WAVES][E]
   int32_t *scan = smem + PERM_WAVES * E;    // [PERM_THREADS] scratch for the scan over experts
-  __shared__ int32_t wave_tot[4][PERM_WAVES];
-  __shared__ int32_t active_tot, mid_tot;
+  __shared__ int32_t wave_tot[5][PERM_WAVES];
+  __shared__ int32_t active_tot, wide_tot, large_tot;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // contiguous segment per wave, a whole number of 64-slot steps
@@ -43,7 +43,8 @@ __device__ __forceinline__ void permute_body(
   for (int i = tid; i < PERM_WAVES * E; i += PERM_THREADS) hist[i] = 0;
   if (tid == 0) {
     active_tot = 0;
-    mid_tot = 0;
+    wide_tot = 0;
+    large_tot = 0;
   }
   __syncthreads();
 
@@ -73,31 +74,37 @@ __device__ __forceinline__ void permute_body(
   }
   // exclusive scans over experts (tid == expert index): the totals give the
   // offsets; the others place each expert in the expert kernels' work lists
-  // (1..16 rows: "small"; 17..128: one "big" entry per 64-row block; more: one
-  // "large" entry per 256-row block)
-  // Experts with 65..128 rows: two passes of the streaming kernel over their weights, or one
-  // 256-row tile of the MFMA kernel that is at most half full.  The tile wins when there are
-  // enough such experts to fill the chip with tiles (tiled_min, from the host; never if the
-  // tiled kernels do not run).
+  // (1..16 rows: "small"; 17..64 and 65..128: the two wide classes of the streaming
+  // kernels; more: one "large" entry per 256-row block for the MFMA-tiled kernels)
+  // An expert with 65..128 rows streams its weights once through a 128-row wide tile, unless the wide
+  // classes together have too few tiles to fill the chip (fewer than wide_fill_min experts with 17..128
+  // rows; the streaming kernels cannot split a tile's contraction over workgroups) while the tiled
+  // kernels, which can, run anyway for some expert with more rows: then it joins their list as one
+  // half-empty 256-row block.
   const int v = (tid < E) ? total : 0;
-  const unsigned long long midb = __ballot(v > 64);
-  if (lane == 0 && midb) atomicAdd(&mid_tot, __popcll(midb));
+  const unsigned long long wideb = __ballot(v > 16 && v <= PLAN_BIG_MAX_ROWS);
+  const unsigned long long largeb = __ballot(v > PLAN_BIG_MAX_ROWS);
+  if (lane == 0 && wideb) atomicAdd(&wide_tot, __popcll(wideb));
+  if (lane == 0 && largeb) atomicAdd(&large_tot, __popcll(largeb));
   __syncthreads();
-  const int big_max = (mid_tot >= tiled_min) ? 64 : PLAN_BIG_MAX_ROWS;
+  const int b128_max = (large_tot > 0 && wide_tot < wide_fill_min) ? 64 : PLAN_BIG_MAX_ROWS;
   const int v_small = (v >= 1 && v <= 16) ? 1 : 0;
-  const int v_big = (v > 16 && v <= big_max) ? (v + 63) / 64 : 0;
-  const int v_large = (v > big_max) ? (v + 255) / 256 : 0;
-  int incl = v, incl_s = v_small, incl_b = v_big, incl_l = v_large;
+  const int v_b64 = (v > 16 && v <= 64) ? 1 : 0;
+  const int v_b128 = (v > 64 && v <= b128_max) ? 1 : 0;
+  const int v_large = (v > b128_max) ? (v + 255) / 256 : 0;
+  int incl = v, incl_s = v_small, incl_b = v_b64, incl_c = v_b128, incl_l = v_large;
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) {
     const int o = __shfl_up(incl, off, 64);
     const int os = __shfl_up(incl_s, off, 64);
     const int ob = __shfl_up(incl_b, off, 64);
+    const int oc = __shfl_up(incl_c, off, 64);
     const int ol = __shfl_up(incl_l, off, 64);
     if (lane >= off) {
       incl += o;
       incl_s += os;
       incl_b += ob;
+      incl_c += oc;
       incl_l += ol;
     }
   }
@@ -106,16 +113,18 @@ __device__ __forceinline__ void permute_body(
     wave_tot[1][wave] = incl_s;
     wave_tot[2][wave] = incl_b;
     wave_tot[3][wave] = incl_l;
+    wave_tot[4][wave] = incl_c;
   }
   const unsigned long long act = __ballot(tid < E && total > 0);
   if (lane == 0 && act) atomicAdd(&active_tot, __popcll(act));
   __syncthreads();
-  int wbase = 0, wbase_s = 0, wbase_b = 0, wbase_l = 0;
+  int wbase = 0, wbase_s = 0, wbase_b = 0, wbase_c = 0, wbase_l = 0;
   for (int w = 0; w < wave; ++w) {
     wbase += wave_tot[0][w];
     wbase_s += wave_tot[1][w];
     wbase_b += wave_tot[2][w];
     wbase_l += wave_tot[3][w];
+    wbase_c += wave_tot[4][w];
   }
   const int excl = wbase + incl - v;
   if (tid < E) {
@@ -123,11 +132,8 @@ __device__ __forceinline__ void permute_body(
     scan[tid] = excl;
     if (plan) {
       if (v_small) plan[PLAN_HDR + wbase_s + incl_s - 1] = tid;
-      const int posb = wbase_b + incl_b - v_big;
-      for (int b = 0; b < v_big; ++b) {
-        plan[PLAN_HDR + E + 2 * (posb + b)] = tid;
-        plan[PLAN_HDR + E + 2 * (posb + b) + 1] = b;
-      }
+      if (v_b64) plan[PLAN_BIG64_OFF(E) + wbase_b + incl_b - 1] = tid;
+      if (v_b128) plan[PLAN_BIG128_OFF(E) + wbase_c + incl_c - 1] = tid;
       const int pos = wbase_l + incl_l - v_large;
       for (int b = 0; b < v_large; ++b) {
         plan[PLAN_LARGE_OFF(E) + 2 * (pos + b)] = tid;
@@ -139,15 +145,17 @@ __device__ __forceinline__ void permute_body(
     offsets[E] = (int32_t)n;
     *n_active = active_tot;
     if (plan) {
-      int ns = 0, nb = 0, nl = 0;
+      int ns = 0, nb = 0, nl = 0, nc = 0;
       for (int w = 0; w < PERM_WAVES; ++w) {
         ns += wave_tot[1][w];
         nb += wave_tot[2][w];
         nl += wave_tot[3][w];
+        nc += wave_tot[4][w];
       }
       plan[0] = ns;
       plan[1] = nb;
       plan[2] = nl;
+      plan[3] = nc;
       plan[PLAN_CTR] = 0;
       plan[PLAN_CTR + 1] = 0;
     }
@@ -181,9 +189,9 @@ __global__ __launch_bounds__(PERM_THREADS) void permute_kernel(
     const int32_t *__restrict__ ids, int64_t n, int E, int K, int nbits,
     int32_t *__restrict__ counts, int32_t *__restrict__ offsets, int32_t *__restrict__ perm,
     int32_t *__restrict__ inv, int32_t *__restrict__ n_active, int32_t *__restrict__ row_token,
-    int32_t *__restrict__ plan, int tiled_min) {
+    int32_t *__restrict__ plan, int wide_fill_min) {
   extern __shared__ int32_t smem[];
-  permute_body(ids, n, E, K, nbits, counts, offsets, perm, inv, n_active, row_token, plan, tiled_min, smem);
+  permute_body(ids, n, E, K, nbits, counts, offsets, perm, inv, n_active, row_token, plan, wide_fill_min, smem);
 }
 
 // Few tokens: the same workgroup first picks every token's top-K (wave w takes
@@ -201,13 +209,13 @@ __global__ __launch_bounds__(PERM_THREADS) void topk_permute_kernel(
     topk_token<SLOTS>(logits, t, lane, E, Etot, K, score_func, renorm, scale, groups, ids, w, gate);
   __threadfence_block();
   __syncthreads();
-  permute_body(ids, (int64_t)T * K, E, K, nbits, counts, offsets, perm, inv, n_active, row_token, plan,
-               0x7fffffff, smem);  // few tokens: no expert comes near 64 rows
+  permute_body(ids, (int64_t)T * K, E, K, nbits, counts, offsets, perm, inv, n_active, row_token, plan, 0,
+               smem);  // few tokens: no expert has more than 128 rows
 }
 
 hipError_t launch_permute(const int32_t *ids, int64_t n, int E, int K, int32_t *counts,
                           int32_t *offsets, int32_t *perm, int32_t *inv, int32_t *n_active,
-                          int32_t *row_token, int32_t *plan, int tiled_min, hipStream_t s) {
+                          int32_t *row_token, int32_t *plan, int wide_fill_min, hipStream_t s) {
   int nbits = 1;
   while ((1 << nbits) < E) ++nbits;
   const size_t smem = sizeof(int32_t) * ((size_t)PERM_WAVES * E + PERM_THREADS);
@@ -220,7 +228,7 @@ hipError_t launch_permute(const int32_t *ids, int64_t n, int E, int K, int32_t *
     if (e != hipSuccess) return e;
   }
   hipLaunchKernelGGL(permute_kernel, dim3(1), dim3(PERM_THREADS), smem, s, ids, n, E, K, nbits,
-                     counts, offsets, perm, inv, n_active, row_token, plan, tiled_min);
+                     counts, offsets, perm, inv, n_active, row_token, plan, wide_fill_min);
   return hipGetLastError();
 }
 
