@@ -37,6 +37,8 @@ def lib():
         L.oracle_route.restype = C.c_int32
         L.oracle_permute.restype = C.c_int32
         L.oracle_moe_forward.restype = C.c_int32
+        L.oracle_moe_forward_fp8.restype = C.c_int32
+        L.oracle_fp8_e4m3_decode.restype = None
         L.oracle_ffn_row_f32.restype = C.c_int32
         L.oracle_ffn_row_f64.restype = C.c_int32
         L.oracle_round_bf16.restype = None
@@ -46,6 +48,26 @@ def lib():
 
 def _p(a):
     return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _u8(a):
+    if a is None:
+        return None
+    a = np.ascontiguousarray(a)
+    assert a.dtype == np.uint8, a.dtype
+    return a
+
+
+def _f32(a):
+    return None if a is None else np.ascontiguousarray(a, np.float32)
+
+
+def fp8_decode(codes):
+    """E4M3 codes (uint8, any shape) -> fp64 values (NaN for the two NaN codes)."""
+    codes = _u8(codes)
+    out = np.empty(codes.shape, np.float64)
+    lib().oracle_fp8_e4m3_decode(_p(codes), C.c_int64(codes.size), _p(out))
+    return out
 
 
 def _u16(a):
@@ -142,14 +164,18 @@ def moe_forward(shape, weights: dict, x, tokens=None):
     gate = np.ones(T, np.float64)
     b = weights.get("router_bias")
     b = None if b is None else np.ascontiguousarray(b, np.float32)
-    wt = {k: _u16(weights.get(k)) for k in ("w_router", "w_gate", "w_up", "w_down", "ws_gate",
-                                             "ws_up", "ws_down", "w_shared_gate")}
-    rc = lib().oracle_moe_forward(
-        C.byref(d), _p(x), _p(wt["w_router"]), _p(b), _p(wt["w_gate"]), _p(wt["w_up"]),
-        _p(wt["w_down"]), _p(wt["ws_gate"]), _p(wt["ws_up"]), _p(wt["ws_down"]),
-        _p(wt["w_shared_gate"]), C.c_int32(T), _p(tl), C.c_int32(n_out if tl is not None else 0),
-        _p(out), _p(outb), _p(ids), _p(w), _p(counts), _p(offsets), _p(perm), _p(inv), _p(na),
-        _p(gate))
+    mats = ("w_gate", "w_up", "w_down", "ws_gate", "ws_up", "ws_down")
+    tail = (C.c_int32(T), _p(tl), C.c_int32(n_out if tl is not None else 0), _p(out), _p(outb), _p(ids), _p(w),
+            _p(counts), _p(offsets), _p(perm), _p(inv), _p(na), _p(gate))
+    wr, wsg = _u16(weights.get("w_router")), _u16(weights.get("w_shared_gate"))
+    if weights.get("w_gate_scale") is not None:     # E4M3 codes + one fp32 scale per output row
+        args = []
+        for k in mats:
+            args += [_p(_u8(weights.get(k))), _p(_f32(weights.get(k + "_scale")))]
+        rc = lib().oracle_moe_forward_fp8(C.byref(d), _p(x), _p(wr), _p(b), *args, _p(wsg), *tail)
+    else:
+        wt = {k: _u16(weights.get(k)) for k in mats}
+        rc = lib().oracle_moe_forward(C.byref(d), _p(x), _p(wr), _p(b), *[_p(wt[k]) for k in mats], _p(wsg), *tail)
     if rc:
         raise ValueError(f"oracle_moe_forward failed: {rc}")
     return dict(out=out, out_bf16=outb, ids=ids, w=w, counts=counts, offsets=offsets, perm=perm,

@@ -32,6 +32,13 @@
  *   out[t,:]   = sum_s w[t,s] * y[inv[t*K+s],:]  +  g_t * shared(x_t)
  *   g_t        = sigmoid(x_t . w_sg) or 1
  *
+ * Low-precision expert weights (outside the paper, whose Appendix C.2 only notes that the
+ * floor of the expert-loading term scales with the weights' bit width): the expert matrices
+ * may be given as 8-bit floating-point codes, format E4M3 of the OCP OFP8 specification
+ * (1 sign, 4 exponent bits with bias 7, 3 mantissa bits, subnormals, no infinities,
+ * S.1111.111 = NaN), with one fp32 scale per output row; the weight is then
+ * decode(code) * scale[row] as a real number, and everything else is unchanged.
+ *
  * Everything is evaluated in fp64 from the bf16-valued inputs, sums run over
  * the contraction index in ascending order, and nothing is rounded in between
  * except the selection key.  Loops are parallelised with OpenMP over
@@ -42,7 +49,10 @@
  * matrix products (E=1,K=1; K=E; identical experts; expert relabelling), the
  * closed form N(t) against Monte-Carlo and against exact enumeration; the
  * group-limited rule against a sort-based restatement, a hand-made case and
- * its two degenerate settings (one group; all groups kept).
+ * its two degenerate settings (one group; all groups kept); the E4M3 decoder
+ * against a table of all 256 code points written with rational arithmetic and
+ * against a library cast, the fp8 layer against the bf16 layer on weights
+ * that both formats hold exactly (tests/test_oracle_fp8.py).
  * Absolute output values have no worked example in the paper: they are pinned
  * only through those reductions ("parity unpinned" by the paper itself).
  */
@@ -85,6 +95,29 @@ static uint16_t f64_to_bf16(double v) {
   uint32_t u;
   memcpy(&u, &f, 4);
   return (uint16_t)(u >> 16);
+}
+
+/* E4M3 code -> double, from the format's definition (OCP OFP8 specification, Sec. 5):
+ * s eeee mmm; exponent field 0: subnormal, m/8 * 2^-6; otherwise (1 + m/8) * 2^(e - 7);
+ * no infinities; exponent 15 with mantissa 7 is NaN (so the largest finite value is 448). */
+static double fp8_e4m3_to_f64(uint8_t c) {
+  const int s = c >> 7, e = (c >> 3) & 15, m = c & 7;
+  double v;
+  if (e == 15 && m == 7) return NAN;
+  if (e == 0) v = ldexp((double)m / 8.0, -6);
+  else v = ldexp(1.0 + (double)m / 8.0, e - 7);
+  return s ? -v : v;
+}
+
+void oracle_fp8_e4m3_decode(const uint8_t *codes, int64_t n, double *out) {
+  for (int64_t i = 0; i < n; ++i) out[i] = fp8_e4m3_to_f64(codes[i]);
+}
+
+/* x . (decode(code) * scale): the weight row as real numbers, then the same ascending sum */
+static double dot_bf16_fp8(const uint16_t *a, const uint8_t *codes, double scale, int64_t n) {
+  double s = 0.0;
+  for (int64_t j = 0; j < n; ++j) s += bf16_to_f64(a[j]) * (fp8_e4m3_to_f64(codes[j]) * scale);
+  return s;
 }
 
 static double dot_bf16(const uint16_t *a, const uint16_t *b, int64_t n) {
@@ -265,6 +298,54 @@ static void ffn_row(const uint16_t *xrow, const uint16_t *wg, const uint16_t *wu
   }
 }
 
+/* The same FFN with E4M3 weight codes and one scale per output row (sg, su: [I]; sd: [d]). */
+static void ffn_row_fp8(const uint16_t *xrow, const uint8_t *wg, const float *sg, const uint8_t *wu,
+                        const float *su, const uint8_t *wd, const float *sd, int d, int I, double *h,
+                        double *y) {
+#pragma omp parallel for schedule(static)
+  for (int i = 0; i < I; ++i) {
+    double g = dot_bf16_fp8(xrow, wg + (int64_t)i * d, (double)sg[i], d);
+    double u = dot_bf16_fp8(xrow, wu + (int64_t)i * d, (double)su[i], d);
+    h[i] = silu64(g) * u;
+  }
+#pragma omp parallel for schedule(static)
+  for (int cidx = 0; cidx < d; ++cidx) {
+    const uint8_t *row = wd + (int64_t)cidx * I;
+    const double sc = (double)sd[cidx];
+    double s = 0.0;
+    for (int i = 0; i < I; ++i) s += h[i] * (fp8_e4m3_to_f64(row[i]) * sc);
+    y[cidx] = s;
+  }
+}
+
+/* Expert weights of one layer in either format.  bf16: wg/wu/wd (and the shared sg/su/sd) are
+ * uint16 words and the scale pointers are NULL; fp8: they are E4M3 codes and every matrix has
+ * one fp32 scale per output row ([E, I], [E, I], [E, d]; shared [S], [S], [d]). */
+typedef struct {
+  int fp8;
+  const void *wg, *wu, *wd, *sg, *su, *sd;
+  const float *wg_s, *wu_s, *wd_s, *sg_s, *su_s, *sd_s;
+} expert_weights;
+
+static void ffn_row_any(const expert_weights *w, int shared, int e, const uint16_t *xrow, int d, int I,
+                        double *h, double *y) {
+  const int64_t gu = shared ? 0 : (int64_t)e * I * d, dn = shared ? 0 : (int64_t)e * d * I;
+  if (!w->fp8) {
+    const uint16_t *g = (const uint16_t *)(shared ? w->sg : w->wg) + gu;
+    const uint16_t *u = (const uint16_t *)(shared ? w->su : w->wu) + gu;
+    const uint16_t *dd = (const uint16_t *)(shared ? w->sd : w->wd) + dn;
+    ffn_row(xrow, g, u, dd, d, I, h, y);
+  } else {
+    const uint8_t *g = (const uint8_t *)(shared ? w->sg : w->wg) + gu;
+    const uint8_t *u = (const uint8_t *)(shared ? w->su : w->wu) + gu;
+    const uint8_t *dd = (const uint8_t *)(shared ? w->sd : w->wd) + dn;
+    const float *gs = shared ? w->sg_s : w->wg_s + (int64_t)e * I;
+    const float *us = shared ? w->su_s : w->wu_s + (int64_t)e * I;
+    const float *ds = shared ? w->sd_s : w->wd_s + (int64_t)e * d;
+    ffn_row_fp8(xrow, g, gs, u, us, dd, ds, d, I, h, y);
+  }
+}
+
 /*
  * Whole layer.  tok_list/n_list select the tokens whose output is wanted
  * (NULL / 0 = all T, in order); routing and the permutation always cover all T.
@@ -272,14 +353,12 @@ static void ffn_row(const uint16_t *xrow, const uint16_t *wg, const uint16_t *wu
  * w [T,K], counts [E], offsets [E+1], perm [T*K], inv [T*K], n_active [1],
  * gate [T] (shared-expert gate of every token).
  */
-int32_t oracle_moe_forward(const oracle_desc *c, const uint16_t *x, const uint16_t *wr,
-                           const float *bias, const uint16_t *wg, const uint16_t *wu,
-                           const uint16_t *wd, const uint16_t *sg, const uint16_t *su,
-                           const uint16_t *sd, const uint16_t *wsg, int32_t T,
-                           const int32_t *tok_list, int32_t n_list, double *out_f64,
-                           uint16_t *out_bf16, int32_t *ids_o, double *w_o, int32_t *counts_o,
-                           int32_t *offsets_o, int32_t *perm_o, int32_t *inv_o,
-                           int32_t *n_active_o, double *gate_o) {
+static int32_t forward_impl(const oracle_desc *c, const uint16_t *x, const uint16_t *wr,
+                            const float *bias, const expert_weights *ew, const uint16_t *wsg, int32_t T,
+                            const int32_t *tok_list, int32_t n_list, double *out_f64,
+                            uint16_t *out_bf16, int32_t *ids_o, double *w_o, int32_t *counts_o,
+                            int32_t *offsets_o, int32_t *perm_o, int32_t *inv_o,
+                            int32_t *n_active_o, double *gate_o) {
   const int E = c->E, K = c->top_k, d = c->d, I = c->inter, S = c->shared_inter;
   if (T < 0) return 1;
   const int64_t n = (int64_t)T * K;
@@ -308,12 +387,11 @@ int32_t oracle_moe_forward(const oracle_desc *c, const uint16_t *x, const uint16
         int e = 0;
         while (!(offsets[e] <= p && p < offsets[e + 1])) ++e; /* owner of row p */
         const int tok = perm[p] / K;                          /* == t */
-        ffn_row(x + (int64_t)tok * d, wg + (int64_t)e * I * d, wu + (int64_t)e * I * d,
-                wd + (int64_t)e * d * I, d, I, h, y + (int64_t)s * d);
+        ffn_row_any(ew, 0, e, x + (int64_t)tok * d, d, I, h, y + (int64_t)s * d);
       }
       double g = 1.0;
       if (S > 0) {
-        ffn_row(x + (int64_t)t * d, sg, su, sd, d, S, h, sh);
+        ffn_row_any(ew, 1, 0, x + (int64_t)t * d, d, S, h, sh);
         if (c->shared_gate) g = sigmoid64(dot_bf16(x + (int64_t)t * d, wsg, d));
       }
       if (gate_o) gate_o[t] = g;
@@ -337,6 +415,36 @@ int32_t oracle_moe_forward(const oracle_desc *c, const uint16_t *x, const uint16
 done:
   free(ids); free(w); free(counts); free(offsets); free(perm); free(inv);
   return rc;
+}
+
+int32_t oracle_moe_forward(const oracle_desc *c, const uint16_t *x, const uint16_t *wr,
+                           const float *bias, const uint16_t *wg, const uint16_t *wu,
+                           const uint16_t *wd, const uint16_t *sg, const uint16_t *su,
+                           const uint16_t *sd, const uint16_t *wsg, int32_t T,
+                           const int32_t *tok_list, int32_t n_list, double *out_f64,
+                           uint16_t *out_bf16, int32_t *ids_o, double *w_o, int32_t *counts_o,
+                           int32_t *offsets_o, int32_t *perm_o, int32_t *inv_o,
+                           int32_t *n_active_o, double *gate_o) {
+  expert_weights ew = {0, wg, wu, wd, sg, su, sd, NULL, NULL, NULL, NULL, NULL, NULL};
+  return forward_impl(c, x, wr, bias, &ew, wsg, T, tok_list, n_list, out_f64, out_bf16, ids_o, w_o,
+                      counts_o, offsets_o, perm_o, inv_o, n_active_o, gate_o);
+}
+
+/* The layer with E4M3 expert weights: codes [E,I,d], [E,I,d], [E,d,I] (shared [S,d], [S,d], [d,S]) and
+ * scales [E,I], [E,I], [E,d] (shared [S], [S], [d]); router and shared gate stay bf16. */
+int32_t oracle_moe_forward_fp8(const oracle_desc *c, const uint16_t *x, const uint16_t *wr,
+                               const float *bias, const uint8_t *wg, const float *wg_s,
+                               const uint8_t *wu, const float *wu_s, const uint8_t *wd,
+                               const float *wd_s, const uint8_t *sg, const float *sg_s,
+                               const uint8_t *su, const float *su_s, const uint8_t *sd,
+                               const float *sd_s, const uint16_t *wsg, int32_t T,
+                               const int32_t *tok_list, int32_t n_list, double *out_f64,
+                               uint16_t *out_bf16, int32_t *ids_o, double *w_o, int32_t *counts_o,
+                               int32_t *offsets_o, int32_t *perm_o, int32_t *inv_o,
+                               int32_t *n_active_o, double *gate_o) {
+  expert_weights ew = {1, wg, wu, wd, sg, su, sd, wg_s, wu_s, wd_s, sg_s, su_s, sd_s};
+  return forward_impl(c, x, wr, bias, &ew, wsg, T, tok_list, n_list, out_f64, out_bf16, ids_o, w_o,
+                      counts_o, offsets_o, perm_o, inv_o, n_active_o, gate_o);
 }
 
 /* The same forward with every sum carried in fp32 instead of fp64: used only

@@ -30,6 +30,8 @@ _TID = {
 
 SCORE_SOFTMAX = 0
 SCORE_SIGMOID = 1
+WEIGHTS_BF16 = 0
+WEIGHTS_FP8_E4M3 = 1
 
 
 @dataclasses.dataclass(frozen=True)
@@ -48,14 +50,23 @@ class LayerShape:
     seed: int = 0
     n_group: int = 0      # > 1: group-limited selection (E experts in n_group consecutive groups)
     topk_group: int = 0   # groups kept per token
+    weight_format: int = 0  # 0: bf16 expert weights; 1: E4M3 codes with one fp32 scale per output row
+
+    @property
+    def weight_bytes_per_element(self) -> int:
+        return 1 if self.weight_format == WEIGHTS_FP8_E4M3 else 2
 
     @property
     def expert_bytes(self) -> int:
-        return 3 * self.d * self.inter * 2
+        """Bytes of one routed expert's three matrices (and of their row scales, if any)."""
+        scales = (2 * self.inter + self.d) * 4 if self.weight_format == WEIGHTS_FP8_E4M3 else 0
+        return 3 * self.d * self.inter * self.weight_bytes_per_element + scales
 
     @property
     def shared_bytes(self) -> int:
-        return 3 * self.d * self.shared_inter * 2 + (self.d * 2 if self.shared_gate else 0)
+        scales = (2 * self.shared_inter + self.d) * 4 if (self.weight_format == WEIGHTS_FP8_E4M3 and self.shared_inter) else 0
+        return 3 * self.d * self.shared_inter * self.weight_bytes_per_element + scales \
+            + (self.d * 2 if self.shared_gate else 0)
 
     @property
     def router_bytes(self) -> int:
@@ -87,6 +98,34 @@ def f32_to_bf16_bits(a: np.ndarray) -> np.ndarray:
 def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
     """Widen bf16 words to fp32 (exact)."""
     return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+# ---- 8-bit weights: preparing the inputs (the layer itself only ever decodes) -------------------
+# E4M3 of the OCP OFP8 specification: s eeee mmm, bias 7, subnormals, no infinities, largest finite
+# value 448.  The 127 positive finite values in code order:
+_E4M3_POS = np.array([(m / 8.0) * 2.0 ** -6 if e == 0 else (1.0 + m / 8.0) * 2.0 ** (e - 7)
+                      for e in range(16) for m in range(8)][:127], dtype=np.float64)
+E4M3_MAX = 448.0
+
+
+def encode_e4m3(a: np.ndarray) -> np.ndarray:
+    """Nearest E4M3 code of each value (ties to the even code, magnitudes above 448 saturate)."""
+    a = np.asarray(a, dtype=np.float64)
+    mag = np.minimum(np.abs(a), E4M3_MAX)
+    hi = np.searchsorted(_E4M3_POS, mag, side="left").clip(1, 126)
+    lo = hi - 1
+    dlo, dhi = mag - _E4M3_POS[lo], _E4M3_POS[hi] - mag
+    code = np.where((dhi < dlo) | ((dhi == dlo) & (hi % 2 == 0)), hi, lo).astype(np.uint8)
+    return code | (np.signbit(a).astype(np.uint8) << 7)
+
+
+def quantize_rows_e4m3(w_bits: np.ndarray):
+    """bf16 words [..., rows, cols] -> (E4M3 codes, fp32 scales [..., rows]): each row is divided by
+    max|row| / 448 (rounded to fp32) and rounded to the nearest code."""
+    w = bf16_bits_to_f32(w_bits).astype(np.float64)
+    amax = np.abs(w).max(axis=-1)
+    scale = np.where(amax > 0, amax / E4M3_MAX, 1.0).astype(np.float32)
+    return encode_e4m3(w / scale[..., None].astype(np.float64)), scale
 
 
 def _rng(seed: int, tensor: str, block: int) -> np.random.Generator:
@@ -149,18 +188,33 @@ def make_shared(shape: LayerShape) -> dict:
 def make_layer(shape: LayerShape, skew_std: float = 0.0, threads: int = 8) -> dict:
     """All weights of one layer as numpy arrays of bf16 words (bias: fp32).
     Expert tensors are filled one expert per task so the host cores share the
-    work; the result does not depend on `threads`."""
+    work; the result does not depend on `threads`.  With shape.weight_format ==
+    WEIGHTS_FP8_E4M3 the expert matrices (routed and shared) are the same Gaussian
+    draws quantised row by row: uint8 codes under the same keys plus fp32 scales
+    under "<key>_scale"."""
     d, E, I = shape.d, shape.E, shape.inter
+    fp8 = shape.weight_format == WEIGHTS_FP8_E4M3
     w = {}
     w.update(make_router(shape, skew_std))
     w.update(make_shared(shape))
-    w["w_gate"] = np.empty((E, I, d), dtype=np.uint16)
-    w["w_up"] = np.empty((E, I, d), dtype=np.uint16)
-    w["w_down"] = np.empty((E, d, I), dtype=np.uint16)
+    wdt = np.uint8 if fp8 else np.uint16
+    w["w_gate"] = np.empty((E, I, d), dtype=wdt)
+    w["w_up"] = np.empty((E, I, d), dtype=wdt)
+    w["w_down"] = np.empty((E, d, I), dtype=wdt)
+    if fp8:
+        w["w_gate_scale"] = np.empty((E, I), dtype=np.float32)
+        w["w_up_scale"] = np.empty((E, I), dtype=np.float32)
+        w["w_down_scale"] = np.empty((E, d), dtype=np.float32)
+        for k in ("ws_gate", "ws_up", "ws_down"):
+            if w[k] is not None:
+                w[k], w[k + "_scale"] = quantize_rows_e4m3(w[k])
 
     def fill(job):
         name, e = job
-        w[name][e] = expert_block(shape, name, e)
+        if fp8:
+            w[name][e], w[name + "_scale"][e] = quantize_rows_e4m3(expert_block(shape, name, e))
+        else:
+            w[name][e] = expert_block(shape, name, e)
 
     jobs = [(n, e) for e in range(E) for n in ("w_gate", "w_up", "w_down")]
     if threads > 1 and len(jobs) > 1:
