@@ -76,8 +76,10 @@ class Runner:
         for k, v in host_w.items():
             if v is None:
                 base[k] = None
-            elif k == "router_bias":
+            elif k == "router_bias" or k.endswith("_scale"):
                 base[k] = torch.from_numpy(v.astype(np.float32)).to(dev)
+            elif v.dtype == np.uint8:                      # E4M3 codes
+                base[k] = torch.from_numpy(np.ascontiguousarray(v)).to(dev)
             else:
                 base[k] = torch.from_numpy(np.ascontiguousarray(v).view(np.int16)).to(dev)
         self.reps = [base]

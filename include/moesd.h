@@ -64,6 +64,16 @@ extern "C" {
 #define MOESD_SCORE_SOFTMAX 0
 #define MOESD_SCORE_SIGMOID 1
 
+/* expert weight formats (routed and shared expert matrices; the router stays bf16) */
+#define MOESD_WEIGHTS_BF16     0
+#define MOESD_WEIGHTS_FP8_E4M3 1  /* 8-bit codes, E4M3 of the OCP OFP8 specification (1 sign, 4 exponent
+                                     bits with bias 7, 3 mantissa bits, subnormals, no infinities,
+                                     S.1111.111 = NaN, largest finite value 448), one fp32 scale per
+                                     output row: weight = decode(code) * scale[row].  Halves the bytes of
+                                     the expert-loading term k2*N of Sec. 3.3, whose floor scales with the
+                                     weights' bit width (Appendix C.2).  Codes are assumed finite.  d,
+                                     inter and shared_inter must be multiples of 16. */
+
 /* One MoE layer's shape, in the paper's notation (Sec. 3.2: E experts, K per
  * token; rho = K/E).  The arithmetic choices below are not in the paper, which
  * never spells the layer out; they follow the usual SwiGLU MoE block. */
@@ -79,9 +89,12 @@ typedef struct {
   float   routed_scale; /* multiplies every routed weight (1.0 = none)           */
   int32_t n_group;      /* > 1: group-limited selection, see moesd_route; else off */
   int32_t topk_group;   /* groups kept per token (1 .. n_group)                    */
+  int32_t weight_format; /* MOESD_WEIGHTS_BF16 or MOESD_WEIGHTS_FP8_E4M3           */
 } moesd_layer_desc;
 
-/* All weights: device pointers, bf16, read-only, caller-owned. */
+/* All weights: device pointers, read-only, caller-owned.  Router, bias and shared gate as stated;
+ * the six expert matrices are bf16, or uint8 E4M3 codes with the same shapes when
+ * desc->weight_format == MOESD_WEIGHTS_FP8_E4M3; then each has an fp32 scale per output row. */
 typedef struct {
   const void  *w_router;      /* [E, d]                                          */
   const float *router_bias;   /* [E] fp32, added to the logits; may be NULL      */
@@ -92,6 +105,13 @@ typedef struct {
   const void  *ws_up;         /* [S, d]                                          */
   const void  *ws_down;       /* [d, S]                                          */
   const void  *w_shared_gate; /* [d]      (NULL iff shared_gate == 0)            */
+  /* row scales, fp32; NULL unless the weights are MOESD_WEIGHTS_FP8_E4M3 */
+  const float *w_gate_scale;  /* [E, I]                                          */
+  const float *w_up_scale;    /* [E, I]                                          */
+  const float *w_down_scale;  /* [E, d]                                          */
+  const float *ws_gate_scale; /* [S]                                             */
+  const float *ws_up_scale;   /* [S]                                             */
+  const float *ws_down_scale; /* [d]                                             */
 } moesd_weights;
 
 /* ---------------------------------------------------------------------------
@@ -127,8 +147,8 @@ int64_t moesd_token_threshold(int32_t E, int32_t K, double tau);
  * T_max tokens (256-byte aligned pieces; the caller's buffer must itself be
  * 256-byte aligned).  Besides the per-token buffers (logits, routing outputs,
  * the bf16 activation [T*K, I] and the fp32 expert outputs [T*K, d]) it holds,
- * for T_max > 128, 128 MB of partial-sum space for the MFMA-tiled expert kernels
- * (512 KB for each of at most 256 persistent workgroups).  The size depends on
+ * for T_max > 128 (E4M3 weights: T_max > 16), 128 MB of partial-sum space for the
+ * MFMA-tiled expert kernels (512 KB for each of at most 256 persistent workgroups).  The size depends on
  * the arguments only, not on the device.  Returns 0 if the descriptor or T_max
  * is invalid. */
 size_t moesd_workspace_bytes(const moesd_layer_desc *desc, int32_t T_max);
@@ -180,7 +200,8 @@ int32_t moesd_permute(int32_t E, int32_t K, int32_t T, const int32_t *topk_ids,
  *   out[t,:] = sum_s w[t,s] * FFN_{ids[t,s]}(x_t)  +  g_t * FFN_shared(x_t)
  *   FFN_e(x) = W_down_e . ( silu(W_gate_e . x) * (W_up_e . x) )
  * bf16 operands, fp32 accumulation, the intermediate activation is rounded to
- * bf16 once, the output is rounded to bf16 once.
+ * bf16 once, the output is rounded to bf16 once.  E4M3 weights are widened to bf16
+ * (exactly) for the multiplication and the row scale is applied to the fp32 sum.
  *   x    device [T, d] bf16;   out  device [T, d] bf16
  *   out_f32   device [T, d] fp32 or NULL: the same result before rounding
  *   topk_ids .. n_active: optional device outputs (any may be NULL), shaped as

@@ -26,12 +26,14 @@ class LayerDesc(C.Structure):
     _fields_ = [("d", C.c_int32), ("E", C.c_int32), ("top_k", C.c_int32), ("inter", C.c_int32),
                 ("shared_inter", C.c_int32), ("score_func", C.c_int32), ("renormalize", C.c_int32),
                 ("shared_gate", C.c_int32), ("routed_scale", C.c_float), ("n_group", C.c_int32),
-                ("topk_group", C.c_int32)]
+                ("topk_group", C.c_int32), ("weight_format", C.c_int32)]
 
 
 class Weights(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("w_router", "router_bias", "w_gate", "w_up", "w_down",
-                                          "ws_gate", "ws_up", "ws_down", "w_shared_gate")]
+                                          "ws_gate", "ws_up", "ws_down", "w_shared_gate",
+                                          "w_gate_scale", "w_up_scale", "w_down_scale",
+                                          "ws_gate_scale", "ws_up_scale", "ws_down_scale")]
 
 
 class MoesdError(RuntimeError):
@@ -99,7 +101,7 @@ def make_desc(shape) -> LayerDesc:
     return LayerDesc(shape.d, shape.E, shape.top_k, shape.inter, shape.shared_inter,
                      shape.score_func, shape.renormalize, shape.shared_gate,
                      float(shape.routed_scale), int(getattr(shape, "n_group", 0)),
-                     int(getattr(shape, "topk_group", 0)))
+                     int(getattr(shape, "topk_group", 0)), int(getattr(shape, "weight_format", 0)))
 
 
 def _ptr(t):

@@ -67,10 +67,13 @@ __device__ __forceinline__ float silu_f32(float z) {
 #define PLAN_WORDS(E, TK) (PLAN_LARGE_OFF(E) + 2 * ((E) + (TK) / 256 + 2))
 
 struct StreamArgs {
-  // routed experts
-  const uint16_t *w_gate, *w_up, *w_down;     // [E,I,d] [E,I,d] [E,d,I]
+  // routed experts: bf16 words, or (fp8 != 0) E4M3 bytes with one fp32 scale per output row
+  const void *w_gate, *w_up, *w_down;         // [E,I,d] [E,I,d] [E,d,I]
   // shared expert
-  const uint16_t *ws_gate, *ws_up, *ws_down;  // [S,d] [S,d] [d,S]
+  const void *ws_gate, *ws_up, *ws_down;      // [S,d] [S,d] [d,S]
+  const float *s_gate, *s_up, *s_down;        // [E,I] [E,I] [E,d] row scales (fp8 only)
+  const float *ss_gate, *ss_up, *ss_down;     // [S] [S] [d]
+  int32_t fp8;
   const uint16_t *x;                          // [T,d]
   uint16_t *h;                                // [T*K, I] bf16
   uint16_t *hs;                               // [T, S]   bf16
@@ -106,7 +109,9 @@ hipError_t launch_topk(const double *logits, int T, int E, int K, int score_func
                        float *gate, hipStream_t s);
 // row_token / plan may be NULL (standalone permutation).  wide_fill_min: experts with 65..128 rows
 // go to the tiled kernels' list if some expert has more than 128 rows and fewer than that many
-// experts have 17..128 rows (0: never).
+// experts have 17..128 rows (0: never; -1: there are no wide classes, every expert with more than
+// 16 rows goes to the tiled kernels' list).
+#define PLAN_NO_WIDE (-1)
 hipError_t launch_permute(const int32_t *ids, int64_t n, int E, int K, int32_t *counts,
                           int32_t *offsets, int32_t *perm, int32_t *inv, int32_t *n_active,
                           int32_t *row_token, int32_t *plan, int wide_fill_min, hipStream_t s);
@@ -114,7 +119,8 @@ hipError_t launch_permute(const int32_t *ids, int64_t n, int E, int K, int32_t *
 hipError_t launch_topk_permute(const double *logits, int T, int E, int K, int score_func, int renorm,
                                float scale, int groups, int has_shared_gate, int32_t *ids, float *w,
                                float *gate, int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv,
-                               int32_t *n_active, int32_t *row_token, int32_t *plan, hipStream_t s);
+                               int32_t *n_active, int32_t *row_token, int32_t *plan, int wide_fill_min,
+                               hipStream_t s);
 hipError_t launch_gate_up(const StreamArgs &a, hipStream_t s);
 hipError_t launch_down(const StreamArgs &a, hipStream_t s);
 // The tiled kernels are persistent and cut the work into equal shares; a tile cut by a

@@ -152,51 +152,56 @@ struct Tables {
 
 // One (group, token block): everything that is constant over its row tiles.
 struct Entry {
-  const uint16_t *a0, *a1;  // row 0 of the two operand halves at this entry's k origin
-  long a_stride;
+  const char *a0, *a1;      // row 0 of the two operand halves at this entry's k origin (bytes)
+  long a_stride;            // bytes per weight row
   int n_rows;               // rows of the weight matrix (for clamping the last tile)
   const uint16_t *b;        // token-row matrix at this entry's k origin
   long b_stride;
   bool use_map;             // token rows go through row_token
-  int row0, m;              // first token row, number of token rows (1..64)
+  int row0, m;              // first token row, number of token rows (1..128)
   int klen, nkb;            // contraction length, blocks (of KB or KBW)
   void *out;
   int out_n;
   int tiles;                // row tiles in this entry
   int first;                // id (in its class) of this entry's row tile 0
+  const float *s0, *s1;     // 8-bit weights: the row scales of the two operand halves
 };
 
-template <int MODE>
+template <int MODE, bool FP8>
 __device__ __forceinline__ void fill_group(Entry &en, const StreamArgs &a, bool shared, int e, int part) {
+  constexpr long esz = FP8 ? 1 : 2;  // bytes per weight
   if (shared) {
     en.use_map = false;
     if (MODE == MODE_GATE_UP) {
-      en.a0 = a.ws_gate;
-      en.a1 = a.ws_up;
-      en.a_stride = a.d;
+      en.a0 = reinterpret_cast<const char *>(a.ws_gate);
+      en.a1 = reinterpret_cast<const char *>(a.ws_up);
+      en.a_stride = a.d * esz;
       en.n_rows = a.S;
       en.b = a.x;
       en.b_stride = a.d;
       en.klen = a.d;
       en.out = a.hs;
       en.out_n = a.S;
+      en.s0 = a.ss_gate;
+      en.s1 = a.ss_up;
     } else {
       const int k0 = part * a.part_k;
-      en.a0 = a.ws_down + k0;
+      en.a0 = reinterpret_cast<const char *>(a.ws_down) + k0 * esz;
       en.a1 = en.a0;
-      en.a_stride = a.S;
+      en.a_stride = a.S * esz;
       en.n_rows = a.d;
       en.b = a.hs + k0;
       en.b_stride = a.S;
       en.klen = min(a.part_k, a.S - k0);
       en.out = a.ys + (size_t)part * a.T * a.d;
       en.out_n = a.d;
+      en.s0 = en.s1 = a.ss_down;
     }
   } else {
     if (MODE == MODE_GATE_UP) {
-      en.a0 = a.w_gate + (size_t)e * a.I * a.d;
-      en.a1 = a.w_up + (size_t)e * a.I * a.d;
-      en.a_stride = a.d;
+      en.a0 = reinterpret_cast<const char *>(a.w_gate) + (size_t)e * a.I * a.d * esz;
+      en.a1 = reinterpret_cast<const char *>(a.w_up) + (size_t)e * a.I * a.d * esz;
+      en.a_stride = a.d * esz;
       en.n_rows = a.I;
       en.b = a.x;
       en.b_stride = a.d;
@@ -204,10 +209,12 @@ __device__ __forceinline__ void fill_group(Entry &en, const StreamArgs &a, bool 
       en.klen = a.d;
       en.out = a.h;
       en.out_n = a.I;
+      en.s0 = a.s_gate + (size_t)e * a.I;
+      en.s1 = a.s_up + (size_t)e * a.I;
     } else {
-      en.a0 = a.w_down + (size_t)e * a.d * a.I;
+      en.a0 = reinterpret_cast<const char *>(a.w_down) + (size_t)e * a.d * a.I * esz;
       en.a1 = en.a0;
-      en.a_stride = a.I;
+      en.a_stride = a.I * esz;
       en.n_rows = a.d;
       en.b = a.h;
       en.b_stride = a.I;
@@ -215,12 +222,13 @@ __device__ __forceinline__ void fill_group(Entry &en, const StreamArgs &a, bool 
       en.klen = a.I;
       en.out = a.y;
       en.out_n = a.d;
+      en.s0 = en.s1 = a.s_down + (size_t)e * a.d;
     }
   }
 }
 
 // entry that owns tile `id` of the class
-template <int MODE, int CLS>
+template <int MODE, int CLS, bool FP8>
 __device__ __forceinline__ Entry load_entry(const StreamArgs &a, const Tables &tb_, const ClassCfg &c,
                                             int id) {
   Entry en;
@@ -235,7 +243,7 @@ __device__ __forceinline__ Entry load_entry(const StreamArgs &a, const Tables &t
     en.m = min(a.T - en.row0, rows);
     en.tiles = per;
     en.first = blk * per;
-    fill_group<MODE>(en, a, true, 0, part);
+    fill_group<MODE, FP8>(en, a, true, 0, part);
   } else {
     const int per = c.per_r;
     const int entry = (id - c.n_sh) / per;
@@ -248,17 +256,17 @@ __device__ __forceinline__ Entry load_entry(const StreamArgs &a, const Tables &t
     en.m = min(end - beg, rows);
     en.tiles = per;
     en.first = c.n_sh + entry * per;
-    fill_group<MODE>(en, a, false, e, 0);
+    fill_group<MODE, FP8>(en, a, false, e, 0);
   }
   en.nkb = WIDE ? (en.klen + KBW - 1) / KBW : (en.klen + KB - 1) / KB;
   return en;
 }
 
-// first weight row of row tile rt
-template <int MODE, bool WIDE>
+// first weight row of row tile rt (small tiles: 16 + 16 or 32 rows of bf16, 32 + 32 or 64 rows of 8-bit codes)
+template <int MODE, bool WIDE, bool FP8>
 __device__ __forceinline__ int tile_i0(int rt) {
-  if (MODE == MODE_GATE_UP) return WIDE ? rt * WHROWS : rt * 16;
-  return WIDE ? rt * 2 * WHROWS : rt * 32;
+  if (MODE == MODE_GATE_UP) return WIDE ? rt * WHROWS : rt * (FP8 ? 32 : 16);
+  return WIDE ? rt * 2 * WHROWS : rt * (FP8 ? 64 : 32);
 }
 
 // Per-lane source pointers of the DMA instructions this wave issues.
@@ -267,7 +275,7 @@ __device__ __forceinline__ int tile_i0(int rt) {
 //          slot is issued (i0: the tile's first weight row)
 template <int CLS>
 struct LoadPtrs {
-  const uint16_t *a[ClsGeo<CLS>::WIDE ? 1 : 8];
+  const char *a[ClsGeo<CLS>::WIDE ? 1 : 8];
   const uint16_t *b[ClsGeo<CLS>::WIDE ? 8 * ClsGeo<CLS>::NTS : 4];
   int i0;
 };
@@ -307,11 +315,11 @@ __device__ __forceinline__ void setup_b(LoadPtrs<CLS> &lp, const Entry &en,
   }
 }
 
-template <int MODE, int CLS>
+template <int MODE, int CLS, bool FP8>
 __device__ __forceinline__ void setup_a(LoadPtrs<CLS> &lp, const Entry &en, int rt, int wave, int lane) {
   constexpr bool WIDE = ClsGeo<CLS>::WIDE;
-  const int i0 = tile_i0<MODE, WIDE>(rt);
-  if (!WIDE) {
+  const int i0 = tile_i0<MODE, WIDE, FP8>(rt);
+  if (!WIDE && !FP8) {
     // valid rows in each 16-row half of this tile (at least 1 after clamping)
     const int rv0 = min(16, en.n_rows - i0);
     const int rv1 = (MODE == MODE_GATE_UP) ? rv0 : max(1, min(16, en.n_rows - i0 - 16));
@@ -320,9 +328,22 @@ __device__ __forceinline__ void setup_a(LoadPtrs<CLS> &lp, const Entry &en, int 
     for (int i = 0; i < 8; ++i) {
       const int j = wave * 8 + i;  // 0..31: half = j >> 4, row = j & 15
       const int r = j & 15;
-      const uint16_t *base = (j >> 4) ? en.a1 : en.a0;
+      const char *base = (j >> 4) ? en.a1 : en.a0;
       const int row = (j >> 4) ? i0 + off1 + min(r, rv1 - 1) : i0 + min(r, rv0 - 1);
-      lp.a[i] = base + (size_t)row * en.a_stride + ((lane ^ r) << 3);
+      lp.a[i] = base + (size_t)row * en.a_stride + ((lane ^ r) << 4);
+    }
+  } else if (!WIDE) {
+    // 8-bit codes: 64 slot rows of 512 bytes, two per instruction (lanes 0..31 row 2p, lanes 32..63 row
+    // 2p + 1).  gate/up: slot rows 0..31 are w_gate rows i0.., slot rows 32..63 the same rows of w_up;
+    // down: 64 consecutive rows.
+    const int half = lane >> 5, pos = lane & 31;
+    const int rv = min((MODE == MODE_GATE_UP) ? 32 : 64, en.n_rows - i0);  // valid rows (at least 1)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int r = 2 * (wave * 8 + i) + half;  // slot row 0..63
+      const bool second = (MODE == MODE_GATE_UP) && r >= 32;
+      const int row = i0 + min(second ? r - 32 : r, rv - 1);
+      lp.a[i] = (second ? en.a1 : en.a0) + (size_t)row * en.a_stride + ((pos ^ (r & 15)) << 4);
     }
   } else {
     lp.i0 = i0;
@@ -331,7 +352,7 @@ __device__ __forceinline__ void setup_a(LoadPtrs<CLS> &lp, const Entry &en, int 
 
 // Issue one slot: exactly LW loads per wave.  Pieces past the end of a row are
 // pulled back inside it; their products are masked in the MFMA loop.
-template <int MODE, int CLS>
+template <int MODE, int CLS, bool FP8>
 __device__ __forceinline__ void issue_slot(const LoadPtrs<CLS> &lp, const Entry &en, int kb, int sub,
                                            uint32_t slot_base, int wave, int lane) {
   constexpr bool WIDE = ClsGeo<CLS>::WIDE;
@@ -345,10 +366,22 @@ __device__ __forceinline__ void issue_slot(const LoadPtrs<CLS> &lp, const Entry 
       const int piece = lane ^ (r & 15);
       return min(k0 + piece * 8, klen - 8) - piece * 8;
     };
+    if (!FP8) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int j = wave * 8 + i;
-      dma16_stream(lp.a[i] + koff(j & 15), slot_base + (uint32_t)j * 1024u);
+      for (int i = 0; i < 8; ++i) {
+        const int j = wave * 8 + i;
+        dma16_stream(lp.a[i] + 2 * koff(j & 15), slot_base + (uint32_t)j * 1024u);
+      }
+    } else {
+      // 16-byte pieces of 16 codes; a piece past the end of the row is pulled back inside it
+      const int pos = lane & 31, half = lane >> 5;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int pair = wave * 8 + i;
+        const int piece = pos ^ ((2 * pair + half) & 15);
+        const int ko = full ? k0 : min(k0 + piece * 16, klen - 16) - piece * 16;
+        dma16_stream(lp.a[i] + ko, slot_base + (uint32_t)pair * 1024u);
+      }
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -381,7 +414,7 @@ __device__ __forceinline__ void issue_slot(const LoadPtrs<CLS> &lp, const Entry 
       }
     } else {
       const int w = sub - NTS;
-      const uint16_t *base = (MODE == MODE_GATE_UP && w >= WNW / 2) ? en.a1 : en.a0;
+      const char *base = (MODE == MODE_GATE_UP && w >= WNW / 2) ? en.a1 : en.a0;
       const int first = (MODE == MODE_GATE_UP) ? 64 * (w % (WNW / 2)) : 64 * w;  // of the tile's rows in this matrix
       const int rv = min((MODE == MODE_GATE_UP) ? WHROWS : 2 * WHROWS, en.n_rows - lp.i0);  // valid ones
 #pragma unroll
@@ -389,7 +422,7 @@ __device__ __forceinline__ void issue_slot(const LoadPtrs<CLS> &lp, const Entry 
         const int pair = wave * 8 + i;
         const int r = 2 * pair + half;
         const int row = lp.i0 + min(first + r, rv - 1);
-        dma16_stream(base + (size_t)row * en.a_stride + (((pos ^ (r & 15)) << 3) + koff(r)),
+        dma16_stream(base + (size_t)row * en.a_stride + 2 * (((pos ^ (r & 15)) << 3) + koff(r)),
                      slot_base + (uint32_t)pair * 1024u);
       }
     }
@@ -434,7 +467,7 @@ __device__ __forceinline__ void store_out4(void *out, int out_n, size_t orow, in
 }
 
 // All tiles of one class for this workgroup: the software pipeline.
-template <int MODE, int CLS>
+template <int MODE, int CLS, bool FP8>
 __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_, const ClassCfg &c,
                                           char *smem) {
   constexpr bool WIDE = ClsGeo<CLS>::WIDE;
@@ -476,18 +509,18 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
     int l_sub = 0;  // wide: 0 .. NTS-1 token slots, then the WNW weight slots
     int l_id = dyn ? first_t0 : c.id0, l_end = first_t1, l_n = 0;  // (dyn: tile, end of its unit, unit number)
     bool l_need = false;  // dyn: the unit is used up, the next one is fetched when its first slot is due
-    Entry len = load_entry<MODE, CLS>(a, tb_, c, l_id);
+    Entry len = load_entry<MODE, CLS, FP8>(a, tb_, c, l_id);
     LoadPtrs<CLS> lp;
     setup_b<MODE, CLS>(lp, len, tb_.row_token, lw, lane);
-    setup_a<MODE, CLS>(lp, len, l_id - len.first, lw, lane);
+    setup_a<MODE, CLS, FP8>(lp, len, l_id - len.first, lw, lane);
     bool l_live = true;
 
     auto open_tile = [&](int id) __attribute__((always_inline)) {
       if (id - len.first >= len.tiles || id < len.first) {
-        len = load_entry<MODE, CLS>(a, tb_, c, id);
+        len = load_entry<MODE, CLS, FP8>(a, tb_, c, id);
         setup_b<MODE, CLS>(lp, len, tb_.row_token, lw, lane);
       }
-      setup_a<MODE, CLS>(lp, len, id - len.first, lw, lane);
+      setup_a<MODE, CLS, FP8>(lp, len, id - len.first, lw, lane);
     };
     auto advance_load = [&]() __attribute__((always_inline)) {
       if (dyn && l_need) {
@@ -502,7 +535,7 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
         l_need = false;
         open_tile(l_id);
       }
-      issue_slot<MODE, CLS>(lp, len, l_kb, l_sub, lds0 + (uint32_t)(l_slot % RG) * SLOTB, lw, lane);
+      issue_slot<MODE, CLS, FP8>(lp, len, l_kb, l_sub, lds0 + (uint32_t)(l_slot % RG) * SLOTB, lw, lane);
       // a tile of one slot: the multiplying waves put one more barrier into that slot's step
       if (!WIDE) single = (single & ~(1ull << (l_slot & 63))) | ((unsigned long long)(len.nkb == 1) << (l_slot & 63));
       ++l_slot;
@@ -546,7 +579,7 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
     int c_i = 0, c_kb = 0, c_slot = 0;
     int c_id = dyn ? first_t0 : c.id0, c_end = first_t1, c_n = 0;
     bool c_first = dyn;  // dyn: this is the first step of a unit
-    Entry cen = load_entry<MODE, CLS>(a, tb_, c, c_id);
+    Entry cen = load_entry<MODE, CLS, FP8>(a, tb_, c, c_id);
     f32x4 acc0[NACC], acc1[NACC];
 #pragma unroll
     for (int nt = 0; nt < NACC; ++nt) {
@@ -557,18 +590,36 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
     bool pend = false;
     int pend_m = 0, pend_row0 = 0, pend_i0 = 0, pend_n = 0;
     void *pend_out = nullptr;
+    const float *pend_s0 = nullptr, *pend_s1 = nullptr;  // (8-bit weights: its row scales)
 
     // After a barrier: add the waves' partial tiles.  Thread t takes token row t >> 4 and feature
     // t & 15 (of both halves), so 16 neighbouring lanes store 16 neighbouring features of a row.
     auto flush_pending = [&]() __attribute__((always_inline)) {
       const int j = tid >> 4, fi = tid & 15;
-      float s0 = 0.f, s1 = 0.f;
+      if (!FP8) {
+        float s0 = 0.f, s1 = 0.f;
 #pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        s0 += red[(w * 2 + 0) * RED_TILE + j * RED_ROW + fi];
-        s1 += red[(w * 2 + 1) * RED_TILE + j * RED_ROW + fi];
+        for (int w = 0; w < 4; ++w) {
+          s0 += red[(w * 2 + 0) * RED_TILE + j * RED_ROW + fi];
+          s1 += red[(w * 2 + 1) * RED_TILE + j * RED_ROW + fi];
+        }
+        if (j < pend_m) store_out<MODE>(pend_out, pend_n, (size_t)(pend_row0 + j), pend_i0 + fi, 16, s0, s1);
+      } else {
+        // 8-bit weights: wave (h, kh) left the sums of rows 16h.. (tile 0) and 32 + 16h.. (tile 1) over
+        // its half kh of the block's contraction; each sum is scaled by its weight row's scale
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+          const int i = pend_i0 + 16 * hh + fi;  // feature (gate/up) or first of the two output rows (down)
+          const int i1 = (MODE == MODE_GATE_UP) ? i : i + 32;
+          const float c0 = (j < pend_m && i < pend_n) ? pend_s0[i] : 0.f;
+          const float c1 = (j < pend_m && i1 < pend_n) ? pend_s1[i1] : 0.f;
+          const float s0 = red[(0 * 4 + hh * 2 + 0) * RED_TILE + j * RED_ROW + fi] +
+                           red[(1 * 4 + hh * 2 + 0) * RED_TILE + j * RED_ROW + fi];
+          const float s1 = red[(0 * 4 + hh * 2 + 1) * RED_TILE + j * RED_ROW + fi] +
+                           red[(1 * 4 + hh * 2 + 1) * RED_TILE + j * RED_ROW + fi];
+          if (j < pend_m) store_out<MODE>(pend_out, pend_n, (size_t)(pend_row0 + j), i, 32, s0 * c0, s1 * c1);
+        }
       }
-      if (j < pend_m) store_out<MODE>(pend_out, pend_n, (size_t)(pend_row0 + j), pend_i0 + fi, 16, s0, s1);
       pend = false;
     };
 
@@ -609,6 +660,54 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
         }
         const char *sb = smem + (size_t)(c_slot % RG) * SLOTB;
         const int kbase = c_kb * KB;
+        if constexpr (FP8) {
+          // 64 rows of 8-bit codes per slot.  Wave (h, kh) = (wave & 1, wave >> 1) multiplies slot rows
+          // 16h .. 16h+15 and 32 + 16h .. (the same rows of w_gate and w_up, or two groups of w_down rows)
+          // over the half kh of the block's 512 contraction elements: 4 chunks of 64.  In a chunk lane
+          // (r, q) holds the 16 codes k = 16q .. 16q+15 of its row: two MFMA operands after widening to
+          // bf16 (exact), matched by the token pieces 2q and 2q + 1 of the chunk.
+          const int h = wave & 1, kh = wave >> 1;
+          const char *pa0 = sb + (size_t)(16 * h + r16) * 512;
+          const char *pa1 = sb + (size_t)(32 + 16 * h + r16) * 512;
+          const char *pb = sb + A_BYTES + (size_t)r16 * SROW_BYTES;
+          auto widen = [&](u32x4 codes, u32x4 &lo, u32x4 &hi) __attribute__((always_inline)) {
+#pragma unroll
+            for (int dw = 0; dw < 2; ++dw) {
+              lo[2 * dw] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(codes[dw], 1.0f, false));
+              lo[2 * dw + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(codes[dw], 1.0f, true));
+              hi[2 * dw] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(codes[2 + dw], 1.0f, false));
+              hi[2 * dw + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(codes[2 + dw], 1.0f, true));
+            }
+          };
+          const bool whole = kbase + KB <= cen.klen;
+          u32x4 ra0[4], ra1[4], fb0[4], fb1[4];
+#pragma unroll
+          for (int cc = 0; cc < 4; ++cc) {
+            const int ch = 4 * kh + cc;        // chunk of 64 contraction elements
+            const int pc = 4 * ch + q;         // 16-byte piece of codes
+            const int pt = 8 * ch + 2 * q;     // first of the two 16-byte pieces of tokens
+            ra0[cc] = *reinterpret_cast<const u32x4 *>(pa0 + ((pc ^ r16) << 4));
+            ra1[cc] = *reinterpret_cast<const u32x4 *>(pa1 + ((pc ^ r16) << 4));
+            fb0[cc] = *reinterpret_cast<const u32x4 *>(pb + ((pt ^ r16) << 4));
+            fb1[cc] = *reinterpret_cast<const u32x4 *>(pb + (((pt + 1) ^ r16) << 4));
+            if (!whole) {  // ragged last block: pieces past the row's end hold bytes pulled back from inside it
+              if (kbase + pt * 8 >= cen.klen) fb0[cc] = (u32x4){0u, 0u, 0u, 0u};
+              if (kbase + (pt + 1) * 8 >= cen.klen) fb1[cc] = (u32x4){0u, 0u, 0u, 0u};
+            }
+          }
+#pragma unroll
+          for (int cc = 0; cc < 4; ++cc) {
+            if (whole || kbase + 64 * (4 * kh + cc) < cen.klen) {
+              u32x4 lo, hi;
+              widen(ra0[cc], lo, hi);
+              acc0[0] = mfma16(lo, fb0[cc], acc0[0]);
+              acc0[0] = mfma16(hi, fb1[cc], acc0[0]);
+              widen(ra1[cc], lo, hi);
+              acc1[0] = mfma16(lo, fb0[cc], acc1[0]);
+              acc1[0] = mfma16(hi, fb1[cc], acc1[0]);
+            }
+          }
+        } else {
         // waves split the 16 steps
         if (kbase + KB <= cen.klen) {  // whole block: no masks, reads issued back to back
           u32x4 fa0[4], fa1[4], fb[4];
@@ -640,6 +739,7 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
               acc1[0] = mfma16(fa1, fb, acc1[0]);
             }
           }
+        }
         }
         tile_done = (c_kb == cen.nkb - 1);
         ++c_kb;
@@ -730,7 +830,7 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
 
       if (tile_done) {
         const int id = c_id;
-        const int i0 = tile_i0<MODE, WIDE>(id - cen.first);
+        const int i0 = tile_i0<MODE, WIDE, FP8>(id - cen.first);
         if (WIDE) {
           // straight from the accumulators: token row 32wt + 16tt + r16; slot w < WNW/2 pairs with slot
           // w + WNW/2 (gate with up rows; down: WHROWS features further on)
@@ -754,8 +854,12 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
         } else {
           if (cen.nkb == 1) wg_barrier();  // the previous tile's sums may still be read from `red`
           // lane (q, r16) holds features 4q..4q+3 of token row r16: one 16-byte store per half
-          *reinterpret_cast<f32x4 *>(red + (wave * 2 + 0) * RED_TILE + r16 * RED_ROW + 4 * q) = acc0[0];
-          *reinterpret_cast<f32x4 *>(red + (wave * 2 + 1) * RED_TILE + r16 * RED_ROW + 4 * q) = acc1[0];
+          // (8-bit weights: partial tile index (kh, h, tile) = 4 (wave >> 1) + 2 (wave & 1) + tile)
+          const int slot2 = FP8 ? 4 * (wave >> 1) + 2 * (wave & 1) : wave * 2;
+          *reinterpret_cast<f32x4 *>(red + (slot2 + 0) * RED_TILE + r16 * RED_ROW + 4 * q) = acc0[0];
+          *reinterpret_cast<f32x4 *>(red + (slot2 + 1) * RED_TILE + r16 * RED_ROW + 4 * q) = acc1[0];
+          pend_s0 = cen.s0;
+          pend_s1 = cen.s1;
           pend = true;
           pend_m = cen.m;
           pend_row0 = cen.row0;
@@ -778,7 +882,7 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
           c_id = c.id0 + c_i * c.stride;
         }
         const int nid = c_id;
-        if (nid - cen.first >= cen.tiles || nid < cen.first) cen = load_entry<MODE, CLS>(a, tb_, c, nid);
+        if (nid - cen.first >= cen.tiles || nid < cen.first) cen = load_entry<MODE, CLS, FP8>(a, tb_, c, nid);
       }
     }
     if (!WIDE && pend) {
@@ -792,8 +896,9 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
 }
 
 // DYN: the variant that can draw units of small tiles from the counter (the host launches the
-// other one, which is a little quicker to start, when the small line is certainly too short for it)
-template <int MODE, bool DYN>
+// other one, which is a little quicker to start, when the small line is certainly too short for it).
+// FP8: expert weights are E4M3 codes with a scale per output row; only small tiles exist then.
+template <int MODE, bool DYN, bool FP8>
 __global__ __launch_bounds__(STREAM_THREADS) void expert_stream_kernel(StreamArgs a,
                                                             const int32_t *__restrict__ plan,
                                                             const int32_t *__restrict__ offsets,
@@ -809,59 +914,48 @@ __global__ __launch_bounds__(STREAM_THREADS) void expert_stream_kernel(StreamArg
   in.mode = MODE;
   in.d = a.d; in.I = a.I; in.S = a.S; in.T = a.T; in.part_k = a.part_k;
   in.shared_stream = a.shared_stream;
-  in.n_small_e = n_small_e; in.n_b64_e = n_b64_e; in.n_b128_e = n_b128_e;
+  in.n_small_e = n_small_e; in.n_b64_e = FP8 ? 0 : n_b64_e; in.n_b128_e = FP8 ? 0 : n_b128_e;
   in.G = G; in.bid = bid;
   in.dyn_allowed = DYN ? 1 : 0;
+  in.fp8 = FP8 ? 1 : 0;
   StreamSched sc;
   stream_schedule(in, const_cast<int32_t *>(plan) + PLAN_CTR + MODE, sc);
-  run_class<MODE, CLS_W128>(a, tb_, sc.c128, smem);
-  run_class<MODE, CLS_W64>(a, tb_, sc.c64, smem);
-  run_class<MODE, CLS_SMALL>(a, tb_, sc.cs, smem);
+  if constexpr (!FP8) {
+    run_class<MODE, CLS_W128, false>(a, tb_, sc.c128, smem);
+    run_class<MODE, CLS_W64, false>(a, tb_, sc.c64, smem);
+  }
+  run_class<MODE, CLS_SMALL, FP8>(a, tb_, sc.cs, smem);
 }
 
 static hipError_t launch_stream(int mode, const StreamArgs &a, hipStream_t s) {
-  static LdsLimitOnce lds_once[4];
+  static LdsLimitOnce lds_once[8];
   int dev = 0, n_cu = 0;
   hipError_t e0 = current_device(&dev, &n_cu);
   if (e0 != hipSuccess) return e0;
   // Upper bound of the small tiles (the plan is on the device): experts with rows x row tiles, plus
   // the shared expert's when it has at most 16 rows.  Below the threshold the kernel would deal
   // everything in fixed ranges anyway.
+  const long srows = a.fp8 ? 64 : 32;  // weight rows of a small tile
   const long kr = mode == MODE_GATE_UP ? a.d : a.I;
   const long nkb_s = (kr + KB - 1) / KB;
-  const long per_r = mode == MODE_GATE_UP ? (a.I + 15) / 16 : (a.d + 31) / 32;
-  const long per_s = mode == MODE_GATE_UP ? (a.S + 15) / 16 : (a.d + 31) / 32;
+  const long per_r = mode == MODE_GATE_UP ? (a.I + srows / 2 - 1) / (srows / 2) : (a.d + srows - 1) / srows;
+  const long per_s = mode == MODE_GATE_UP ? (a.S + srows / 2 - 1) / (srows / 2) : (a.d + srows - 1) / srows;
   const long parts = (mode == MODE_DOWN && a.S > 0) ? (a.S + a.part_k - 1) / a.part_k : 1;
   const long e_max = (long)a.T * a.K < a.E ? (long)a.T * a.K : a.E;
   const long small_max = e_max * per_r + ((a.S > 0 && a.T <= SMALL_M) ? per_s * parts : 0);
   const bool dyn = DYN_STATIC_PCT < 100 && small_max * nkb_s >= (long)DYN_MIN_SLOTS * n_cu &&
                    small_max >= (long)DYN_MIN_TILES * n_cu;
-  const int which = mode * 2 + (dyn ? 1 : 0);
-  const void *fns[4] = {reinterpret_cast<const void *>(expert_stream_kernel<MODE_GATE_UP, false>),
-                        reinterpret_cast<const void *>(expert_stream_kernel<MODE_GATE_UP, true>),
-                        reinterpret_cast<const void *>(expert_stream_kernel<MODE_DOWN, false>),
-                        reinterpret_cast<const void *>(expert_stream_kernel<MODE_DOWN, true>)};
-  e0 = raise_dynamic_lds_limit(lds_once[which], dev, fns[which], STREAM_LDS_BYTES);
+  const int which = (a.fp8 ? 4 : 0) + mode * 2 + (dyn ? 1 : 0);
+  typedef void (*kern_t)(StreamArgs, const int32_t *, const int32_t *, const int32_t *);
+  static const kern_t fns[8] = {
+      expert_stream_kernel<MODE_GATE_UP, false, false>, expert_stream_kernel<MODE_GATE_UP, true, false>,
+      expert_stream_kernel<MODE_DOWN, false, false>,    expert_stream_kernel<MODE_DOWN, true, false>,
+      expert_stream_kernel<MODE_GATE_UP, false, true>,  expert_stream_kernel<MODE_GATE_UP, true, true>,
+      expert_stream_kernel<MODE_DOWN, false, true>,     expert_stream_kernel<MODE_DOWN, true, true>};
+  e0 = raise_dynamic_lds_limit(lds_once[which], dev, reinterpret_cast<const void *>(fns[which]), STREAM_LDS_BYTES);
   if (e0 != hipSuccess) return e0;
-  const dim3 grid(n_cu), block(STREAM_THREADS);
-  switch (which) {
-    case 0:
-      hipLaunchKernelGGL((expert_stream_kernel<MODE_GATE_UP, false>), grid, block, STREAM_LDS_BYTES, s, a, a.plan,
-                         a.offsets, a.row_token);
-      break;
-    case 1:
-      hipLaunchKernelGGL((expert_stream_kernel<MODE_GATE_UP, true>), grid, block, STREAM_LDS_BYTES, s, a, a.plan,
-                         a.offsets, a.row_token);
-      break;
-    case 2:
-      hipLaunchKernelGGL((expert_stream_kernel<MODE_DOWN, false>), grid, block, STREAM_LDS_BYTES, s, a, a.plan,
-                         a.offsets, a.row_token);
-      break;
-    default:
-      hipLaunchKernelGGL((expert_stream_kernel<MODE_DOWN, true>), grid, block, STREAM_LDS_BYTES, s, a, a.plan,
-                         a.offsets, a.row_token);
-      break;
-  }
+  hipLaunchKernelGGL(fns[which], dim3(n_cu), dim3(STREAM_THREADS), STREAM_LDS_BYTES, s, a, a.plan, a.offsets,
+                     a.row_token);
   return hipGetLastError();
 }
 

@@ -126,7 +126,7 @@ __device__ __forceinline__ long tiled_team_start(const TiledWork &w, int g) { re
 
 // One piece: stages [st0, st1) of one tile (stage numbers in units of the region's nkb_reg).
 // FIXUP: no multiplication; the accumulators are the sum of the tile's stored pieces.
-template <int MODE, bool FIXUP>
+template <int MODE, bool FIXUP, bool FP8>
 __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSched &sc, char *smem, bool shared_region,
                                             int tile, int st0, int st1, int nkb_reg, long run_base, int slot,
                                             int team_member, const TiledWork &w) {
@@ -146,12 +146,16 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
   }
 
   const int parts = (MODE == TMODE_DOWN && a.S > 0) ? (a.S + a.part_k - 1) / a.part_k : 1;
-  const uint16_t *A0, *A1;  // the two 64-row operand halves, row 0, at this entry's k origin
+  // Weights: bf16 words, or (FP8) E4M3 codes that the loading waves widen to bf16 on their way into
+  // LDS, with one scale per output row applied in the epilogue.
+  constexpr long esz = FP8 ? 1 : 2;
+  const char *A0, *A1;  // the two 128-row operand halves, row 0, at this entry's k origin
   const uint16_t *B;
-  long a_stride, b_stride;
+  long a_stride, b_stride;  // a_stride: bytes per weight row; b_stride: elements per token row
   int n_rows, row0, m, klen, out_n;
   bool use_map;
   void *out;
+  const float *sc0 = nullptr, *sc1 = nullptr;  // (FP8) row scales of the two halves' matrices
   if (entry < n_shared_entries) {
     const int part = (MODE == TMODE_DOWN) ? entry % parts : 0;
     const int blk = (MODE == TMODE_DOWN) ? entry / parts : entry;
@@ -159,13 +163,17 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
     m = min(a.T - row0, TBM);
     use_map = false;
     if (MODE == TMODE_GATE_UP) {
-      A0 = a.ws_gate; A1 = a.ws_up; a_stride = a.d; n_rows = a.S;
+      A0 = reinterpret_cast<const char *>(a.ws_gate); A1 = reinterpret_cast<const char *>(a.ws_up);
+      a_stride = a.d * esz; n_rows = a.S;
       B = a.x; b_stride = a.d; klen = a.d; out = a.hs; out_n = a.S;
+      sc0 = a.ss_gate; sc1 = a.ss_up;
     } else {
       const int k0 = part * a.part_k;
-      A0 = a.ws_down + k0; A1 = A0 + (size_t)128 * a.S; a_stride = a.S; n_rows = a.d;
+      a_stride = a.S * esz;
+      A0 = reinterpret_cast<const char *>(a.ws_down) + k0 * esz; A1 = A0 + (size_t)128 * a_stride; n_rows = a.d;
       B = a.hs + k0; b_stride = a.S; klen = min(a.part_k, a.S - k0);
       out = a.ys + (size_t)part * a.T * a.d; out_n = a.d;
+      sc0 = sc1 = a.ss_down;
     }
   } else {
     const int le = entry - n_shared_entries;
@@ -175,11 +183,16 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
     row0 = beg + blk * TBM;
     m = min(end - row0, TBM);
     if (MODE == TMODE_GATE_UP) {
-      A0 = a.w_gate + (size_t)e * a.I * a.d; A1 = a.w_up + (size_t)e * a.I * a.d; a_stride = a.d;
+      A0 = reinterpret_cast<const char *>(a.w_gate) + (size_t)e * a.I * a.d * esz;
+      A1 = reinterpret_cast<const char *>(a.w_up) + (size_t)e * a.I * a.d * esz;
+      a_stride = a.d * esz;
       n_rows = a.I; B = a.x; b_stride = a.d; use_map = true; klen = a.d; out = a.h; out_n = a.I;
+      sc0 = a.s_gate + (size_t)e * a.I; sc1 = a.s_up + (size_t)e * a.I;
     } else {
-      A0 = a.w_down + (size_t)e * a.d * a.I; A1 = A0 + (size_t)128 * a.I; a_stride = a.I;
+      a_stride = a.I * esz;
+      A0 = reinterpret_cast<const char *>(a.w_down) + (size_t)e * a.d * a.I * esz; A1 = A0 + (size_t)128 * a_stride;
       n_rows = a.d; B = a.h; b_stride = a.I; use_map = false; klen = a.I; out = a.y; out_n = a.d;
+      sc0 = sc1 = a.s_down + (size_t)e * a.d;
     }
   }
   // first output feature of this tile; gate/up: 128 features (rows i0.. of both matrices),
@@ -199,13 +212,13 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
   uint32_t off[T_LW];   // this lane's rows (clamped into the valid rows), in bytes from wbase
   if (!load_b) {
     const bool second = lw * T_LROWS >= 128;
-    const uint16_t *base = (second && second_ok) ? A1 : A0;
+    const char *base = (second && second_ok) ? A1 : A0;
     const int rv = second ? rv1 : rv0;
-    wbase = reinterpret_cast<const char *>(base + (size_t)i0 * a_stride);
+    wbase = base + (size_t)i0 * a_stride;
 #pragma unroll
     for (int i = 0; i < T_LW; ++i) {
       const int hrow = (lw * T_LROWS) % 128 + 8 * i + lrow;
-      off[i] = (uint32_t)min(hrow, rv - 1) * (uint32_t)(a_stride * 2);
+      off[i] = (uint32_t)min(hrow, rv - 1) * (uint32_t)a_stride;
     }
   } else {
     wbase = reinterpret_cast<const char *>(use_map ? B : B + (size_t)row0 * b_stride);
@@ -220,11 +233,30 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
   const int srow0 = (load_b ? TBN : 0) + T_LROWS * lw + lrow;
   auto load_stage = [&](int s, u32x4 (&pre)[T_LW]) __attribute__((always_inline)) {
     // a piece past the end of the rows is pulled back inside (it is zeroed before the store)
-    const uint32_t kk = 2u * (uint32_t)min(s * TBK + piece * 8, klen - 8);
+    const uint32_t k8 = (uint32_t)min(s * TBK + piece * 8, klen - 8);  // this lane's 8 contraction elements
+    if (FP8 && !load_b) {  // 8 codes = 8 bytes; widened when they are stored
 #pragma unroll
-    for (int i = 0; i < T_LW; ++i) pre[i] = *reinterpret_cast<const u32x4 *>(wbase + (off[i] + kk));
+      for (int i = 0; i < T_LW; ++i) {
+        const u32x2 v = *reinterpret_cast<const u32x2 *>(wbase + (off[i] + k8));
+        pre[i][0] = v[0];
+        pre[i][1] = v[1];
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < T_LW; ++i) pre[i] = *reinterpret_cast<const u32x4 *>(wbase + (off[i] + 2u * k8));
+    }
   };
   auto store_stage = [&](int s, int buf, u32x4 (&pre)[T_LW], bool ragged) __attribute__((always_inline)) {
+    if (FP8 && !load_b) {  // E4M3 -> bf16 is exact
+#pragma unroll
+      for (int i = 0; i < T_LW; ++i) {
+        const uint32_t c0 = pre[i][0], c1 = pre[i][1];
+        pre[i][0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(c0, 1.0f, false));
+        pre[i][1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(c0, 1.0f, true));
+        pre[i][2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(c1, 1.0f, false));
+        pre[i][3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(c1, 1.0f, true));
+      }
+    }
     if (ragged && s * TBK + piece * 8 >= klen) {
 #pragma unroll
       for (int i = 0; i < T_LW; ++i) pre[i] = (u32x4){0u, 0u, 0u, 0u};
@@ -497,10 +529,15 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
           if (MODE == TMODE_GATE_UP) {
             const int i = i0 + f;
             if (i < out_n) {
+              f32x4 cg = {1.f, 1.f, 1.f, 1.f}, cu = {1.f, 1.f, 1.f, 1.f};
+              if (FP8) {  // one scale per weight row = per output feature
+                cg = *reinterpret_cast<const f32x4 *>(sc0 + i);
+                cu = *reinterpret_cast<const f32x4 *>(sc1 + i);
+              }
               uint32_t hb[4];
 #pragma unroll
               for (int c = 0; c < 4; ++c)
-                hb[c] = f32_to_bf16_bits(silu_f32(acc[hh][t][4 * g + c]) * acc[2 + hh][t][4 * g + c]);
+                hb[c] = f32_to_bf16_bits(silu_f32(acc[hh][t][4 * g + c] * cg[c]) * (acc[2 + hh][t][4 * g + c] * cu[c]));
               u32x2 o;
               o[0] = hb[0] | (hb[1] << 16);
               o[1] = hb[2] | (hb[3] << 16);
@@ -514,6 +551,11 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
               if (i < out_n) {
                 const f32x16 &v = acc[2 * h2 + hh][t];
                 f32x4 o = {v[4 * g], v[4 * g + 1], v[4 * g + 2], v[4 * g + 3]};
+                if (FP8) {
+                  const f32x4 cd = *reinterpret_cast<const f32x4 *>(sc0 + i);
+#pragma unroll
+                  for (int c = 0; c < 4; ++c) o[c] *= cd[c];
+                }
                 *reinterpret_cast<f32x4 *>(y + orow * out_n + i) = o;
               }
             }
@@ -523,7 +565,7 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
   }
 }
 
-template <int MODE>
+template <int MODE, bool FP8>
 __global__ __launch_bounds__(T_THREADS) void expert_tiled_kernel(StreamArgs a, TiledSched sc) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   // Workgroup ids are dealt to the 8 XCDs round-robin: team g lives on XCD g % 8.
@@ -570,7 +612,7 @@ __global__ __launch_bounds__(T_THREADS) void expert_tiled_kernel(StreamArgs a, T
         tile = rt * w.n_large + entry;
       }
       const int nkb_reg = shared_region ? sc.nkb_s : sc.nkb_r;
-      if (valid) tiled_piece<MODE, false>(a, sc, smem, shared_region, tile, 0, nkb_reg, nkb_reg, 0, 0, member, w);
+      if (valid) tiled_piece<MODE, false, FP8>(a, sc, smem, shared_region, tile, 0, nkb_reg, nkb_reg, 0, 0, member, w);
     }
     return;
   }
@@ -586,7 +628,7 @@ __global__ __launch_bounds__(T_THREADS) void expert_tiled_kernel(StreamArgs a, T
     const int st1 = (int)min((long)nkb_reg, st0 + (u_end - u));
     const int tile = (int)(4 * run + member);
     if (tile < (shared_region ? w.n_sh_tiles : w.n_r_tiles))
-      tiled_piece<MODE, false>(a, sc, smem, shared_region, tile, st0, st1, nkb_reg, u - st0,
+      tiled_piece<MODE, false, FP8>(a, sc, smem, shared_region, tile, st0, st1, nkb_reg, u - st0,
                                2 * (int)blockIdx.x + (piece == 0 ? 0 : 1), member, w);
     u += st1 - st0;
     ++piece;
@@ -595,7 +637,7 @@ __global__ __launch_bounds__(T_THREADS) void expert_tiled_kernel(StreamArgs a, T
 
 // Finishes the tiles the main kernel's share boundaries cut.  Workgroup (g, member): if the
 // boundary between teams g and g+1 is the first one inside its run, sum that run's pieces.
-template <int MODE>
+template <int MODE, bool FP8>
 __global__ __launch_bounds__(T_THREADS) void expert_tiled_fixup_kernel(StreamArgs a, TiledSched sc) {
   const int g = blockIdx.x / 4, member = blockIdx.x % 4;
   const TiledWork w = tiled_work(a, sc);
@@ -611,7 +653,7 @@ __global__ __launch_bounds__(T_THREADS) void expert_tiled_fixup_kernel(StreamArg
   if (tiled_team_start(w, g) > run_base) return;  // an earlier boundary inside this run does the work
   const int tile = (int)(4 * (ur / nkb_reg) + member);
   if (tile >= (shared_region ? w.n_sh_tiles : w.n_r_tiles)) return;
-  tiled_piece<MODE, true>(a, sc, nullptr, shared_region, tile, 0, nkb_reg, nkb_reg, run_base, 0, member, w);
+  tiled_piece<MODE, true, FP8>(a, sc, nullptr, shared_region, tile, 0, nkb_reg, nkb_reg, run_base, 0, member, w);
 }
 
 // The persistent grid: whole teams of 4 on each of the 8 XCDs, at most TILED_MAX_WGS workgroups
@@ -642,16 +684,21 @@ int shared_expert_streams(int T, int d, int S, int part_k, int K, int E, int n_c
 
 size_t tiled_partials_bytes() { return (size_t)2 * TILED_MAX_WGS * T_SLOT_FLOATS * sizeof(float); }
 static hipError_t launch_tiled(int mode, const StreamArgs &a, float *partials, hipStream_t s) {
-  static LdsLimitOnce lds_once[2];
-  const void *fn = mode == TMODE_GATE_UP ? reinterpret_cast<const void *>(expert_tiled_kernel<TMODE_GATE_UP>)
-                                         : reinterpret_cast<const void *>(expert_tiled_kernel<TMODE_DOWN>);
+  static LdsLimitOnce lds_once[4];
+  typedef void (*kern_t)(StreamArgs, TiledSched);
+  static const kern_t mains[4] = {expert_tiled_kernel<TMODE_GATE_UP, false>, expert_tiled_kernel<TMODE_DOWN, false>,
+                                  expert_tiled_kernel<TMODE_GATE_UP, true>, expert_tiled_kernel<TMODE_DOWN, true>};
+  static const kern_t fixups[4] = {
+      expert_tiled_fixup_kernel<TMODE_GATE_UP, false>, expert_tiled_fixup_kernel<TMODE_DOWN, false>,
+      expert_tiled_fixup_kernel<TMODE_GATE_UP, true>, expert_tiled_fixup_kernel<TMODE_DOWN, true>};
+  const int which = (a.fp8 ? 2 : 0) + mode;
   int dev = 0, n_cu = 0;
   hipError_t e = current_device(&dev, &n_cu);
   if (e != hipSuccess) return e;
-  e = raise_dynamic_lds_limit(lds_once[mode], dev, fn, TILED_LDS_BYTES);
+  e = raise_dynamic_lds_limit(lds_once[which], dev, reinterpret_cast<const void *>(mains[which]), TILED_LDS_BYTES);
   if (e != hipSuccess) return e;
-  // (row offsets are kept as 32-bit byte counts inside the kernel: T * d * 2 < 2^32, checked by the caller)
-  if (a.T <= PLAN_BIG_MAX_ROWS) return hipSuccess;
+  // (row offsets are kept as 32-bit byte counts inside the kernel: T * d * 2 < 2^32, checked by the caller,
+  // which also decides whether these kernels have anything to do at this T)
   const int parts = (mode == TMODE_DOWN && a.S > 0) ? (a.S + a.part_k - 1) / a.part_k : 1;
   TiledSched sc;
   sc.n_shared_entries = (a.S > 0 && !a.shared_stream) ? ((a.T + TBM - 1) / TBM) * parts : 0;
@@ -667,13 +714,8 @@ static hipError_t launch_tiled(int mode, const StreamArgs &a, float *partials, h
   sc.partials = partials;
   const unsigned grid = (unsigned)tiled_grid_for(n_cu);
   sc.n_teams = (int)grid / 4;
-  if (mode == TMODE_GATE_UP) {
-    hipLaunchKernelGGL(expert_tiled_kernel<TMODE_GATE_UP>, dim3(grid), dim3(T_THREADS), TILED_LDS_BYTES, s, a, sc);
-    hipLaunchKernelGGL(expert_tiled_fixup_kernel<TMODE_GATE_UP>, dim3(grid), dim3(T_THREADS), 0, s, a, sc);
-  } else {
-    hipLaunchKernelGGL(expert_tiled_kernel<TMODE_DOWN>, dim3(grid), dim3(T_THREADS), TILED_LDS_BYTES, s, a, sc);
-    hipLaunchKernelGGL(expert_tiled_fixup_kernel<TMODE_DOWN>, dim3(grid), dim3(T_THREADS), 0, s, a, sc);
-  }
+  hipLaunchKernelGGL(mains[which], dim3(grid), dim3(T_THREADS), TILED_LDS_BYTES, s, a, sc);
+  hipLaunchKernelGGL(fixups[which], dim3(grid), dim3(T_THREADS), 0, s, a, sc);
   return hipGetLastError();
 }
 

@@ -35,6 +35,10 @@ int32_t check_desc(const moesd_layer_desc *c) {
   if (c->score_func != MOESD_SCORE_SOFTMAX && c->score_func != MOESD_SCORE_SIGMOID)
     return MOESD_UNSUPPORTED;
   if ((c->renormalize | 1) != 1 || (c->shared_gate | 1) != 1) return MOESD_UNSUPPORTED;
+  if (c->weight_format != MOESD_WEIGHTS_BF16 && c->weight_format != MOESD_WEIGHTS_FP8_E4M3)
+    return MOESD_UNSUPPORTED;
+  if (c->weight_format == MOESD_WEIGHTS_FP8_E4M3 && (c->d % 16 || c->inter % 16 || c->shared_inter % 16))
+    return MOESD_INVALID_ARG;  // 16-byte pieces of 8-bit weights
   return MOESD_OK;
 }
 
@@ -63,6 +67,13 @@ struct Workspace {
   int32_t part_k, parts;
   size_t bytes;
 };
+
+// Above how many tokens the MFMA-tiled kernels run (and need their partial-sum space): they take
+// the experts with more than 128 rows; 8-bit weights have no wide streaming classes, so there they
+// take every expert (and the shared expert) with more than 16 rows.
+inline int32_t tiled_from(const moesd_layer_desc *c) {
+  return c->weight_format == MOESD_WEIGHTS_FP8_E4M3 ? 16 : PLAN_BIG_MAX_ROWS;
+}
 
 // the group-limited selection's two settings in one launch argument (0: unconstrained)
 inline int groups_of(const moesd_layer_desc *c) {
@@ -103,7 +114,7 @@ Workspace carve(const moesd_layer_desc *c, int64_t T, char *base) {
   ws.hs = (uint16_t *)take(sizeof(uint16_t) * T * S);
   ws.y = (float *)take(sizeof(float) * T * K * d);
   ws.ys = (float *)take(sizeof(float) * ws.parts * T * d);
-  ws.tiled_partials = (float *)take(T > PLAN_BIG_MAX_ROWS ? tiled_partials_bytes() : 0);
+  ws.tiled_partials = (float *)take(T > tiled_from(c) ? tiled_partials_bytes() : 0);
   ws.bytes = off;
   return ws;
 }
@@ -206,6 +217,10 @@ int32_t check_forward(const moesd_layer_desc *desc, const moesd_weights *wt, con
   if (!wt->w_router || !wt->w_gate || !wt->w_up || !wt->w_down) return MOESD_INVALID_ARG;
   if (has_shared && (!wt->ws_gate || !wt->ws_up || !wt->ws_down)) return MOESD_INVALID_ARG;
   if (has_shared && desc->shared_gate && !wt->w_shared_gate) return MOESD_INVALID_ARG;
+  if (desc->weight_format == MOESD_WEIGHTS_FP8_E4M3) {
+    if (!wt->w_gate_scale || !wt->w_up_scale || !wt->w_down_scale) return MOESD_INVALID_ARG;
+    if (has_shared && (!wt->ws_gate_scale || !wt->ws_up_scale || !wt->ws_down_scale)) return MOESD_INVALID_ARG;
+  }
   *need_bytes = 0;
   if (T == 0) return MOESD_OK;
   if (!x || !out) return MOESD_INVALID_ARG;
@@ -257,29 +272,38 @@ int32_t run_forward(const moesd_layer_desc *desc, const moesd_weights *wt, const
   MOESD_TRY(launch_router_logits((const uint16_t *)x, (const uint16_t *)wt->w_router,
                                  wt->router_bias, gated ? (const uint16_t *)wt->w_shared_gate : nullptr,
                                  T, desc->d, desc->E, ws.logits, s))
+  const bool fp8 = desc->weight_format == MOESD_WEIGHTS_FP8_E4M3;
+  const bool tiled = T > tiled_from(desc);
   if (T <= MOESD_FUSED_TOPK_MAX_T && desc->E <= 256) {
     MOESD_TRY(launch_topk_permute(ws.logits, T, desc->E, desc->top_k, desc->score_func,
                                   desc->renormalize, desc->routed_scale, groups_of(desc), gated ? 1 : 0, ids, w,
-                                  ws.gate, cnt, off, pm, iv, na, ws.row_token, ws.plan, s))
+                                  ws.gate, cnt, off, pm, iv, na, ws.row_token, ws.plan, fp8 ? PLAN_NO_WIDE : 0, s))
   } else {
     MOESD_TRY(launch_topk(ws.logits, T, desc->E, desc->top_k, desc->score_func, desc->renormalize,
                           desc->routed_scale, groups_of(desc), gated ? 1 : 0, ids, w, ws.gate, s))
     // the wide classes of the streaming kernels fill the chip when their tiles of the down projection
     // (128 output rows each), the shorter of the two lists, number at least one per compute unit
     const int wide_rt = (desc->d + 127) / 128;
-    const int wide_fill_min = T > PLAN_BIG_MAX_ROWS ? (n_cu + wide_rt - 1) / wide_rt : 0;
+    const int wide_fill_min = fp8 ? PLAN_NO_WIDE : (T > PLAN_BIG_MAX_ROWS ? (n_cu + wide_rt - 1) / wide_rt : 0);
     MOESD_TRY(launch_permute(ids, (int64_t)T * desc->top_k, desc->E, desc->top_k, cnt, off, pm, iv, na,
                              ws.row_token, ws.plan, wide_fill_min, s))
   }
   MOESD_EVENT(1)
 
   StreamArgs a;
-  a.w_gate = (const uint16_t *)wt->w_gate;
-  a.w_up = (const uint16_t *)wt->w_up;
-  a.w_down = (const uint16_t *)wt->w_down;
-  a.ws_gate = (const uint16_t *)wt->ws_gate;
-  a.ws_up = (const uint16_t *)wt->ws_up;
-  a.ws_down = (const uint16_t *)wt->ws_down;
+  a.w_gate = wt->w_gate;
+  a.w_up = wt->w_up;
+  a.w_down = wt->w_down;
+  a.ws_gate = wt->ws_gate;
+  a.ws_up = wt->ws_up;
+  a.ws_down = wt->ws_down;
+  a.s_gate = wt->w_gate_scale;
+  a.s_up = wt->w_up_scale;
+  a.s_down = wt->w_down_scale;
+  a.ss_gate = wt->ws_gate_scale;
+  a.ss_up = wt->ws_up_scale;
+  a.ss_down = wt->ws_down_scale;
+  a.fp8 = fp8 ? 1 : 0;
   a.x = (const uint16_t *)x;
   a.h = ws.h;
   a.hs = ws.hs;
@@ -295,15 +319,17 @@ int32_t run_forward(const moesd_layer_desc *desc, const moesd_weights *wt, const
   a.I = desc->inter;
   a.S = desc->shared_inter;
   a.T = T;
-  a.shared_stream = shared_expert_streams(T, desc->d, desc->shared_inter, ws.part_k, desc->top_k, desc->E, n_cu);
-  // experts with at most 128 rows stream; the others (possible only if T > 128) are tiled
+  // 8-bit weights: the streaming kernels keep the shared expert only up to 16 tokens
+  a.shared_stream = fp8 ? (T <= 16 ? 1 : 0)
+                        : shared_expert_streams(T, desc->d, desc->shared_inter, ws.part_k, desc->top_k, desc->E, n_cu);
+  // experts with at most 128 rows stream (8-bit weights: at most 16); the others are tiled
   MOESD_TRY(launch_gate_up(a, s))
-  if (T > PLAN_BIG_MAX_ROWS) {
+  if (tiled) {
     MOESD_TRY(launch_gate_up_tiled(a, ws.tiled_partials, s))
   }
   MOESD_EVENT(2)
   MOESD_TRY(launch_down(a, s))
-  if (T > PLAN_BIG_MAX_ROWS) { MOESD_TRY(launch_down_tiled(a, ws.tiled_partials, s)) }
+  if (tiled) { MOESD_TRY(launch_down_tiled(a, ws.tiled_partials, s)) }
   MOESD_EVENT(3)
   MOESD_TRY(launch_combine(ws.y, ws.ys, ws.parts, w, ws.gate, iv, T, desc->top_k, desc->d,
                            (uint16_t *)out, out_f32, s))

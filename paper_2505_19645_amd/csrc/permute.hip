@@ -87,9 +87,10 @@ __device__ __forceinline__ void permute_body(
   if (lane == 0 && wideb) atomicAdd(&wide_tot, __popcll(wideb));
   if (lane == 0 && largeb) atomicAdd(&large_tot, __popcll(largeb));
   __syncthreads();
-  const int b128_max = (large_tot > 0 && wide_tot < wide_fill_min) ? 64 : PLAN_BIG_MAX_ROWS;
+  const bool no_wide = wide_fill_min == PLAN_NO_WIDE;
+  const int b128_max = no_wide ? 16 : ((large_tot > 0 && wide_tot < wide_fill_min) ? 64 : PLAN_BIG_MAX_ROWS);
   const int v_small = (v >= 1 && v <= 16) ? 1 : 0;
-  const int v_b64 = (v > 16 && v <= 64) ? 1 : 0;
+  const int v_b64 = (!no_wide && v > 16 && v <= 64) ? 1 : 0;
   const int v_b128 = (v > 64 && v <= b128_max) ? 1 : 0;
   const int v_large = (v > b128_max) ? (v + 255) / 256 : 0;
   int incl = v, incl_s = v_small, incl_b = v_b64, incl_c = v_b128, incl_l = v_large;
@@ -202,15 +203,15 @@ __global__ __launch_bounds__(PERM_THREADS) void topk_permute_kernel(
     float scale, int groups, int32_t *ids, float *__restrict__ w, float *__restrict__ gate, int nbits,
     int32_t *__restrict__ counts, int32_t *__restrict__ offsets, int32_t *__restrict__ perm,
     int32_t *__restrict__ inv, int32_t *__restrict__ n_active, int32_t *__restrict__ row_token,
-    int32_t *__restrict__ plan) {
+    int32_t *__restrict__ plan, int wide_fill_min) {
   extern __shared__ int32_t smem[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   for (int t = wave; t < T; t += PERM_WAVES)
     topk_token<SLOTS>(logits, t, lane, E, Etot, K, score_func, renorm, scale, groups, ids, w, gate);
   __threadfence_block();
   __syncthreads();
-  permute_body(ids, (int64_t)T * K, E, K, nbits, counts, offsets, perm, inv, n_active, row_token, plan, 0,
-               smem);  // few tokens: no expert has more than 128 rows
+  permute_body(ids, (int64_t)T * K, E, K, nbits, counts, offsets, perm, inv, n_active, row_token, plan,
+               wide_fill_min, smem);  // (few tokens: no expert has more than 128 rows)
 }
 
 hipError_t launch_permute(const int32_t *ids, int64_t n, int E, int K, int32_t *counts,
@@ -235,7 +236,8 @@ hipError_t launch_permute(const int32_t *ids, int64_t n, int E, int K, int32_t *
 hipError_t launch_topk_permute(const double *logits, int T, int E, int K, int score_func, int renorm,
                                float scale, int groups, int has_shared_gate, int32_t *ids, float *w,
                                float *gate, int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv,
-                               int32_t *n_active, int32_t *row_token, int32_t *plan, hipStream_t s) {
+                               int32_t *n_active, int32_t *row_token, int32_t *plan, int wide_fill_min,
+                               hipStream_t s) {
   const int Etot = E + (has_shared_gate ? 1 : 0);
   int nbits = 1;
   while ((1 << nbits) < E) ++nbits;
@@ -243,11 +245,11 @@ hipError_t launch_topk_permute(const double *logits, int T, int E, int K, int sc
   if (E <= 64) {
     hipLaunchKernelGGL(topk_permute_kernel<1>, dim3(1), dim3(PERM_THREADS), smem, s, logits, T, E, Etot,
                        K, score_func, renorm, scale, groups, ids, w, gate, nbits, counts, offsets, perm, inv,
-                       n_active, row_token, plan);
+                       n_active, row_token, plan, wide_fill_min);
   } else if (E <= 256) {
     hipLaunchKernelGGL(topk_permute_kernel<4>, dim3(1), dim3(PERM_THREADS), smem, s, logits, T, E, Etot,
                        K, score_func, renorm, scale, groups, ids, w, gate, nbits, counts, offsets, perm, inv,
-                       n_active, row_token, plan);
+                       n_active, row_token, plan, wide_fill_min);
   } else {
     return hipErrorInvalidValue;  // callers use the two-kernel path for wider routers
   }

@@ -78,6 +78,7 @@ struct SchedIn {
   int n_small_e, n_b64_e, n_b128_e;  // experts with 1..16, 17..64, 65..128 rows
   int G, bid;                // workgroups, this workgroup
   int dyn_allowed;           // the launched kernel can draw units
+  int fp8;                   // 8-bit weights: small tiles of 64 weight rows, no wide classes
 };
 
 struct StreamSched {
@@ -94,13 +95,16 @@ MOESD_SCHED_FN void stream_schedule(const SchedIn &in, int32_t *ctr, StreamSched
   const int parts = (!gu && has_shared) ? (in.S + in.part_k - 1) / in.part_k : 1;
   ClassCfg &c128 = out.c128, &c64 = out.c64, &cs = out.cs;
   c128.parts = c64.parts = cs.parts = parts;
-  cs.per_r = gu ? (in.I + 15) / 16 : (in.d + 31) / 32;
-  cs.per_s = gu ? (in.S + 15) / 16 : (in.d + 31) / 32;
+  // a small tile is one 32 KB weight slot wide: 32 rows of bf16 (16 of w_gate + 16 of w_up, or 32 of
+  // w_down) or 64 rows of 8-bit codes
+  const int srows = in.fp8 ? 64 : 32;
+  cs.per_r = gu ? (in.I + srows / 2 - 1) / (srows / 2) : (in.d + srows - 1) / srows;
+  cs.per_s = gu ? (in.S + srows / 2 - 1) / (srows / 2) : (in.d + srows - 1) / srows;
   c64.per_r = c128.per_r = gu ? (in.I + WHROWS - 1) / WHROWS : (in.d + 2 * WHROWS - 1) / (2 * WHROWS);
   c64.per_s = c128.per_s = gu ? (in.S + WHROWS - 1) / WHROWS : (in.d + 2 * WHROWS - 1) / (2 * WHROWS);
   cs.n_sh = (has_shared && in.T <= SMALL_M) ? cs.per_s * parts : 0;
-  c64.n_sh = (has_shared && in.T > SMALL_M && in.T <= W64_TB) ? c64.per_s * parts : 0;
-  c128.n_sh = (has_shared && in.T > W64_TB && in.shared_stream)
+  c64.n_sh = (has_shared && !in.fp8 && in.T > SMALL_M && in.T <= W64_TB) ? c64.per_s * parts : 0;
+  c128.n_sh = (has_shared && !in.fp8 && in.T > W64_TB && in.shared_stream)
                   ? c128.per_s * parts * ((in.T + W128_TB - 1) / W128_TB) : 0;
   const int n128 = c128.n_sh + in.n_b128_e * c128.per_r;
   const int n64 = c64.n_sh + in.n_b64_e * c64.per_r;

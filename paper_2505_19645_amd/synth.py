@@ -109,23 +109,30 @@ E4M3_MAX = 448.0
 
 
 def encode_e4m3(a: np.ndarray) -> np.ndarray:
-    """Nearest E4M3 code of each value (ties to the even code, magnitudes above 448 saturate)."""
-    a = np.asarray(a, dtype=np.float64)
-    mag = np.minimum(np.abs(a), E4M3_MAX)
-    hi = np.searchsorted(_E4M3_POS, mag, side="left").clip(1, 126)
-    lo = hi - 1
-    dlo, dhi = mag - _E4M3_POS[lo], _E4M3_POS[hi] - mag
-    code = np.where((dhi < dlo) | ((dhi == dlo) & (hi % 2 == 0)), hi, lo).astype(np.uint8)
-    return code | (np.signbit(a).astype(np.uint8) << 7)
+    """Nearest E4M3 code of each value (ties to the even code, magnitudes above 448 saturate).
+    Works on the fp32 bit patterns: above 2^-6 the fp32 mantissa is rounded to 3 bits (nearest even,
+    the carry runs into the exponent by itself); below, the codes are multiples of 2^-9."""
+    x = np.ascontiguousarray(a, dtype=np.float32)
+    u = x.view(np.uint32)
+    sign = ((u >> np.uint32(24)) & np.uint32(0x80)).astype(np.uint8)
+    mag = u & np.uint32(0x7FFFFFFF)
+    r = mag + np.uint32(0x7FFFF) + ((mag >> np.uint32(20)) & np.uint32(1))   # round to 3 mantissa bits
+    code = ((r >> np.uint32(20)).astype(np.int32) - np.int32((127 - 7) << 3))  # rebias: (e - 127 + 7) << 3 | m
+    sub = mag < np.uint32(0x3C800000)                                         # |x| < 2^-6: subnormal codes
+    if sub.any():
+        code[sub] = np.rint(np.abs(x[sub]) * np.float32(512.0)).astype(np.int32)
+    np.clip(code, 0, 0x7E, out=code)
+    return code.astype(np.uint8) | sign
 
 
 def quantize_rows_e4m3(w_bits: np.ndarray):
     """bf16 words [..., rows, cols] -> (E4M3 codes, fp32 scales [..., rows]): each row is divided by
     max|row| / 448 (rounded to fp32) and rounded to the nearest code."""
-    w = bf16_bits_to_f32(w_bits).astype(np.float64)
+    w = bf16_bits_to_f32(w_bits)
     amax = np.abs(w).max(axis=-1)
-    scale = np.where(amax > 0, amax / E4M3_MAX, 1.0).astype(np.float32)
-    return encode_e4m3(w / scale[..., None].astype(np.float64)), scale
+    scale = np.where(amax > 0, amax / np.float32(E4M3_MAX), np.float32(1.0)).astype(np.float32)
+    w /= scale[..., None]
+    return encode_e4m3(w), scale
 
 
 def _rng(seed: int, tensor: str, block: int) -> np.random.Generator:

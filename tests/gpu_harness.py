@@ -28,8 +28,10 @@ class GpuLayer:
         for k, v in weights_np.items():
             if v is None:
                 self.t[k] = None
-            elif k == "router_bias":
+            elif k == "router_bias" or k.endswith("_scale"):
                 self.t[k] = to_dev(v.astype(np.float32))
+            elif v.dtype == np.uint8:                      # E4M3 codes
+                self.t[k] = to_dev(v)
             else:
                 self.t[k] = to_dev_bf16(v)
         self.weights = moesd.make_weights(self.t)

@@ -7,12 +7,12 @@ extern "C" {
 // per_s, per_r; then the small class's dyn, n_units, n_double, ut, pool0, n_tiles.
 void moesd_test_stream_schedule(int mode, int d, int I, int S, int T, int part_k, int shared_stream,
                                 int n_small_e, int n_b64_e, int n_b128_e, int G, int bid,
-                                int dyn_allowed, int *out) {
+                                int dyn_allowed, int fp8, int *out) {
   SchedIn in;
   in.mode = mode; in.d = d; in.I = I; in.S = S; in.T = T; in.part_k = part_k;
   in.shared_stream = shared_stream;
   in.n_small_e = n_small_e; in.n_b64_e = n_b64_e; in.n_b128_e = n_b128_e;
-  in.G = G; in.bid = bid; in.dyn_allowed = dyn_allowed;
+  in.G = G; in.bid = bid; in.dyn_allowed = dyn_allowed; in.fp8 = fp8;
   StreamSched sc;
   stream_schedule(in, nullptr, sc);
   const ClassCfg *cs[3] = {&sc.c128, &sc.c64, &sc.cs};

@@ -111,6 +111,18 @@ def test_forward_argument_errors_need_no_gpu():
                                  check=False) == binding.INVALID_ARG
     assert binding.moesd_route(d, None, 0x1000, None, 4, 0x1000, 0x1000, 0x1000, 1 << 20, stream=0,
                                check=False) == binding.INVALID_ARG
+    # 8-bit expert weights: unknown format, sizes that are not multiples of 16, missing row scales
+    bad = moesd.make_desc(LayerShape("b", 256, 8, 2, 512, weight_format=2))
+    assert _fwd(bad, 16) == binding.UNSUPPORTED
+    bad = moesd.make_desc(LayerShape("b", 264, 8, 2, 512, weight_format=1))
+    assert _fwd(bad, 16) == binding.INVALID_ARG
+    bad = moesd.make_desc(LayerShape("b", 256, 8, 2, 520, weight_format=1))
+    assert _fwd(bad, 16) == binding.INVALID_ARG
+    q = moesd.make_desc(LayerShape("q", 256, 8, 2, 512, shared_inter=64, weight_format=1))
+    assert _fwd(q, 16, ws_bytes=1 << 30, wt={"w_up_scale": None}) == binding.INVALID_ARG
+    assert _fwd(q, 16, ws_bytes=1 << 30, wt={"ws_down_scale": None}) == binding.INVALID_ARG
+    # with 8-bit weights the MFMA-tiled kernels (and their partial-sum space) come in above 16 tokens
+    assert moesd.moesd_workspace_bytes(q, 16) < (64 << 20) < (128 << 20) <= moesd.moesd_workspace_bytes(q, 17)
     # the entry point on the library's static scratch array: the same checks, and sizes beyond the array
     wq = binding.Weights()
     for n, _ in binding.Weights._fields_:

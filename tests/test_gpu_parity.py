@@ -171,6 +171,41 @@ def test_group_limited_selection(gpu, oracle, shape, T):
     assert all(len(set((got["ids"][t] // gs).tolist())) <= shape.topk_group for t in range(T))
 
 
+@pytest.mark.parametrize("T", [1, 5, 16, 17, 40, 64, 130, 300])
+def test_fp8_weights_small_shapes(gpu, oracle, T):
+    # expert weights as E4M3 codes with a scale per output row (64-row small tiles in the streaming kernels up to 16
+    # rows per expert; beyond that, and the shared expert beyond 16 tokens, the MFMA-tiled kernels, which widen the
+    # codes on their way into LDS); ragged sizes (multiples of 16), gated shared expert
+    shape = LayerShape("fp8-ragged", d=400, E=12, top_k=3, inter=208, shared_inter=144, shared_gate=1,
+                       weight_format=1, seed=51)
+    run_case(gpu, oracle, shape, T)
+
+
+@pytest.mark.parametrize("shape,T,skew", [
+    (LayerShape("fp8-sigmoid", d=512, E=40, top_k=6, inter=272, shared_inter=80, score_func=1, weight_format=1, seed=52), 23, 0.0),
+    (LayerShape("fp8-no-shared", d=1040, E=24, top_k=2, inter=1040, weight_format=1, seed=53), 33, 0.0),
+    (LayerShape("fp8-one-block", d=512, E=16, top_k=4, inter=512, weight_format=1, seed=54), 12, 0.0),   # one-slot tiles
+    (LayerShape("fp8-skewed", d=256, E=16, top_k=2, inter=128, shared_inter=64, shared_gate=1, weight_format=1, seed=55), 200, 2.0),
+    (LayerShape("fp8-many-rows", d=128, E=2, top_k=1, inter=144, weight_format=1, seed=56), 700, 0.0),
+])
+def test_fp8_weights_variants(gpu, oracle, shape, T, skew):
+    run_case(gpu, oracle, shape, T, skew=skew)
+
+
+def test_fp8_weights_benchmark_shapes_full_size(gpu, oracle):
+    # benchmark configs 1 and 2 with their expert weights quantised to E4M3 (row scales), full size: T = 16 with
+    # every token compared, T = 64 (the shared expert in the MFMA-tiled kernels) on tokens chosen from the permutation
+    for name, pt in (("qwen1.5-moe-a2.7b", 180), ("qwen2-57b-a14b", 280)):
+        shape = dataclasses.replace(PRESETS[name], name=name + "-fp8", weight_format=1)
+        w = synth.make_layer(shape, threads=16)
+        layer = gpu.GpuLayer(shape, w)
+        run_case(gpu, oracle, shape, 16, point=pt, weights=w, layer=layer)
+        x = synth.make_tokens(shape, 64, point=pt + 1)
+        run_case(gpu, oracle, shape, 64, tokens=tokens_from_permutation(oracle, shape, w, x), point=pt + 1, weights=w,
+                 layer=layer)
+        del layer, w
+
+
 def _random_shape(i):
     """A small layer with every size drawn at random (seeded): odd row counts, ragged contraction lengths,
     all expert classes, with and without shared expert, groups, bias."""

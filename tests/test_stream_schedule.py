@@ -19,22 +19,22 @@ def sched(tmp_path_factory):
     subprocess.run(["g++", "-O1", "-std=c++17", "-shared", "-fPIC", "-Wall", "-Werror", "-fsanitize=undefined",
                     "-fno-sanitize-recover=undefined", "-o", so, SRC], check=True)
     L = C.CDLL(so)
-    L.moesd_test_stream_schedule.argtypes = [C.c_int] * 13 + [C.POINTER(C.c_int)]
+    L.moesd_test_stream_schedule.argtypes = [C.c_int] * 14 + [C.POINTER(C.c_int)]
     L.moesd_test_unit_range.argtypes = [C.c_int] * 6 + [C.POINTER(C.c_int)]
     return L
 
 
-def split(L, mode, d, I, S, T, part_k, shared_stream, ns, n64, n128, G, dyn):
+def split(L, mode, d, I, S, T, part_k, shared_stream, ns, n64, n128, G, dyn, fp8=0):
     rows = []
     for b in range(G):
         out = (C.c_int * 24)()
-        L.moesd_test_stream_schedule(mode, d, I, S, T, part_k, shared_stream, ns, n64, n128, G, b, dyn, out)
+        L.moesd_test_stream_schedule(mode, d, I, S, T, part_k, shared_stream, ns, n64, n128, G, b, dyn, fp8, out)
         rows.append(list(out))
     return np.array(rows)
 
 
-def check(L, mode, d, I, S, T, part_k, shared_stream, ns, n64, n128, G, dyn):
-    r = split(L, mode, d, I, S, T, part_k, shared_stream, ns, n64, n128, G, dyn)
+def check(L, mode, d, I, S, T, part_k, shared_stream, ns, n64, n128, G, dyn, fp8=0):
+    r = split(L, mode, d, I, S, T, part_k, shared_stream, ns, n64, n128, G, dyn, fp8)
     label = dict(mode=mode, d=d, I=I, S=S, T=T, ns=ns, n64=n64, n128=n128, G=G, dyn=dyn)
     parts = -(-S // part_k) if (mode == 1 and S > 0) else 1
     for ci, (n_e, rows_per) in enumerate(((n128, 128), (n64, 64))):
@@ -50,7 +50,7 @@ def check(L, mode, d, I, S, T, part_k, shared_stream, ns, n64, n128, G, dyn):
         assert (taken == 1).all(), (label, "wide class", rows_per)
         # where the shared expert is
         want_sh = 0
-        if S > 0 and ((ci == 1 and 16 < T <= 64) or (ci == 0 and T > 64 and shared_stream)):
+        if S > 0 and not fp8 and ((ci == 1 and 16 < T <= 64) or (ci == 0 and T > 64 and shared_stream)):
             want_sh = per_s * parts * (-(-T // rows_per) if ci == 0 else 1)
         assert n_sh == want_sh, (label, ci)
     # the small line: fixed ranges are consecutive, start at 0 and end where the drawn part begins
@@ -65,6 +65,8 @@ def check(L, mode, d, I, S, T, part_k, shared_stream, ns, n64, n128, G, dyn):
     assert pos == n_stat, label
     want_small = ns * r[0, 17] + (r[0, 16] * parts if (S > 0 and T <= 16) else 0)
     assert n_tiles == want_small, label
+    srows = 64 if fp8 else 32          # weight rows of a small tile
+    assert r[0, 17] == (-(-I // (srows // 2)) if mode == 0 else -(-d // srows)), label
     if dyn_on:
         assert dyn and n_units >= G and pool0 % ut == 0
         end = pool0
@@ -111,8 +113,11 @@ def test_random_splits(sched):
             n64 = n128 = 0
         if rng.random() < 0.2:
             ns = 0
+        fp8 = int(rng.random() < 0.3)
+        if fp8:
+            n64 = n128 = 0          # 8-bit weights have no wide classes: the plan lists none
         check(sched, int(rng.integers(0, 2)), d, I, S, T, part_k, int(rng.integers(0, 2)), ns, n64, n128, G,
-              int(rng.integers(0, 2)))
+              int(rng.integers(0, 2)), fp8)
 
 
 def test_long_small_line_is_drawn_and_balanced(sched):
