@@ -45,13 +45,19 @@ def layer_bytes(shape, n_active, T):
 def gate_up_bytes(shape, n_active, T):
     """Algorithmic bytes of the gate/up kernel: the gate and up matrices of the
     activated experts and of the shared expert once, tokens in, activations out."""
-    w = (n_active * 2 * shape.d * shape.inter + 2 * shape.d * shape.shared_inter) * 2
+    esz = shape.weight_bytes_per_element
+    w = (n_active * 2 * shape.d * shape.inter + 2 * shape.d * shape.shared_inter) * esz
+    if esz == 1:   # one fp32 scale per weight row
+        w += (n_active * 2 * shape.inter + 2 * shape.shared_inter) * 4
     act = T * shape.d * 2 + (T * shape.top_k * shape.inter + T * shape.shared_inter) * 2
     return w + act
 
 
 def down_bytes(shape, n_active, T):
-    w = (n_active * shape.d * shape.inter + shape.d * shape.shared_inter) * 2
+    esz = shape.weight_bytes_per_element
+    w = (n_active * shape.d * shape.inter + shape.d * shape.shared_inter) * esz
+    if esz == 1:
+        w += (n_active * shape.d + (shape.d if shape.shared_inter else 0)) * 4
     act = (T * shape.top_k * shape.inter + T * shape.shared_inter) * 2 \
         + (T * shape.top_k * shape.d + (T * shape.d if shape.shared_inter else 0)) * 4
     return w + act

@@ -942,7 +942,8 @@ static hipError_t launch_stream(int mode, const StreamArgs &a, hipStream_t s) {
   const long per_s = mode == MODE_GATE_UP ? (a.S + srows / 2 - 1) / (srows / 2) : (a.d + srows - 1) / srows;
   const long parts = (mode == MODE_DOWN && a.S > 0) ? (a.S + a.part_k - 1) / a.part_k : 1;
   const long e_max = (long)a.T * a.K < a.E ? (long)a.T * a.K : a.E;
-  const long small_max = e_max * per_r + ((a.S > 0 && a.T <= SMALL_M) ? per_s * parts : 0);
+  const long small_max = e_max * per_r + ((a.S > 0 && (a.T <= SMALL_M || (a.fp8 && a.shared_stream)))
+                                              ? per_s * parts * ((a.T + SMALL_M - 1) / SMALL_M) : 0);
   const bool dyn = DYN_STATIC_PCT < 100 && small_max * nkb_s >= (long)DYN_MIN_SLOTS * n_cu &&
                    small_max >= (long)DYN_MIN_TILES * n_cu;
   const int which = (a.fp8 ? 4 : 0) + mode * 2 + (dyn ? 1 : 0);

@@ -319,9 +319,15 @@ int32_t run_forward(const moesd_layer_desc *desc, const moesd_weights *wt, const
   a.I = desc->inter;
   a.S = desc->shared_inter;
   a.T = T;
-  // 8-bit weights: the streaming kernels keep the shared expert only up to 16 tokens
-  a.shared_stream = fp8 ? (T <= 16 ? 1 : 0)
-                        : shared_expert_streams(T, desc->d, desc->shared_inter, ws.part_k, desc->top_k, desc->E, n_cu);
+  // 8-bit weights have no wide streaming classes: above 16 tokens the shared expert either passes
+  // through the small class once per 16 tokens (its weights stream that often) or goes to the tiled
+  // kernels; the latter when its 128-row tiles there would fill at least half the chip, or beyond 128 tokens
+  if (fp8) {
+    const long tiles = (long)((desc->shared_inter + 127) / 128) * ((T + 255) / 256);
+    a.shared_stream = (T <= 16 || (T <= PLAN_BIG_MAX_ROWS && 2 * tiles < n_cu)) ? 1 : 0;
+  } else {
+    a.shared_stream = shared_expert_streams(T, desc->d, desc->shared_inter, ws.part_k, desc->top_k, desc->E, n_cu);
+  }
   // experts with at most 128 rows stream (8-bit weights: at most 16); the others are tiled
   MOESD_TRY(launch_gate_up(a, s))
   if (tiled) {

@@ -74,7 +74,8 @@ MOESD_SCHED_FN void unit_range(const ClassCfg &c, int u, int &t0, int &t1) {
 struct SchedIn {
   int mode;                  // MODE_GATE_UP or MODE_DOWN
   int d, I, S, T, part_k;    // layer shape, tokens, k-part length of the shared down projection
-  int shared_stream;         // the streaming kernels take the shared expert also above 128 tokens
+  int shared_stream;         // the streaming kernels take the shared expert also above 128 tokens (8-bit
+                             // weights: above 16 tokens, in token blocks of 16 through the small class)
   int n_small_e, n_b64_e, n_b128_e;  // experts with 1..16, 17..64, 65..128 rows
   int G, bid;                // workgroups, this workgroup
   int dyn_allowed;           // the launched kernel can draw units
@@ -102,7 +103,8 @@ MOESD_SCHED_FN void stream_schedule(const SchedIn &in, int32_t *ctr, StreamSched
   cs.per_s = gu ? (in.S + srows / 2 - 1) / (srows / 2) : (in.d + srows - 1) / srows;
   c64.per_r = c128.per_r = gu ? (in.I + WHROWS - 1) / WHROWS : (in.d + 2 * WHROWS - 1) / (2 * WHROWS);
   c64.per_s = c128.per_s = gu ? (in.S + WHROWS - 1) / WHROWS : (in.d + 2 * WHROWS - 1) / (2 * WHROWS);
-  cs.n_sh = (has_shared && in.T <= SMALL_M) ? cs.per_s * parts : 0;
+  cs.n_sh = (has_shared && (in.T <= SMALL_M || (in.fp8 && in.shared_stream)))
+                ? cs.per_s * parts * ((in.T + SMALL_M - 1) / SMALL_M) : 0;
   c64.n_sh = (has_shared && !in.fp8 && in.T > SMALL_M && in.T <= W64_TB) ? c64.per_s * parts : 0;
   c128.n_sh = (has_shared && !in.fp8 && in.T > W64_TB && in.shared_stream)
                   ? c128.per_s * parts * ((in.T + W128_TB - 1) / W128_TB) : 0;

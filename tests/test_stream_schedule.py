@@ -63,7 +63,7 @@ def check(L, mode, d, I, S, T, part_k, shared_stream, ns, n64, n128, G, dyn, fp8
         assert stride == 1 and n_mine >= 0 and id0 == pos, (label, b, id0, pos)
         pos += n_mine
     assert pos == n_stat, label
-    want_small = ns * r[0, 17] + (r[0, 16] * parts if (S > 0 and T <= 16) else 0)
+    want_small = ns * r[0, 17] + (r[0, 16] * parts * -(-T // 16) if (S > 0 and (T <= 16 or (fp8 and shared_stream))) else 0)
     assert n_tiles == want_small, label
     srows = 64 if fp8 else 32          # weight rows of a small tile
     assert r[0, 17] == (-(-I // (srows // 2)) if mode == 0 else -(-d // srows)), label
