@@ -408,6 +408,81 @@ def fit_models(shape, rows, moesd):
     return out
 
 
+def device_fp8_weights(shape, torch, synth, np):
+    """E4M3 expert weights drawn on the device (timing only: values do not affect time); the router, which
+    decides the routing, is the canonical one.  Gaussian draws scaled so that a row's 3.5-sigma lands on 448."""
+    dev = "cuda:0"
+    g = torch.Generator(device=dev)
+    g.manual_seed(shape.seed + 8)
+    r = synth.make_router(shape)
+    sh = synth.make_shared(dataclasses_replace(shape, shared_inter=0))
+    w = {"w_router": torch.from_numpy(r["w_router"].view(np.int16)).to(dev), "router_bias": None,
+         "w_shared_gate": None}
+    if shape.shared_gate:
+        w["w_shared_gate"] = torch.from_numpy(synth.normal_bf16(shape.seed, "w_shared_gate", 0, (shape.d,), 0.02)
+                                              .view(np.int16)).to(dev)
+
+    def codes(rows, cols):
+        out = torch.empty((rows, cols), dtype=torch.uint8, device=dev)
+        step = max(1, (1 << 26) // cols)
+        for r0 in range(0, rows, step):
+            n = min(step, rows - r0)
+            out[r0:r0 + n] = (torch.randn(n, cols, device=dev, generator=g) * 128.0).clamp_(-448.0, 448.0) \
+                .to(torch.float8_e4m3fn).view(torch.uint8)
+        return out
+
+    E, I, d, S = shape.E, shape.inter, shape.d, shape.shared_inter
+    for name, rows, cols, fan in (("w_gate", E * I, d, d), ("w_up", E * I, d, d), ("w_down", E * d, I, I),
+                                  ("ws_gate", S, d, d), ("ws_up", S, d, d), ("ws_down", d, S, S)):
+        if rows == 0 or cols == 0:
+            w[name] = w[name + "_scale"] = None
+            continue
+        w[name] = codes(rows, cols)
+        w[name + "_scale"] = torch.full((rows,), float(fan) ** -0.5 / 128.0, dtype=torch.float32, device=dev)
+    del sh
+    return w
+
+
+def dataclasses_replace(shape, **kw):
+    import dataclasses
+    return dataclasses.replace(shape, **kw)
+
+
+def fp8_points(shape, torch, moesd, synth, np, Ts, steps, bf16_us):
+    """The same layer with its expert weights as E4M3 codes and one fp32 scale per output row: layer time against
+    the bf16 layer's and against the floor of the expert-loading term at one byte per weight (Appendix C.2)."""
+    q = dataclasses_replace(shape, name=shape.name + "-fp8", weight_format=1)
+    dw = device_fp8_weights(q, torch, synth, np)
+    run = Runner.__new__(Runner)
+    run.torch, run.moesd, run.shape = torch, moesd, q
+    run.desc = moesd.make_desc(q)
+    n_rep = 2 if q.E * q.expert_bytes > 4e9 else 3
+    run.reps = [dw] + [{k: (None if v is None else v.clone()) for k, v in dw.items()} for _ in range(n_rep - 1)]
+    run.wstructs = [moesd.make_weights(r) for r in run.reps]
+    run.stream = torch.cuda.current_stream().cuda_stream
+    rows = []
+    for T in Ts:
+        r, _ = measure_point(run, q, T, 0, steps, max(5, steps // 3), point=100 * T)
+        r.pop("B"), r.pop("gamma")
+        r["bf16_us"] = bf16_us.get(T)
+        if r["bf16_us"]:
+            r["speedup_over_bf16"] = round(r["bf16_us"] / r["us"], 3)
+        rows.append(r)
+    out = {"workload": f"{shape.name}-shaped layer, E4M3 expert weights with row scales (router from the seeded "
+                       "generator, expert codes drawn on the device: timing only)",
+           "k2_min_us_per_expert": round(q.expert_bytes / (HBM_PEAK_GBS * 1e9) * 1e6, 3), "points": rows}
+    if len(rows) >= 2 and rows[-1]["n_active"] > rows[0]["n_active"]:
+        k2 = (rows[-1]["us"] - rows[0]["us"]) / (rows[-1]["n_active"] - rows[0]["n_active"])
+        out["k2_us_per_expert"] = round(k2, 3)
+        out["k2_over_k2_min"] = round(k2 / out["k2_min_us_per_expert"], 3)
+    log(f"[bench] {q.name}: " + ", ".join(f"T={r['T']}: {r['us']:.0f} us (bf16 {r['bf16_us']}, layer {r['layer_hbm_frac']:.2f} "
+                                            f"of the HBM peak on 1-byte weights)" for r in rows)
+        + (f"; k2 = {out['k2_us_per_expert']} us per expert = {out['k2_over_k2_min']} x its floor" if "k2_us_per_expert" in out else ""))
+    del run, dw
+    torch.cuda.empty_cache()
+    return out
+
+
 def mfma_points(run, shape, Ts, steps=8, warmup=3):
     """Compute-bound points: layer and gate/up kernel against the bf16 MFMA peak."""
     from paper_2505_19645_amd import synth
@@ -456,6 +531,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--replicas", type=int, default=0)
     ap.add_argument("--no-mfma-point", action="store_true", help="skip the compute-bound extension points")
+    ap.add_argument("--no-fp8", action="store_true", help="skip the points with E4M3 expert weights")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (known traffic) for scaling rocprofv3 --pmc byte counters")
     args = ap.parse_args()
@@ -564,14 +640,30 @@ def main():
         assert ref["n_active"] == head["n_active"]
 
     # ---- the headline shape's sweep, then the other shapes -------------------------
-    configs, sweeps, fits, mfma = [], {}, {}, {}
+    configs, sweeps, fits, mfma, fp8 = [], {}, {}, {}, {}
+    FP8_TS = (1, 16, 64)
+
+    def bf16_times(run_, sh_, rows_):
+        """bf16 layer times at the token counts of the fp8 comparison (from the sweep where it has them)."""
+        have = {}
+        for c in rows_ or []:
+            if c["gamma"] == 0:
+                have[c["T"]] = c["us"]
+        for t in FP8_TS:
+            if t not in have:
+                have[t] = measure_point(run_, sh_, t, 0, args.curve_steps, 6, stages=False)[0]["us"]
+        return have
+
     if pts:
         sweeps[shape.name] = sweep(run, shape, pts, args.curve_steps)
         fits[shape.name] = fit_models(shape, sweeps[shape.name], moesd)
     if shape.name in MFMA_POINTS and not args.no_mfma_point:
         mfma[shape.name] = mfma_points(run, shape, MFMA_POINTS[shape.name])
+    head_bf16 = bf16_times(run, shape, sweeps.get(shape.name)) if not args.no_fp8 else None
     del run, host_w
     torch.cuda.empty_cache()
+    if not args.no_fp8:
+        fp8[shape.name] = fp8_points(shape, torch, moesd, synth, np, FP8_TS, args.curve_steps, head_bf16)
 
     if args.others == "all":
         for name in synth.PRESET_ORDER[1:]:
@@ -611,8 +703,11 @@ def main():
                 orun.wstructs = [k[1] for k in keep]
             if name in MFMA_POINTS and not args.no_mfma_point:
                 mfma[name] = mfma_points(orun, sh, MFMA_POINTS[name])
+            o_bf16 = bf16_times(orun, sh, sweeps.get(name)) if not args.no_fp8 else None
             del orun, ow
             torch.cuda.empty_cache()
+            if not args.no_fp8:
+                fp8[name] = fp8_points(sh, torch, moesd, synth, np, FP8_TS, args.curve_steps, o_bf16)
     log(f"[bench] whole run {time.time() - t_start:.0f}s")
 
     result = {
@@ -626,7 +721,7 @@ def main():
                    "weight_replicas": n_rep, "cold_weights": True},
         "roofline": roofline, "cpu_baseline": cpu, "layer": layer, "stages_us": head["stages_us"],
         "routing_share": head["routing_share"], "spread_us": spread_us,
-        "configs": configs, "sweeps": sweeps, "fits": fits, "mfma_points": mfma,
+        "configs": configs, "sweeps": sweeps, "fits": fits, "mfma_points": mfma, "fp8_weights": fp8,
     }
     print(json.dumps(result), flush=True)
 
