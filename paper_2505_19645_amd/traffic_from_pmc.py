@@ -7,7 +7,8 @@ Usage (after the two profiling runs, each made with `--calibrate-copy`):
 key = "<preset>/B<B>/g<gamma>/skew<skew>" as bench.py builds it.
 
 Both counters tick in units whose size is taken from a plain 1 GiB device copy in the same
-run (1 GiB read, 1 GiB written): factor = 2^30 / counter value of one copy dispatch.
+run (1 GiB read, 1 GiB written): factor = 2^30 / counter value of one copy dispatch.  bench.py
+makes that copy before anything else, so it is the first device-to-device copy of the run.
 """
 from __future__ import annotations
 
@@ -22,11 +23,15 @@ OUT = os.path.join(HERE, "measured_traffic.json")
 
 
 def per_kernel(path, counter):
-    vals = defaultdict(list)
+    """-> {kernel name: [counter values in dispatch order]}"""
+    rows = []
     with open(path) as f:
         for r in csv.DictReader(f):
             if r["Counter_Name"] == counter:
-                vals[r["Kernel_Name"]].append(float(r["Counter_Value"]))
+                rows.append((int(r["Dispatch_Id"]), r["Kernel_Name"], float(r["Counter_Value"])))
+    vals = defaultdict(list)
+    for _, name, v in sorted(rows):
+        vals[name].append(v)
     return vals
 
 
@@ -41,10 +46,10 @@ def main():
     fetch_csv, write_csv, key = sys.argv[1:4]
     fetch = per_kernel(fetch_csv, "FETCH_SIZE")
     write = per_kernel(write_csv, "WRITE_SIZE")
-    # the calibration copy: the largest device-to-device copy of the run is bench.py's
-    # 1 GiB tensor copy (torch issues it through the runtime's copy kernel)
-    f_copy = max(pick(fetch, "copyBuffer"))
-    w_copy = max(pick(write, "copyBuffer"))
+    # the calibration copy: the first device-to-device copy of the run is bench.py's 1 GiB tensor
+    # copy (torch issues it through the runtime's copy kernel); it is repeated three times
+    f_copy = sorted(pick(fetch, "copyBuffer")[:3])[1]
+    w_copy = sorted(pick(write, "copyBuffer")[:3])[1]
     f_unit, w_unit = 2.0 ** 30 / f_copy, 2.0 ** 30 / w_copy
     out = {"fetch_unit_bytes": f_unit, "write_unit_bytes": w_unit}
     for name, needle in (("gate_up", "expert_stream_kernel<0,"), ("down", "expert_stream_kernel<1,")):
