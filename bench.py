@@ -344,15 +344,54 @@ def measure_point(run, shape, B, gamma, steps, warmup, point=None, stages=True):
     return out, x
 
 
-def sweep(run, shape, pts, steps):
+SWEEP_FIELDS = ["sweep", "B", "gamma", "T", "us", "n_active", "N_model", "Texp_model", "layer_hbm_frac", "roofline_us",
+                "roofline_frac"]
+
+
+class SweepLog:
+    """Optional CSV of every sweep point, written as the run goes; a later run with the same file takes the
+    points it already holds from it instead of measuring them again (an interrupted sweep resumes)."""
+
+    def __init__(self, path):
+        import csv
+        self.path, self.have = path, {}
+        if path and os.path.exists(path):
+            with open(path, newline="") as f:
+                for r in csv.DictReader(f):
+                    self.have[(r["sweep"], int(r["B"]), int(r["gamma"]))] = r
+        if path and not self.have:
+            with open(path, "w", newline="") as f:
+                csv.writer(f).writerow(SWEEP_FIELDS)
+
+    def get(self, key, b, g):
+        r = self.have.get((key, b, g))
+        if r is None:
+            return None
+        out = {k: (int(r[k]) if k in ("B", "gamma", "T", "n_active") else float(r[k])) for k in SWEEP_FIELDS[1:]}
+        return out
+
+    def put(self, key, row):
+        if not self.path:
+            return
+        import csv
+        with open(self.path, "a", newline="") as f:
+            csv.writer(f).writerow([key] + [row[k] for k in SWEEP_FIELDS[1:]])
+
+
+def sweep(run, shape, pts, steps, log_csv=None, key=None):
     """Layer time over a (B, gamma) grid: us, measured and modelled activated experts, roofline fraction,
     and the layer-level target efficiency t(B) / t(B (gamma + 1)) (Sec. 3.1) where the gamma = 0 point exists."""
     rows = []
+    key = key or shape.name
     for (b, g) in pts:
-        r, _ = measure_point(run, shape, b, g, steps, max(5, steps // 3), stages=False)
-        r["Texp_model"] = round(run.moesd.moesd_expected_tokens_per_expert(shape.E, shape.top_k, r["T"]), 2)
-        for k in ("layer_bytes", "layer_GBps", "max_rows_per_expert"):
-            r.pop(k)
+        r = log_csv.get(key, b, g) if log_csv else None
+        if r is None:
+            r, _ = measure_point(run, shape, b, g, steps, max(5, steps // 3), stages=False)
+            r["Texp_model"] = round(run.moesd.moesd_expected_tokens_per_expert(shape.E, shape.top_k, r["T"]), 2)
+            for k in ("layer_bytes", "layer_GBps", "max_rows_per_expert"):
+                r.pop(k)
+            if log_csv:
+                log_csv.put(key, r)
         rows.append(r)
     by = {(c["B"], c["gamma"]): c["us"] for c in rows}
     for c in rows:
@@ -532,6 +571,8 @@ def main():
     ap.add_argument("--replicas", type=int, default=0)
     ap.add_argument("--no-mfma-point", action="store_true", help="skip the compute-bound extension points")
     ap.add_argument("--no-fp8", action="store_true", help="skip the points with E4M3 expert weights")
+    ap.add_argument("--sweep-csv", default="", help="write every sweep point to this CSV as the run goes; points the "
+                                                    "file already holds are not measured again (resume)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (known traffic) for scaling rocprofv3 --pmc byte counters")
     args = ap.parse_args()
@@ -565,6 +606,7 @@ def main():
 
     threads = min(16, os.cpu_count() or 1)
     t_start = time.time()
+    sweep_log = SweepLog(args.sweep_csv) if args.sweep_csv else None
 
     def curve_points(sh):
         if args.curve == "none":
@@ -655,7 +697,7 @@ def main():
         return have
 
     if pts:
-        sweeps[shape.name] = sweep(run, shape, pts, args.curve_steps)
+        sweeps[shape.name] = sweep(run, shape, pts, args.curve_steps, sweep_log)
         fits[shape.name] = fit_models(shape, sweeps[shape.name], moesd)
     if shape.name in MFMA_POINTS and not args.no_mfma_point:
         mfma[shape.name] = mfma_points(run, shape, MFMA_POINTS[shape.name])
@@ -679,7 +721,7 @@ def main():
                 f"{c['gate_up']['hbm_frac']:.3f}, down {c['down']['hbm_frac']:.3f} of the HBM peak, routing "
                 f"{c['routing_share']:.1%} of the layer")
             if opts:
-                sweeps[name] = sweep(orun, sh, opts, args.curve_steps)
+                sweeps[name] = sweep(orun, sh, opts, args.curve_steps, sweep_log)
                 fits[name] = fit_models(sh, sweeps[name], moesd)
             if name == "qwen2-57b-a14b":
                 # the skewed-routing variant: per-expert logit bias N(0, 1.5), same weights otherwise
@@ -697,7 +739,7 @@ def main():
                     f"(uniform model {c2['N_model']}), layer {c2['layer_hbm_frac']:.3f} of the HBM peak")
                 if opts:
                     sk_pts = [(b, g) for (b, g) in opts if g in (0, 3)]
-                    sweeps[name + "/skew1.5"] = sweep(orun, sh, sk_pts, args.curve_steps)
+                    sweeps[name + "/skew1.5"] = sweep(orun, sh, sk_pts, args.curve_steps, sweep_log, key=name + "/skew1.5")
                 for r, (b0, w0) in zip(orun.reps, keep):
                     r["router_bias"] = b0
                 orun.wstructs = [k[1] for k in keep]
