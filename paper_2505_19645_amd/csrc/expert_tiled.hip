@@ -6,14 +6,18 @@
 // into blocks of 256 rows and handled here: a workgroup computes a 256-token x
 // 256-weight-row tile (128 w_gate rows + the same 128 w_up rows with SwiGLU
 // fused, or 256 w_down rows), marching over the contraction dimension in
-// 64-element stages through two LDS buffers, with v_mfma_f32_32x32x16_bf16.
+// 64-element stages through two LDS buffers, with v_mfma_f32_16x16x32_bf16.
 //
+//  * The card runs these kernels against its power limit, not its clock limit (registers-only
+//    MFMA loops on random bf16 data sustain 0.80 of the 2.5 PFLOP/s peak with the 32x32x16
+//    shape and 0.91 with 16x16x32, whose accumulator traffic per flop is half), hence the
+//    16x16x32 shape although it needs twice the instructions.
 //  * Eight waves (two per SIMD, so one multiplies while the other waits) as
-//    2 (row halves) x 4 (token quarters); a wave owns 2 x 2 32-row tiles (gate
-//    and up rows 64wr..64wr+63, or two 64-row groups of w_down) x two 32-token
-//    tiles = 8 accumulator tiles; 131 flops per byte brought into LDS.
+//    2 (row halves) x 4 (token quarters); a wave owns 2 x 4 16-row tiles (gate
+//    and up rows 64wr..64wr+63, or two 64-row groups of w_down) x four 16-token
+//    tiles = 32 accumulator tiles; 131 flops per byte brought into LDS.
 //  * Operands travel global memory -> registers -> LDS: every lane fetches eight
-//    16-byte pieces of a stage (whole 128-byte lines per row) one stage ahead of
+//    16-byte pieces of a stage (whole 128-byte lines per row) about one stage ahead of
 //    the multiplication and stores them when the other buffer has been read.
 //    (Measured on this chip: the same traffic through global_load_lds tops out at
 //    about two thirds of this path's rate, and 64-byte row pieces at less again.)
@@ -23,9 +27,10 @@
 //    different 16-byte bank groups.
 //  * A wave whose 64 token rows are all padding multiplies nothing (it still loads and
 //    stores its share of the stages): a block of at most 128 rows costs half the MFMA time.
-//  * The MFMA fragments of a 16-element half step are double-buffered in
-//    registers: the LDS reads of the next half step run under the MFMAs of the
-//    current one; one s_barrier per stage.
+//  * A stage is two steps of 32 contraction elements.  The 8 weight fragments of a step are
+//    refilled in place, each right after the four MFMAs that read it, with the fragment of the
+//    next step; the 4 token fragments alternate between two register sets.  One s_barrier per
+//    stage, between its two steps.
 //  * Persistent launch, one workgroup per CU.  Four workgroups on one XCD form a team
 //    that walks runs of 4 consecutive tiles in lockstep (the token blocks of one expert
 //    that share a weight tile meet in that XCD's L2).  Normally whole runs are dealt
@@ -37,10 +42,9 @@
 //    adds the partials of every cut tile in k order (the same order on every run) and
 //    runs the epilogue.  No atomics, no fences, nobody waits for anybody.
 //
-// MFMA operand use (32x32x16): lane l = 32*q + r supplies 8 consecutive
-// contraction elements (piece 2*s + q of half step s) of weight row r as A and of
-// token row r as B; it receives, for token r, output features
-// 8*g + 4*q + c (g, c = 0..3) in accumulator register 4*g + c.
+// MFMA operand use (16x16x32): lane l = 16*q + r supplies 8 consecutive
+// contraction elements (piece 4*s + q of step s) of weight row r as A and of
+// token row r as B; it receives, for token r, output features 4*q .. 4*q+3.
 #include <type_traits>
 
 #include "common.h"
@@ -51,18 +55,15 @@
 #define T_ROW_BYTES 128
 #define T_A_BYTES (TBN * T_ROW_BYTES)  // 32 KB
 #define T_B_BYTES (TBM * T_ROW_BYTES)  // 32 KB
-#define T_STAGE_BYTES (T_A_BYTES + T_B_BYTES)
-#ifndef T_WAVES
-#define T_WAVES 8  // 8: two waves per SIMD, 128 x 64 per wave; 4: one wave per SIMD, 128 x 128 per wave
-#endif
+// LDS: NAB weight buffers, then 2 token buffers.  bf16 weights come from HBM by LDS-DMA and get three
+// buffers (two stages of lead); the tokens come from L2 and get two.  E4M3 weights pass through registers:
+// two buffers.
+#define T_NAB(fp8) ((fp8) ? 2 : 3)
+#define T_LDS_BYTES(fp8) (T_NAB(fp8) * T_A_BYTES + 2 * T_B_BYTES)
+#define T_WAVES 8
 #define T_THREADS (64 * T_WAVES)
 #define T_LW (4096 / T_THREADS)  // 16-byte pieces per lane per stage
-#define T_NT (16 / T_WAVES)      // 32-token tiles per wave
 #define T_LROWS (512 / T_WAVES)  // rows of one operand a loader wave fetches
-#ifndef T_AHEAD
-#define T_AHEAD 1  // stages of global loads in flight in registers (2 needs more registers than either variant has)
-#endif
-#define TILED_LDS_BYTES (2 * T_STAGE_BYTES)
 
 enum { TMODE_GATE_UP = 0, TMODE_DOWN = 1 };
 
@@ -75,10 +76,16 @@ __device__ __forceinline__ void t_barrier() {
   asm volatile("s_barrier" ::: "memory");
 }
 
-__device__ __forceinline__ f32x16 mfma32(u32x4 a, u32x4 b, f32x16 c) {
-  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b),
-                                                 c, 0, 0, 0);
+// Global memory -> LDS without passing through registers: lane l's 16 bytes land at lds_base + 16 l
+// (lds_base wave-uniform, in m0).  The compiler does not track m0 across inline asm (it warns on seeing it
+// in a clobber list; the clobber is what keeps any value of its own out of m0 here).
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void t_dma16(const void *g, uint32_t lds_base) {
+  const uint32_t b = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_base);
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(b) : "memory", "m0");
 }
+#pragma clang diagnostic pop
 
 // Launch-wide schedule, filled by the host.
 struct TiledSched {
@@ -88,7 +95,7 @@ struct TiledSched {
   float *partials;        // [2 * workgroups of the main kernel] slots of T_THREADS * 128 floats
   int n_teams;            // teams of the main kernel (its grid / 4)
 };
-#define T_SLOT_FLOATS (T_THREADS * 64 * T_NT)
+#define T_SLOT_FLOATS (T_THREADS * 128)  // a workgroup's accumulators
 
 // The schedule both kernels derive from the plan: units of (run, stage), two regions.
 struct TiledWork {
@@ -133,8 +140,8 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
   const int n_large = w.n_large;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wr = wave & 1, wt = wave >> 1;  // wt: token part, 0 .. T_WAVES/2 - 1
-  const int r32 = lane & 31, q = lane >> 5;
+  const int wr = wave & 1, wt = wave >> 1;  // weight row half, token quarter
+  const int r16 = lane & 15, q = lane >> 4;
   const int n_shared_entries = sc.n_shared_entries;
   int rt, entry;
   if (shared_region) {
@@ -202,286 +209,242 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
   const int rv1 = (MODE == TMODE_GATE_UP) ? rv0 : max(1, min(128, n_rows - i0 - 128));  // second half
   const bool second_ok = (MODE == TMODE_GATE_UP) || (n_rows - i0 > 128);
 
-  // ---- loader: a stage is 512 rows x 128 bytes; wave w fetches rows 64(w&3).. of the weight
-  // rows (w < 4) or of the token rows (w >= 4), instruction i rows 8i..8i+7, lane l row
-  // (l >> 3), piece (l & 7)
-  const int lrow = lane >> 3, piece = lane & 7;
-  const bool load_b = wave >= T_WAVES / 2;
-  const int lw = wave % (T_WAVES / 2);  // which T_LROWS rows of the operand
-  const char *wbase;    // wave-uniform: first row this wave may touch, at the k origin
-  uint32_t off[T_LW];   // this lane's rows (clamped into the valid rows), in bytes from wbase
-  if (!load_b) {
-    const bool second = lw * T_LROWS >= 128;
-    const char *base = (second && second_ok) ? A1 : A0;
-    const int rv = second ? rv1 : rv0;
-    wbase = base + (size_t)i0 * a_stride;
+  // ---- loader: a stage is 256 weight rows + 256 token rows x 128 bytes.  Wave w moves weight rows
+  // 32w .. 32w+31 of the tile's 256 (waves 4..7: the second half) and token rows 32w .. 32w+31, 8 rows
+  // per instruction: lane l row (l >> 3), LDS position (l & 7) of that row.  The data travel by LDS-DMA
+  // (no registers, no LDS store instructions); the DMA writes a wave's 64 x 16 bytes linearly, so the
+  // swizzle is done on the way in: position p of row r receives piece p ^ ((r >> 1) & 7).  E4M3 weights
+  // cannot take that road (they are widened to bf16 on the way): their 8-byte pieces go through
+  // registers, rows 16w' + 8i + (l >> 3) of each half for the wave pair.
+  const int lrow = lane >> 3, pos = lane & 7;
+  const bool second = wave >= T_WAVES / 2;
+  const char *abase = ((second && second_ok) ? A1 : A0) + (size_t)i0 * a_stride;  // wave-uniform
+  const char *bbase = reinterpret_cast<const char *>(use_map ? B : B + (size_t)row0 * b_stride);
+  const int rvh = second ? rv1 : rv0;
+  uint32_t offA[4], offB[4];  // this lane's rows (clamped into the valid rows), in bytes
 #pragma unroll
-    for (int i = 0; i < T_LW; ++i) {
-      const int hrow = (lw * T_LROWS) % 128 + 8 * i + lrow;
-      off[i] = (uint32_t)min(hrow, rv - 1) * (uint32_t)a_stride;
-    }
-  } else {
-    wbase = reinterpret_cast<const char *>(use_map ? B : B + (size_t)row0 * b_stride);
-#pragma unroll
-    for (int i = 0; i < T_LW; ++i) {
-      const int row = min(T_LROWS * lw + 8 * i + lrow, m - 1);
-      const int tr = use_map ? a.row_token[row0 + row] : row;
-      off[i] = (uint32_t)tr * (uint32_t)(b_stride * 2);
-    }
+  for (int i = 0; i < 4; ++i) {
+    const int hrow = 32 * (wave & 3) + 8 * i + lrow;  // row inside its half
+    offA[i] = (uint32_t)min(hrow, rvh - 1) * (uint32_t)a_stride;
+    const int row = min(32 * wave + 8 * i + lrow, m - 1);
+    const int tr = use_map ? a.row_token[row0 + row] : row;
+    offB[i] = (uint32_t)tr * (uint32_t)(b_stride * 2);
   }
-  // this lane's eight LDS store positions (stage buffer 0)
-  const int srow0 = (load_b ? TBN : 0) + T_LROWS * lw + lrow;
-  auto load_stage = [&](int s, u32x4 (&pre)[T_LW]) __attribute__((always_inline)) {
-    // a piece past the end of the rows is pulled back inside (it is zeroed before the store)
-    const uint32_t k8 = (uint32_t)min(s * TBK + piece * 8, klen - 8);  // this lane's 8 contraction elements
-    if (FP8 && !load_b) {  // 8 codes = 8 bytes; widened when they are stored
-#pragma unroll
-      for (int i = 0; i < T_LW; ++i) {
-        const u32x2 v = *reinterpret_cast<const u32x2 *>(wbase + (off[i] + k8));
-        pre[i][0] = v[0];
-        pre[i][1] = v[1];
-      }
+  // rows 32w + 8i + lrow: (row >> 1) & 7 = (4i + (lrow >> 1)) & 7, two values by the parity of i
+  const int pc0 = pos ^ ((lrow >> 1) & 7), pc1 = pos ^ ((4 + (lrow >> 1)) & 7);
+  const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
+  // a piece past the end of the rows is pulled back inside (and zeroed in LDS once it has landed)
+  auto k_off = [&](int s, int pc) __attribute__((always_inline)) {
+    return (uint32_t)min(s * TBK + pc * 8, klen - 8);
+  };
+  u32x4 pre[4];  // (E4M3) this lane's weight codes of one stage on their way to LDS: 4 x 8 bytes
+  constexpr int NAB = T_NAB(FP8);
+  constexpr int B_BASE = NAB * T_A_BYTES;
+  // instruction ii of the 4 that bring a wave's share of the weights of stage s into weight buffer ab
+  auto issue_a = [&](int s, int ab, int ii) __attribute__((always_inline)) {
+    const uint32_t kk = k_off(s, (ii & 1) ? pc1 : pc0);
+    if constexpr (FP8) {
+      const u32x2 v = *reinterpret_cast<const u32x2 *>(abase + (offA[ii] + kk));
+      pre[ii][0] = v[0];
+      pre[ii][1] = v[1];
     } else {
-#pragma unroll
-      for (int i = 0; i < T_LW; ++i) pre[i] = *reinterpret_cast<const u32x4 *>(wbase + (off[i] + 2u * k8));
+      t_dma16(abase + (offA[ii] + 2u * kk), lds0 + ab * T_A_BYTES + (32 * wave + 8 * ii) * T_ROW_BYTES);
     }
   };
-  auto store_stage = [&](int s, int buf, u32x4 (&pre)[T_LW], bool ragged) __attribute__((always_inline)) {
-    if (FP8 && !load_b) {  // E4M3 -> bf16 is exact
+  // the same for the tokens of stage s into token buffer bb
+  auto issue_b = [&](int s, int bb, int ii) __attribute__((always_inline)) {
+    const uint32_t kk = k_off(s, (ii & 1) ? pc1 : pc0);
+    t_dma16(bbase + (offB[ii] + 2u * kk), lds0 + B_BASE + bb * T_B_BYTES + (32 * wave + 8 * ii) * T_ROW_BYTES);
+  };
+  // What remains to do before the barrier that publishes stage s (weights in buffer ab): (E4M3) widen and
+  // store the weight pieces; wait for the DMA (all but the `later` youngest instructions, which belong to a
+  // later stage); zero the weight pieces past the end of a ragged contraction.
+  auto finish_stage = [&](int s, int ab, bool rag, auto later) __attribute__((always_inline)) {
+    constexpr int LATER = decltype(later)::value;
+    char *dst = smem + ab * T_A_BYTES + (32 * wave + lrow) * T_ROW_BYTES + (pos << 4);
+    if constexpr (FP8) {
 #pragma unroll
-      for (int i = 0; i < T_LW; ++i) {
+      for (int i = 0; i < 4; ++i) {
         const uint32_t c0 = pre[i][0], c1 = pre[i][1];
-        pre[i][0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(c0, 1.0f, false));
-        pre[i][1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(c0, 1.0f, true));
-        pre[i][2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(c1, 1.0f, false));
-        pre[i][3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(c1, 1.0f, true));
+        u32x4 v;
+        v[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(c0, 1.0f, false));
+        v[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(c0, 1.0f, true));
+        v[2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(c1, 1.0f, false));
+        v[3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(c1, 1.0f, true));
+        const int pc = (i & 1) ? pc1 : pc0;
+        if (rag && s * TBK + pc * 8 >= klen) v = (u32x4){0u, 0u, 0u, 0u};
+        *reinterpret_cast<u32x4 *>(dst + 8 * i * T_ROW_BYTES) = v;
       }
     }
-    if (ragged && s * TBK + piece * 8 >= klen) {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(FP8 ? 0 : LATER) : "memory");
+    if (!FP8 && rag) {
 #pragma unroll
-      for (int i = 0; i < T_LW; ++i) pre[i] = (u32x4){0u, 0u, 0u, 0u};
-    }
-#pragma unroll
-    for (int i = 0; i < T_LW; ++i) {
-      const int row = srow0 + 8 * i;
-      *reinterpret_cast<u32x4 *>(smem + buf * T_STAGE_BYTES + row * T_ROW_BYTES + ((piece ^ ((row >> 1) & 7)) << 4)) =
-          pre[i];
+      for (int i = 0; i < 4; ++i) {
+        const int pc = (i & 1) ? pc1 : pc0;
+        if (s * TBK + pc * 8 >= klen) *reinterpret_cast<u32x4 *>(dst + 8 * i * T_ROW_BYTES) = (u32x4){0u, 0u, 0u, 0u};
+      }
     }
   };
 
-  f32x16 acc[4][T_NT];  // [weight tile: 2 of the first half, 2 of the second][token tile]
+  f32x4 acc[8][4];  // [weight tile: 4 of the first half, 4 of the second][token tile]
 #pragma unroll
-  for (int h = 0; h < 4; ++h)
+  for (int h = 0; h < 8; ++h)
 #pragma unroll
-    for (int t = 0; t < T_NT; ++t)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[h][t][v] = 0.f;
+    for (int t = 0; t < 4; ++t) acc[h][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  // Operand fragments of one 16-element half step: 4 weight tiles and 2 token tiles.
-  const int key = (r32 >> 1) & 7;
-  const char *pa0 = smem + (64 * wr + r32) * T_ROW_BYTES;
-  const char *pb0 = smem + T_A_BYTES + (32 * T_NT * wt + r32) * T_ROW_BYTES;
-  auto read_half = [&](int buf, int hs, u32x4 (&fa)[4], u32x4 (&fb)[T_NT]) __attribute__((always_inline)) {
-    const int so = buf * T_STAGE_BYTES + (((2 * hs + q) ^ key) << 4);
-#pragma unroll
-    for (int h = 0; h < 4; ++h)
-      fa[h] = *reinterpret_cast<const u32x4 *>(pa0 + so + ((h >> 1) * 128 + (h & 1) * 32) * T_ROW_BYTES);
-#pragma unroll
-    for (int t = 0; t < T_NT; ++t) fb[t] = *reinterpret_cast<const u32x4 *>(pb0 + so + t * 32 * T_ROW_BYTES);
+  // Operand fragments of one 32-element step: 8 weight tiles and 4 token tiles of 16 rows.
+  const int key = (r16 >> 1) & 7;
+  const char *pa0 = smem + (64 * wr + r16) * T_ROW_BYTES;
+  const char *pb0 = smem + B_BASE + (64 * wt + r16) * T_ROW_BYTES;
+  auto frag_off = [&](int ks) __attribute__((always_inline)) { return ((4 * ks + q) ^ key) << 4; };
+  auto read_a = [&](int ab, int ks, int h) __attribute__((always_inline)) {
+    return *reinterpret_cast<const u32x4 *>(pa0 + ab * T_A_BYTES + frag_off(ks) + ((h >> 2) * 128 + (h & 3) * 16) * T_ROW_BYTES);
   };
-  auto mfma_half = [&](const u32x4 (&fa)[4], const u32x4 (&fb)[T_NT]) __attribute__((always_inline)) {
-#pragma unroll
-    for (int h = 0; h < 4; ++h)
-#pragma unroll
-      for (int t = 0; t < T_NT; ++t) acc[h][t] = mfma32(fa[h], fb[t], acc[h][t]);
+  auto read_b = [&](int bb, int ks, int t) __attribute__((always_inline)) {
+    return *reinterpret_cast<const u32x4 *>(pb0 + bb * T_B_BYTES + frag_off(ks) + t * 16 * T_ROW_BYTES);
   };
 
   const int nkb = (klen + TBK - 1) / TBK;          // this tile's own stage count (<= nkb_reg)
   const int s0 = min(st0, nkb), s1 = min(st1, nkb);  // the part of the piece that exists
   const bool ragged = (klen % TBK) != 0 && s1 == nkb;  // then the piece's last stage is zero-padded
-  u32x4 pre[T_AHEAD][T_LW], fa0[4], fb0[T_NT], fa1[4], fb1[T_NT];
-  const int n = s1 - s0;  // stages of this piece; stage s0 + j lives in LDS buffer j & 1 and in pre[j % T_AHEAD]
-  // One stage (four half steps) from buffer j & 1.  PI: which register set holds stage j+1.
-  // Stage j+1 goes from registers to the other buffer (its last readers passed the previous
-  // barrier), the loads of stage j+1+T_AHEAD are issued into the freed registers; after the
-  // barrier the first fragments of stage j+1 are read under the last MFMAs of stage j.
-  auto step = [&](int j, auto pi, auto has_next, auto has_load) __attribute__((always_inline)) {
-    constexpr int PI = decltype(pi)::value;
-    constexpr bool HN = decltype(has_next)::value, HL = decltype(has_load)::value;
-    const int buf = j & 1;
-#if defined(T_PHASES)
-    // phases, fenced so that the compiler cannot sink the reads below the MFMAs
-    mfma_half(fa0, fb0);
-    __builtin_amdgcn_sched_barrier(0);
-    read_half(buf, 2, fa0, fb0);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_half(fa1, fb1);
-    __builtin_amdgcn_sched_barrier(0);
-    read_half(buf, 3, fa1, fb1);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_half(fa0, fb0);
-    __builtin_amdgcn_sched_barrier(0);
-    if constexpr (HN) {
-      store_stage(s0 + j + 1, buf ^ 1, pre[PI], ragged && j + 2 == n);
-      if constexpr (HL) load_stage(s0 + j + 1 + T_AHEAD, pre[PI]);
-      t_barrier();  // stage j+1 is in LDS for everyone; everyone has stage j in registers
-      read_half(buf ^ 1, 0, fa0, fb0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_half(fa1, fb1);
-    __builtin_amdgcn_sched_barrier(0);
-    if constexpr (HN) read_half(buf ^ 1, 1, fa1, fb1);
-    __builtin_amdgcn_sched_barrier(0);
-#else
-    // Every other instruction is issued in the shadow of an MFMA (scheduling groups:
-    // 0x008 MFMA, 0x020 VMEM read, 0x100 DS read, 0x200 DS write).  The LDS stores are
-    // spread one per MFMA: bunching them was measured 7 % slower.
-    constexpr int MH = 4 * T_NT;  // MFMAs of a half step
-    constexpr int RH = 4 + T_NT;  // fragment reads of a half step
-    mfma_half(fa0, fb0);
-    if constexpr (HN) store_stage(s0 + j + 1, buf ^ 1, pre[PI], ragged && j + 2 == n);
+  u32x4 fa[8], fb[2][4];
+  const int n = s1 - s0;  // stages of this piece; stage s0 + j lives in weight buffer j % NAB and token buffer j & 1
+  // One stage: two steps of 32 MFMAs; on entry fa and fb[0] hold the fragments of its first step.  Each
+  // weight fragment is refilled in place right after the four MFMAs that read it (one weight fragment
+  // against the four token fragments), the token fragments alternate between two register sets.  In the
+  // shadow of the first step the fragments of the second are read; then the next stage must have landed,
+  // and the barrier; in the shadow of the second step the fragments of the next stage's first step are
+  // read and loads are issued into the buffers just left: the tokens of stage j + 2, then the weights of
+  // stage j + NAB.  (Scheduling groups: 0x008 MFMA, 0x100 DS read.)
+  auto mfma_group = [&](int h, int set) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < MH; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      if (HN) __builtin_amdgcn_sched_group_barrier(0x200, T_LW / MH, 0);
-    }
+    for (int t = 0; t < 4; ++t) acc[h][t] = mfma16(fa[h], fb[set][t], acc[h][t]);
+  };
+  auto group_shadow = [&](bool reads, bool two) __attribute__((always_inline)) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    if (reads) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    if (reads && two) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
     __builtin_amdgcn_sched_barrier(0);
-    read_half(buf, 2, fa0, fb0);
-    mfma_half(fa1, fb1);
-    if constexpr (HL) load_stage(s0 + j + 1 + T_AHEAD, pre[PI]);
-#pragma unroll
-    for (int i = 0; i < RH; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-    }
-#pragma unroll
-    for (int i = 0; i < MH - RH; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      if (HL) __builtin_amdgcn_sched_group_barrier(0x020, T_LW / (MH - RH), 0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    read_half(buf, 3, fa1, fb1);
-    mfma_half(fa0, fb0);
-#pragma unroll
-    for (int i = 0; i < RH; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-    }
-    __builtin_amdgcn_sched_group_barrier(0x008, MH - RH, 0);
-    __builtin_amdgcn_sched_barrier(0);
-    if constexpr (HN) {
-      t_barrier();  // stage j+1 is in LDS for everyone; everyone has stage j in registers
-      read_half(buf ^ 1, 0, fa0, fb0);
-    }
-    mfma_half(fa1, fb1);
-    if constexpr (HN) read_half(buf ^ 1, 1, fa1, fb1);
-#pragma unroll
-    for (int i = 0; i < 2 * RH - MH; ++i) {  // 2 RH reads over MH MFMAs: two each at first, then one each
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      if (HN) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-    }
-#pragma unroll
-    for (int i = 0; i < 2 * (MH - RH); ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      if (HN) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-#endif
   };
   using std::integral_constant;
-  using P0 = integral_constant<int, 0>;
-#if T_AHEAD > 1
-  using P1 = integral_constant<int, T_AHEAD - 1>;
-#endif
   using Y = std::true_type;
   using N = std::false_type;
-  // A wave whose 64 token rows are all padding (a block with few rows: the last one of an expert, or an
-  // expert with 65..128 rows) only keeps loading and storing its share of the stages and the barriers.
-  // With the usual placement of a workgroup's waves (wave i on SIMD i mod 4) a block of at most 128
-  // rows then leaves one multiplying wave per SIMD instead of two.
-  const bool idle_wave = 32 * T_NT * wt >= m;
-  auto step_idle = [&](int j, auto pi, auto has_next, auto has_load) __attribute__((always_inline)) {
-    constexpr int PI = decltype(pi)::value;
-    constexpr bool HN = decltype(has_next)::value, HL = decltype(has_load)::value;
-    if constexpr (HN) {
-      store_stage(s0 + j + 1, (j & 1) ^ 1, pre[PI], ragged && j + 2 == n);
-      if constexpr (HL) load_stage(s0 + j + 1 + T_AHEAD, pre[PI]);
-      t_barrier();
+  // ab: weight buffer of stage j.  H1, H2, H3: stages j+1, j+2, j+3 exist in this piece.  At the wait,
+  // the youngest instructions in flight are the 4 weight loads of stage j + 2 (3 weight buffers), if any.
+  auto step = [&](int j, int ab, auto h1, auto h2, auto h3, auto mult) __attribute__((always_inline)) {
+    constexpr bool H1 = decltype(h1)::value, H2 = decltype(h2)::value, H3 = decltype(h3)::value;
+    constexpr bool MULT = decltype(mult)::value;  // false: a wave whose token rows are all padding
+    constexpr bool HA = NAB == 3 ? H3 : H2;       // the weights to issue in this stage exist
+    const int bb = j & 1;
+    const int ab1 = ab + 1 == NAB ? 0 : ab + 1;
+    if constexpr (MULT) {
+#pragma unroll
+      for (int h = 0; h < 8; ++h) {
+        mfma_group(h, 0);
+        fa[h] = read_a(ab, 1, h);
+        if (h < 4) fb[1][h] = read_b(bb, 1, h);
+        group_shadow(true, h < 4);
+      }
+    }
+    if constexpr (H1) {
+      finish_stage(s0 + j + 1, ab1, ragged && j + 2 == n, integral_constant<int, (NAB == 3 && H2) ? 4 : 0>{});
+      t_barrier();  // the next stage is in LDS for everyone; everyone has read this one
+    }
+    if constexpr (MULT) {
+#pragma unroll
+      for (int h = 0; h < 8; ++h) {
+        mfma_group(h, 1);
+        if constexpr (H1) {
+          fa[h] = read_a(ab1, 0, h);
+          if (h < 4) fb[0][h] = read_b(bb ^ 1, 0, h);
+        }
+        group_shadow(H1, h < 4);
+        if (h < 4) {
+          if constexpr (H2) issue_b(s0 + j + 2, bb, h);
+        } else {
+          if constexpr (HA) issue_a(s0 + j + NAB, ab, h - 4);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if constexpr (H2) issue_b(s0 + j + 2, bb, i);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if constexpr (HA) issue_a(s0 + j + NAB, ab, i);
     }
   };
-  if (!FIXUP && n > 0) {
+  // A wave whose 64 token rows are all padding (a block with few rows: the last one of an expert, or an
+  // expert with 65..128 rows) only keeps moving its share of the stages and the barriers.
+  // With the usual placement of a workgroup's waves (wave i on SIMD i mod 4) a block of at most 128
+  // rows then leaves one multiplying wave per SIMD instead of two.
+  const bool idle_wave = 64 * wt >= m;
+  // the stages of a piece; the last ones are straight-line sequences chosen by how many remain, so the
+  // steady state is branch-free
+  auto run_stages = [&](auto mult) __attribute__((always_inline)) {
+    constexpr bool MULT = decltype(mult)::value;
+    if constexpr (MULT) {
 #pragma unroll
-    for (int a2 = 0; a2 < T_AHEAD; ++a2)
-      if (a2 < n) load_stage(s0 + a2, pre[a2]);
-    t_barrier();  // everyone is done with the LDS of the previous piece
-    store_stage(s0, 0, pre[0], ragged && n == 1);
-    if (T_AHEAD < n) load_stage(s0 + T_AHEAD, pre[0]);
-    t_barrier();
-    int j = 0;
-#if T_AHEAD == 1
-    if (idle_wave) {
-      for (; j + 2 < n; ++j) step_idle(j, P0{}, Y{}, Y{});
-      if (j + 1 < n) {
-        step_idle(j, P0{}, Y{}, N{});
-        ++j;
-      }
-      step_idle(j, P0{}, N{}, N{});
-    } else {
-#else
-    {
-#endif
-    read_half(0, 0, fa0, fb0);
-    read_half(0, 1, fa1, fb1);
-    // steady state: branch-free, so the compiler's wait counts stay exact; the last stages are
-    // straight-line sequences chosen by how many remain (no loop around differently shaped steps)
-#if T_AHEAD == 1
-    for (; j + 2 < n; ++j) step(j, P0{}, Y{}, Y{});
-    if (j + 1 < n) {
-      step(j, P0{}, Y{}, N{});
+      for (int h = 0; h < 8; ++h) fa[h] = read_a(0, 0, h);
+#pragma unroll
+      for (int t = 0; t < 4; ++t) fb[0][t] = read_b(0, 0, t);
+    }
+    int j = 0, ab = 0;
+    for (; j + 3 < n; ++j) {
+      step(j, ab, Y{}, Y{}, Y{}, mult);
+      ab = ab + 1 == NAB ? 0 : ab + 1;
+    }
+    if (j + 2 < n) {
+      step(j, ab, Y{}, Y{}, N{}, mult);
+      ab = ab + 1 == NAB ? 0 : ab + 1;
       ++j;
     }
-    step(j, P0{}, N{}, N{});
-#else
-    for (; j + 4 < n; j += 2) {
-      step(j, P1{}, Y{}, Y{});
-      step(j + 1, P0{}, Y{}, Y{});
+    if (j + 1 < n) {
+      step(j, ab, Y{}, N{}, N{}, mult);
+      ab = ab + 1 == NAB ? 0 : ab + 1;
+      ++j;
     }
-    switch (n - j) {  // j is even here
-      case 4:
-        step(j, P1{}, Y{}, Y{});
-        step(j + 1, P0{}, Y{}, N{});
-        step(j + 2, P1{}, Y{}, N{});
-        step(j + 3, P0{}, N{}, N{});
-        break;
-      case 3:
-        step(j, P1{}, Y{}, N{});
-        step(j + 1, P0{}, Y{}, N{});
-        step(j + 2, P1{}, N{}, N{});
-        break;
-      case 2:
-        step(j, P1{}, Y{}, N{});
-        step(j + 1, P0{}, N{}, N{});
-        break;
-      default:
-        step(j, P1{}, N{}, N{});
-        break;
+    step(j, ab, N{}, N{}, N{}, mult);
+  };
+  if (!FIXUP && n > 0) {
+    t_barrier();  // everyone is done with the LDS of the previous piece
+    // in flight before the loop: stage 0; the tokens of stage 1; the weights of stages 1 .. NAB-1
+#pragma unroll
+    for (int i = 0; i < 4; ++i) issue_b(s0, 0, i);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) issue_a(s0, 0, i);
+    if constexpr (FP8) finish_stage(s0, 0, ragged && n == 1, integral_constant<int, 0>{});
+    if (1 < n) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) issue_b(s0 + 1, 1, i);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) issue_a(s0 + 1, 1, i);
     }
-#endif
+    if constexpr (!FP8) {
+      if (2 < n) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) issue_a(s0 + 2, 2, i);
+        finish_stage(s0, 0, false, integral_constant<int, 12>{});
+      } else if (1 < n) {
+        finish_stage(s0, 0, false, integral_constant<int, 8>{});
+      } else {
+        finish_stage(s0, 0, ragged, integral_constant<int, 0>{});
+      }
     }
+    t_barrier();
+    if (idle_wave) run_stages(N{});
+    else run_stages(Y{});
   }
 
   // ---- a tile cut by the schedule: its pieces meet in memory, the second kernel finishes it --
   if (!FIXUP && !(st0 == 0 && st1 == nkb_reg)) {
     f32x4 *mine = reinterpret_cast<f32x4 *>(sc.partials + (size_t)slot * T_SLOT_FLOATS);
 #pragma unroll
-    for (int h = 0; h < 4; ++h)
+    for (int h = 0; h < 8; ++h)
 #pragma unroll
-      for (int t = 0; t < T_NT; ++t)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const f32x16 &v = acc[h][t];
-          mine[((h * T_NT + t) * 4 + g) * T_THREADS + tid] = (f32x4){v[4 * g], v[4 * g + 1], v[4 * g + 2], v[4 * g + 3]};
-        }
+      for (int t = 0; t < 4; ++t) mine[(h * 4 + t) * T_THREADS + tid] = acc[h][t];
     return;
   }
   if (FIXUP) {
@@ -502,65 +465,56 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
       const int sl = 2 * wg + (ts >= run_base ? 0 : 1);  // its first piece, or its last
       const f32x4 *theirs = reinterpret_cast<const f32x4 *>(sc.partials + (size_t)sl * T_SLOT_FLOATS);
 #pragma unroll
-      for (int h = 0; h < 4; ++h)
+      for (int h = 0; h < 8; ++h)
 #pragma unroll
-        for (int t = 0; t < T_NT; ++t)
-#pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const f32x4 p = theirs[((h * T_NT + t) * 4 + g) * T_THREADS + tid];
-#pragma unroll
-            for (int c = 0; c < 4; ++c) acc[h][t][4 * g + c] += p[c];
-          }
+        for (int t = 0; t < 4; ++t) acc[h][t] += theirs[(h * 4 + t) * T_THREADS + tid];
     }
   }
 
-  // ---- epilogue: lane holds, for token (64wt + 32t + r32), features 8g + 4q + c -------------
-  // weight tile h: half (h >> 1), rows 64wr + 32(h & 1) .. +31 of that half
+  // ---- epilogue: lane holds, for token (64wt + 16t + r16), features 4q .. 4q+3 of every weight tile ------
+  // weight tile h: half (h >> 2), rows 64wr + 16(h & 3) .. +15 of that half
 #pragma unroll
-  for (int t = 0; t < T_NT; ++t) {
-    const int j = 32 * T_NT * wt + 32 * t + r32;
+  for (int t = 0; t < 4; ++t) {
+    const int j = 64 * wt + 16 * t + r16;
     if (j < m) {
       const size_t orow = (size_t)(row0 + j);
 #pragma unroll
-      for (int hh = 0; hh < 2; ++hh)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int f = 64 * wr + 32 * hh + 8 * g + 4 * q;  // feature inside the 128 of a half
-          if (MODE == TMODE_GATE_UP) {
-            const int i = i0 + f;
-            if (i < out_n) {
-              f32x4 cg = {1.f, 1.f, 1.f, 1.f}, cu = {1.f, 1.f, 1.f, 1.f};
-              if (FP8) {  // one scale per weight row = per output feature
-                cg = *reinterpret_cast<const f32x4 *>(sc0 + i);
-                cu = *reinterpret_cast<const f32x4 *>(sc1 + i);
-              }
-              uint32_t hb[4];
-#pragma unroll
-              for (int c = 0; c < 4; ++c)
-                hb[c] = f32_to_bf16_bits(silu_f32(acc[hh][t][4 * g + c] * cg[c]) * (acc[2 + hh][t][4 * g + c] * cu[c]));
-              u32x2 o;
-              o[0] = hb[0] | (hb[1] << 16);
-              o[1] = hb[2] | (hb[3] << 16);
-              *reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(out) + orow * out_n + i) = o;
+      for (int hh = 0; hh < 4; ++hh) {
+        const int f = 64 * wr + 16 * hh + 4 * q;  // feature inside the 128 of a half
+        if (MODE == TMODE_GATE_UP) {
+          const int i = i0 + f;
+          if (i < out_n) {
+            f32x4 cg = {1.f, 1.f, 1.f, 1.f}, cu = {1.f, 1.f, 1.f, 1.f};
+            if (FP8) {  // one scale per weight row = per output feature
+              cg = *reinterpret_cast<const f32x4 *>(sc0 + i);
+              cu = *reinterpret_cast<const f32x4 *>(sc1 + i);
             }
-          } else {
-            float *y = reinterpret_cast<float *>(out);
+            uint32_t hb[4];
 #pragma unroll
-            for (int h2 = 0; h2 < 2; ++h2) {
-              const int i = i0 + 128 * h2 + f;
-              if (i < out_n) {
-                const f32x16 &v = acc[2 * h2 + hh][t];
-                f32x4 o = {v[4 * g], v[4 * g + 1], v[4 * g + 2], v[4 * g + 3]};
-                if (FP8) {
-                  const f32x4 cd = *reinterpret_cast<const f32x4 *>(sc0 + i);
+            for (int c = 0; c < 4; ++c)
+              hb[c] = f32_to_bf16_bits(silu_f32(acc[hh][t][c] * cg[c]) * (acc[4 + hh][t][c] * cu[c]));
+            u32x2 o;
+            o[0] = hb[0] | (hb[1] << 16);
+            o[1] = hb[2] | (hb[3] << 16);
+            *reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(out) + orow * out_n + i) = o;
+          }
+        } else {
+          float *y = reinterpret_cast<float *>(out);
 #pragma unroll
-                  for (int c = 0; c < 4; ++c) o[c] *= cd[c];
-                }
-                *reinterpret_cast<f32x4 *>(y + orow * out_n + i) = o;
+          for (int h2 = 0; h2 < 2; ++h2) {
+            const int i = i0 + 128 * h2 + f;
+            if (i < out_n) {
+              f32x4 o = acc[4 * h2 + hh][t];
+              if (FP8) {
+                const f32x4 cd = *reinterpret_cast<const f32x4 *>(sc0 + i);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) o[c] *= cd[c];
               }
+              *reinterpret_cast<f32x4 *>(y + orow * out_n + i) = o;
             }
           }
         }
+      }
     }
   }
 }
@@ -695,7 +649,7 @@ static hipError_t launch_tiled(int mode, const StreamArgs &a, float *partials, h
   int dev = 0, n_cu = 0;
   hipError_t e = current_device(&dev, &n_cu);
   if (e != hipSuccess) return e;
-  e = raise_dynamic_lds_limit(lds_once[which], dev, reinterpret_cast<const void *>(mains[which]), TILED_LDS_BYTES);
+  e = raise_dynamic_lds_limit(lds_once[which], dev, reinterpret_cast<const void *>(mains[which]), T_LDS_BYTES(a.fp8));
   if (e != hipSuccess) return e;
   // (row offsets are kept as 32-bit byte counts inside the kernel: T * d * 2 < 2^32, checked by the caller,
   // which also decides whether these kernels have anything to do at this T)
@@ -714,7 +668,7 @@ static hipError_t launch_tiled(int mode, const StreamArgs &a, float *partials, h
   sc.partials = partials;
   const unsigned grid = (unsigned)tiled_grid_for(n_cu);
   sc.n_teams = (int)grid / 4;
-  hipLaunchKernelGGL(mains[which], dim3(grid), dim3(T_THREADS), TILED_LDS_BYTES, s, a, sc);
+  hipLaunchKernelGGL(mains[which], dim3(grid), dim3(T_THREADS), T_LDS_BYTES(a.fp8), s, a, sc);
   hipLaunchKernelGGL(fixups[which], dim3(grid), dim3(T_THREADS), 0, s, a, sc);
   return hipGetLastError();
 }

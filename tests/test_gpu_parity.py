@@ -54,12 +54,13 @@ def class_of(m):
     return next(i for i, (lo, hi) in enumerate(ROW_CLASSES) if lo <= m <= hi)
 
 
-def tokens_from_permutation(oracle, shape, w, x, budget=20):
+def tokens_from_permutation(oracle, shape, w, x, budget=22):
     """Tokens to compare at a size where the oracle cannot evaluate them all, chosen from the oracle's own
     routing so that every kind of row position is hit: for each class of expert size (1..16, 17..64, 65..128,
     more rows) the first and last row of its smallest and of its largest expert; the rows on both sides of a
-    64-row block border and of a 256-row tile border; a token whose K experts lie in different classes; the
-    first and the last token."""
+    64-row block border, of a 256-row border (where the tiled kernels' waves pass from their first token tile
+    to their second) and of a 512-row block border; a token whose K experts lie in different classes; the first
+    and the last token."""
     T, K = x.shape[0], shape.top_k
     ids, _, _ = oracle.route(shape, x, w["w_router"], w.get("router_bias"))
     pr = oracle.permute(shape.E, K, ids)
@@ -77,6 +78,8 @@ def tokens_from_permutation(oracle, shape, w, x, budget=20):
         rows += [offsets[e] + 63, offsets[e] + 64]
         if counts[e] > 256:
             rows += [offsets[e] + 255, offsets[e] + 256, offsets[e] + 256 * ((counts[e] - 1) // 256) - 1]
+        if counts[e] > 512:
+            rows += [offsets[e] + 511, offsets[e] + 512]
     toks = [0, T - 1] + [int(perm[r]) // K for r in rows]
     for t in range(T):
         if len({class_of(counts[e]) for e in ids[t]}) > 1:
