@@ -123,9 +123,13 @@ __device__ __forceinline__ TiledWork tiled_work(const StreamArgs &a, const Tiled
   // Cutting runs costs a round trip of partial sums through memory and a second epilogue
   // pass: only worth it when whole runs would leave the busiest team more than 15 % above
   // the mean, or when at least half the teams would idle and every team still gets 32 stages.
-  const long per_team = (w.runs + w.n_teams - 1) / w.n_teams;
-  w.cut = (w.runs > w.n_teams && per_team * w.n_teams * 100 > w.runs * 115) ||
-          (2 * w.runs <= w.n_teams && w.W >= 32L * w.n_teams);  // half the teams idle, and long contractions
+  // (Whole runs are dealt region by region; the shared expert's runs are as long as its whole
+  // contraction, the routed experts' as theirs.)
+  const long nt = w.n_teams;
+  const long busiest = (w.runs_s + nt - 1) / nt * sc.nkb_s + (w.runs - w.runs_s + nt - 1) / nt * sc.nkb_r;
+  const bool mixed = w.runs_s > 0 && w.runs > w.runs_s && sc.nkb_s != sc.nkb_r;
+  w.cut = ((w.runs > nt || (mixed && w.W >= 8 * nt)) && busiest * nt * 100 > w.W * 115) ||
+          (2 * w.runs <= nt && w.W >= 32L * nt);  // half the teams idle, and long contractions
   return w;
 }
 // when runs are cut: first unit of team g's share (g = n_teams: one past the end)

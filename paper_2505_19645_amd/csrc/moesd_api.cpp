@@ -328,6 +328,17 @@ int32_t run_forward(const moesd_layer_desc *desc, const moesd_weights *wt, const
   } else {
     a.shared_stream = shared_expert_streams(T, desc->d, desc->shared_inter, ws.part_k, desc->top_k, desc->E, n_cu);
   }
+  // A shared expert that goes to the tiled kernels need not be split into k-parts: their own schedule cuts
+  // contractions where that balances the chip, and every extra part costs T * d * 4 bytes written by the
+  // down projection and read again by the combine.  That schedule counts every stage alike, though, and
+  // a stage of a half-empty token block is cheaper than one of the shared expert's full blocks, and it
+  // cuts only where there are many stages to share out: the parts go only where the routed experts'
+  // blocks are many and well filled (512 rows per expert on average).
+  int n_parts = ws.parts;
+  if (desc->shared_inter > 0 && !a.shared_stream && (long)T * desc->top_k >= 512L * desc->E) {
+    a.part_k = desc->shared_inter;
+    n_parts = 1;
+  }
   // experts with at most 128 rows stream (8-bit weights: at most 16); the others are tiled
   MOESD_TRY(launch_gate_up(a, s))
   if (tiled) {
@@ -337,7 +348,7 @@ int32_t run_forward(const moesd_layer_desc *desc, const moesd_weights *wt, const
   MOESD_TRY(launch_down(a, s))
   if (tiled) { MOESD_TRY(launch_down_tiled(a, ws.tiled_partials, s)) }
   MOESD_EVENT(3)
-  MOESD_TRY(launch_combine(ws.y, ws.ys, ws.parts, w, ws.gate, iv, T, desc->top_k, desc->d,
+  MOESD_TRY(launch_combine(ws.y, ws.ys, n_parts, w, ws.gate, iv, T, desc->top_k, desc->d,
                            (uint16_t *)out, out_f32, s))
   MOESD_EVENT(4)
 #undef MOESD_EVENT

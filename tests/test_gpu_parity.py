@@ -149,6 +149,10 @@ def test_many_rows_per_expert(gpu, oracle, shape, T):
     (LayerShape("cut-gate-up", d=192, E=1, top_k=1, inter=12800, shared_inter=6400, seed=35), 520),
     # many token blocks x row tiles of the down projection: cuts there
     (LayerShape("cut-down", d=2048, E=1, top_k=1, inter=192, seed=36), 8500),
+    # 600 rows per expert: the tiled shared expert is not split into k-parts, so its down projection is two
+    # runs of 512 stages beside routed runs of one stage; the runs are cut into the shares of all the teams,
+    # and the second kernel adds that many pieces
+    (LayerShape("cut-shared-down", d=512, E=1, top_k=1, inter=64, shared_inter=32768, seed=37), 600),
 ])
 def test_tiles_cut_by_the_schedule(gpu, oracle, shape, T):
     # On a 256-CU device the tiled kernels run 64 teams; with more runs of 4 tiles than teams and an
