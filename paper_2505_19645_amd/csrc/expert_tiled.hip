@@ -136,11 +136,14 @@ __device__ __forceinline__ TiledWork tiled_work(const StreamArgs &a, const Tiled
 __device__ __forceinline__ long tiled_team_start(const TiledWork &w, int g) { return (w.W * g) / w.n_teams; }
 
 // One piece: stages [st0, st1) of one tile (stage numbers in units of the region's nkb_reg).
-// FIXUP: no multiplication; the accumulators are the sum of the tile's stored pieces.
+// FIXUP: no multiplication; the accumulators are the sum of the tile's stored pieces, and the workgroup
+// finishes only token tile tq of every wave (a quarter of the tile: 32 accumulator registers instead of
+// 128, so that enough waves fit a CU to hide the latency of reading the pieces).
 template <int MODE, bool FIXUP, bool FP8>
 __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSched &sc, char *smem, bool shared_region,
                                             int tile, int st0, int st1, int nkb_reg, long run_base, int slot,
-                                            int team_member, const TiledWork &w) {
+                                            int team_member, const TiledWork &w, int tq = 0) {
+  constexpr int NT = FIXUP ? 1 : 4;  // token tiles held per wave
   const int n_large = w.n_large;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -213,6 +216,13 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
   const int rv1 = (MODE == TMODE_GATE_UP) ? rv0 : max(1, min(128, n_rows - i0 - 128));  // second half
   const bool second_ok = (MODE == TMODE_GATE_UP) || (n_rows - i0 > 128);
 
+  f32x4 acc[8][NT];  // [weight tile: 4 of the first half, 4 of the second][token tile]
+#pragma unroll
+  for (int h = 0; h < 8; ++h)
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[h][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  if constexpr (!FIXUP) {
   // ---- loader: a stage is 256 weight rows + 256 token rows x 128 bytes.  Wave w moves weight rows
   // 32w .. 32w+31 of the tile's 256 (waves 4..7: the second half) and token rows 32w .. 32w+31, 8 rows
   // per instruction: lane l row (l >> 3), LDS position (l & 7) of that row.  The data travel by LDS-DMA
@@ -289,12 +299,6 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
       }
     }
   };
-
-  f32x4 acc[8][4];  // [weight tile: 4 of the first half, 4 of the second][token tile]
-#pragma unroll
-  for (int h = 0; h < 8; ++h)
-#pragma unroll
-    for (int t = 0; t < 4; ++t) acc[h][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
   // Operand fragments of one 32-element step: 8 weight tiles and 4 token tiles of 16 rows.
   const int key = (r16 >> 1) & 7;
@@ -443,15 +447,16 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
   }
 
   // ---- a tile cut by the schedule: its pieces meet in memory, the second kernel finishes it --
-  if (!FIXUP && !(st0 == 0 && st1 == nkb_reg)) {
+  if (!(st0 == 0 && st1 == nkb_reg)) {
     f32x4 *mine = reinterpret_cast<f32x4 *>(sc.partials + (size_t)slot * T_SLOT_FLOATS);
 #pragma unroll
     for (int h = 0; h < 8; ++h)
 #pragma unroll
-      for (int t = 0; t < 4; ++t) mine[(h * 4 + t) * T_THREADS + tid] = acc[h][t];
+      for (int t = 0; t < NT; ++t) mine[(h * 4 + t) * T_THREADS + tid] = acc[h][t];
     return;
   }
-  if (FIXUP) {
+  }  // !FIXUP
+  if constexpr (FIXUP) {
     // contributors: the teams whose shares meet this run's units, in k order
     const int n_teams = w.n_teams;
     auto team_start = [&](int g) -> long { return tiled_team_start(w, g); };
@@ -469,16 +474,15 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
       const int sl = 2 * wg + (ts >= run_base ? 0 : 1);  // its first piece, or its last
       const f32x4 *theirs = reinterpret_cast<const f32x4 *>(sc.partials + (size_t)sl * T_SLOT_FLOATS);
 #pragma unroll
-      for (int h = 0; h < 8; ++h)
-#pragma unroll
-        for (int t = 0; t < 4; ++t) acc[h][t] += theirs[(h * 4 + t) * T_THREADS + tid];
+      for (int h = 0; h < 8; ++h) acc[h][0] += theirs[(h * 4 + tq) * T_THREADS + tid];
     }
   }
 
   // ---- epilogue: lane holds, for token (64wt + 16t + r16), features 4q .. 4q+3 of every weight tile ------
   // weight tile h: half (h >> 2), rows 64wr + 16(h & 3) .. +15 of that half
 #pragma unroll
-  for (int t = 0; t < 4; ++t) {
+  for (int tl = 0; tl < NT; ++tl) {
+    const int t = FIXUP ? tq : tl;  // which of the wave's four token tiles acc[.][tl] is
     const int j = 64 * wt + 16 * t + r16;
     if (j < m) {
       const size_t orow = (size_t)(row0 + j);
@@ -496,7 +500,7 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
             uint32_t hb[4];
 #pragma unroll
             for (int c = 0; c < 4; ++c)
-              hb[c] = f32_to_bf16_bits(silu_f32(acc[hh][t][c] * cg[c]) * (acc[4 + hh][t][c] * cu[c]));
+              hb[c] = f32_to_bf16_bits(silu_f32(acc[hh][tl][c] * cg[c]) * (acc[4 + hh][tl][c] * cu[c]));
             u32x2 o;
             o[0] = hb[0] | (hb[1] << 16);
             o[1] = hb[2] | (hb[3] << 16);
@@ -508,7 +512,7 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
           for (int h2 = 0; h2 < 2; ++h2) {
             const int i = i0 + 128 * h2 + f;
             if (i < out_n) {
-              f32x4 o = acc[4 * h2 + hh][t];
+              f32x4 o = acc[4 * h2 + hh][tl];
               if (FP8) {
                 const f32x4 cd = *reinterpret_cast<const f32x4 *>(sc0 + i);
 #pragma unroll
@@ -593,11 +597,12 @@ __global__ __launch_bounds__(T_THREADS) void expert_tiled_kernel(StreamArgs a, T
   }
 }
 
-// Finishes the tiles the main kernel's share boundaries cut.  Workgroup (g, member): if the
-// boundary between teams g and g+1 is the first one inside its run, sum that run's pieces.
+// Finishes the tiles the main kernel's share boundaries cut.  Workgroup (g, member, tq): if the
+// boundary between teams g and g+1 is the first one inside its run, sum that run's pieces for token
+// tile tq of every wave.
 template <int MODE, bool FP8>
 __global__ __launch_bounds__(T_THREADS) void expert_tiled_fixup_kernel(StreamArgs a, TiledSched sc) {
-  const int g = blockIdx.x / 4, member = blockIdx.x % 4;
+  const int tq = blockIdx.x & 3, g = blockIdx.x / 16, member = (blockIdx.x / 4) % 4;
   const TiledWork w = tiled_work(a, sc);
   if (w.W == 0 || !w.cut || g + 1 >= w.n_teams) return;
   const long b = tiled_team_start(w, g + 1);  // first unit of team g+1
@@ -611,7 +616,7 @@ __global__ __launch_bounds__(T_THREADS) void expert_tiled_fixup_kernel(StreamArg
   if (tiled_team_start(w, g) > run_base) return;  // an earlier boundary inside this run does the work
   const int tile = (int)(4 * (ur / nkb_reg) + member);
   if (tile >= (shared_region ? w.n_sh_tiles : w.n_r_tiles)) return;
-  tiled_piece<MODE, true, FP8>(a, sc, nullptr, shared_region, tile, 0, nkb_reg, nkb_reg, run_base, 0, member, w);
+  tiled_piece<MODE, true, FP8>(a, sc, nullptr, shared_region, tile, 0, nkb_reg, nkb_reg, run_base, 0, member, w, tq);
 }
 
 // The persistent grid: whole teams of 4 on each of the 8 XCDs, at most TILED_MAX_WGS workgroups
@@ -673,7 +678,7 @@ static hipError_t launch_tiled(int mode, const StreamArgs &a, float *partials, h
   const unsigned grid = (unsigned)tiled_grid_for(n_cu);
   sc.n_teams = (int)grid / 4;
   hipLaunchKernelGGL(mains[which], dim3(grid), dim3(T_THREADS), T_LDS_BYTES(a.fp8), s, a, sc);
-  hipLaunchKernelGGL(fixups[which], dim3(grid), dim3(T_THREADS), 0, s, a, sc);
+  hipLaunchKernelGGL(fixups[which], dim3(4 * grid), dim3(T_THREADS), 0, s, a, sc);
   return hipGetLastError();
 }
 
