@@ -265,8 +265,8 @@ __device__ __forceinline__ Entry load_entry(const StreamArgs &a, const Tables &t
 // first weight row of row tile rt (small tiles: 16 + 16 or 32 rows of bf16, 32 + 32 or 64 rows of 8-bit codes)
 template <int MODE, bool WIDE, bool FP8>
 __device__ __forceinline__ int tile_i0(int rt) {
-  if (MODE == MODE_GATE_UP) return WIDE ? rt * WHROWS : rt * (FP8 ? 32 : 16);
-  return WIDE ? rt * 2 * WHROWS : rt * (FP8 ? 64 : 32);
+  if (MODE == MODE_GATE_UP) return WIDE ? rt * (FP8 ? 2 : 1) * WHROWS : rt * (FP8 ? 32 : 16);
+  return WIDE ? rt * (FP8 ? 4 : 2) * WHROWS : rt * (FP8 ? 64 : 32);
 }
 
 // Per-lane source pointers of the DMA instructions this wave issues.
@@ -415,15 +415,33 @@ __device__ __forceinline__ void issue_slot(const LoadPtrs<CLS> &lp, const Entry 
     } else {
       const int w = sub - NTS;
       const char *base = (MODE == MODE_GATE_UP && w >= WNW / 2) ? en.a1 : en.a0;
-      const int first = (MODE == MODE_GATE_UP) ? 64 * (w % (WNW / 2)) : 64 * w;  // of the tile's rows in this matrix
-      const int rv = min((MODE == MODE_GATE_UP) ? WHROWS : 2 * WHROWS, en.n_rows - lp.i0);  // valid ones
+      if constexpr (!FP8) {
+        const int first = (MODE == MODE_GATE_UP) ? 64 * (w % (WNW / 2)) : 64 * w;  // of the tile's rows in this matrix
+        const int rv = min((MODE == MODE_GATE_UP) ? WHROWS : 2 * WHROWS, en.n_rows - lp.i0);  // valid ones
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int pair = wave * 8 + i;
-        const int r = 2 * pair + half;
-        const int row = lp.i0 + min(first + r, rv - 1);
-        dma16_stream(base + (size_t)row * en.a_stride + 2 * (((pos ^ (r & 15)) << 3) + koff(r)),
-                     slot_base + (uint32_t)pair * 1024u);
+        for (int i = 0; i < 8; ++i) {
+          const int pair = wave * 8 + i;
+          const int r = 2 * pair + half;
+          const int row = lp.i0 + min(first + r, rv - 1);
+          dma16_stream(base + (size_t)row * en.a_stride + 2 * (((pos ^ (r & 15)) << 3) + koff(r)),
+                       slot_base + (uint32_t)pair * 1024u);
+        }
+      } else {
+        // 8-bit codes: a weight slot is 128 rows of 256 bytes, four rows per instruction (lane l: row
+        // l >> 4 of the four, LDS position l & 15 of the row, which receives the row's piece
+        // (l & 15) ^ (row & 15) of 16 codes); wave w moves rows 32w .. 32w+31
+        const int first = (MODE == MODE_GATE_UP) ? 128 * (w % (WNW / 2)) : 128 * w;
+        const int rv = min((MODE == MODE_GATE_UP) ? 2 * WHROWS : 4 * WHROWS, en.n_rows - lp.i0);
+        const int sub4 = lane >> 4, p16 = lane & 15;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int quad = wave * 8 + i;
+          const int r = 4 * quad + sub4;
+          const int row = lp.i0 + min(first + r, rv - 1);
+          const int piece = p16 ^ (r & 15);
+          const int ko = full ? k0 : min(k0 + piece * 16, klen - 16) - piece * 16;
+          dma16_stream(base + (size_t)row * en.a_stride + (piece * 16 + ko), slot_base + (uint32_t)quad * 1024u);
+        }
       }
     }
   }
@@ -627,7 +645,7 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
     // in registers.  64-row class: the waves form 2 (row halves of a weight slot) x 2 (token halves) and a
     // wave multiplies 2 row tiles of every weight slot; 128-row class: wave w owns token rows 32w .. 32w+31
     // (token slot w >> 1) and multiplies all 4 row tiles of every weight slot.
-    constexpr int NRT = CLS == CLS_W128 ? 4 : 2;  // row tiles of a weight slot per wave
+    constexpr int NRT = (CLS == CLS_W128 || FP8) ? 4 : 2;  // row tiles of a weight slot per wave (8-bit codes: slots of 128 rows)
     u32x4 fbw[WIDE ? 2 : 1][WIDE ? 8 : 1];
     f32x4 accw[WIDE ? WNW : 1][WIDE ? NRT : 1][2];  // [weight slot][row tile of the wave][token tile of the wave]
 #pragma unroll
@@ -761,7 +779,10 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
               const char *pb = sb + (size_t)(tok_row + 16 * tt + r16) * ROW_BYTES;
 #pragma unroll
               for (int st = 0; st < 8; ++st) {
-                const int piece = 4 * st + q;
+                // bf16 weights: step st takes the 8 elements 32 st + 8 q ..; 8-bit weights: lane (r, q) holds the
+                // 16 codes 64 (st >> 1) + 16 q .. of its row per chunk, two operands once widened, which meet
+                // the token pieces 8 (st >> 1) + 2 q and the next
+                const int piece = FP8 ? 8 * (st >> 1) + 2 * q + (st & 1) : 4 * st + q;
                 fbw[tt][st] = *reinterpret_cast<const u32x4 *>(pb + ((piece ^ r16) << 4));
                 // ragged last block: pieces past the row's end hold bytes pulled back from inside it
                 if (kbase + piece * 8 >= cen.klen) fbw[tt][st] = (u32x4){0u, 0u, 0u, 0u};
@@ -807,6 +828,32 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
                   }
                 __builtin_amdgcn_sched_barrier(0);  // keeps the reads DEPTH - 1 chunks ahead, not more
               }
+            } else if constexpr (FP8) {
+              // 128 rows of 256 codes: the wave's 4 row tiles, 4 chunks of 64 contraction elements each
+#pragma unroll
+              for (int rtl = 0; rtl < NRT; ++rtl) {
+                const char *pa = sb + (size_t)(16 * (NRT * wr + rtl) + r16) * 256;
+                u32x4 codes[4];
+#pragma unroll
+                for (int ch = 0; ch < 4; ++ch)
+                  codes[ch] = *reinterpret_cast<const u32x4 *>(pa + (((4 * ch + q) ^ r16) << 4));
+#pragma unroll
+                for (int ch = 0; ch < 4; ++ch) {
+                  u32x4 lo, hi;
+#pragma unroll
+                  for (int dw = 0; dw < 2; ++dw) {
+                    lo[2 * dw] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(codes[ch][dw], 1.0f, false));
+                    lo[2 * dw + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(codes[ch][dw], 1.0f, true));
+                    hi[2 * dw] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(codes[ch][2 + dw], 1.0f, false));
+                    hi[2 * dw + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(codes[ch][2 + dw], 1.0f, true));
+                  }
+#pragma unroll
+                  for (int tt = 0; tt < 2; ++tt) {
+                    accw[w][rtl][tt] = mfma16(lo, fbw[tt][2 * ch], accw[w][rtl][tt]);
+                    accw[w][rtl][tt] = mfma16(hi, fbw[tt][2 * ch + 1], accw[w][rtl][tt]);
+                  }
+                }
+              }
             } else {
 #pragma unroll
               for (int rtl = 0; rtl < NRT; ++rtl) {
@@ -841,10 +888,29 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
 #pragma unroll
               for (int w = 0; w < WNW / 2; ++w)
 #pragma unroll
-                for (int rtl = 0; rtl < NRT; ++rtl)
-                  store_out4<MODE>(cen.out, cen.out_n, (size_t)(cen.row0 + j),
-                                   i0 + 64 * w + 16 * (NRT * wr + rtl) + 4 * q, WHROWS, accw[w][rtl][tt],
-                                   accw[w + WNW / 2][rtl][tt]);
+                for (int rtl = 0; rtl < NRT; ++rtl) {
+                  if constexpr (!FP8) {
+                    store_out4<MODE>(cen.out, cen.out_n, (size_t)(cen.row0 + j),
+                                     i0 + 64 * w + 16 * (NRT * wr + rtl) + 4 * q, WHROWS, accw[w][rtl][tt],
+                                     accw[w + WNW / 2][rtl][tt]);
+                  } else {
+                    // one scale per weight row = per output feature (both halves' rows exist or the store is skipped)
+                    const int i = i0 + 128 * w + 16 * (NRT * wr + rtl) + 4 * q;
+                    const int i1 = (MODE == MODE_GATE_UP) ? i : i + 2 * WHROWS;
+                    f32x4 v0 = accw[w][rtl][tt], v1 = accw[w + WNW / 2][rtl][tt];
+                    if (i < cen.out_n) {
+                      const f32x4 c0 = *reinterpret_cast<const f32x4 *>(cen.s0 + i);
+#pragma unroll
+                      for (int c = 0; c < 4; ++c) v0[c] *= c0[c];
+                    }
+                    if (i1 < cen.out_n) {
+                      const f32x4 c1 = *reinterpret_cast<const f32x4 *>(cen.s1 + i1);
+#pragma unroll
+                      for (int c = 0; c < 4; ++c) v1[c] *= c1[c];
+                    }
+                    store_out4<MODE>(cen.out, cen.out_n, (size_t)(cen.row0 + j), i, 2 * WHROWS, v0, v1);
+                  }
+                }
             }
           }
 #pragma unroll
@@ -897,7 +963,7 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
 
 // DYN: the variant that can draw units of small tiles from the counter (the host launches the
 // other one, which is a little quicker to start, when the small line is certainly too short for it).
-// FP8: expert weights are E4M3 codes with a scale per output row; only small tiles exist then.
+// FP8: expert weights are E4M3 codes with a scale per output row; small tiles and the 64-row wide class.
 template <int MODE, bool DYN, bool FP8>
 __global__ __launch_bounds__(STREAM_THREADS) void expert_stream_kernel(StreamArgs a,
                                                             const int32_t *__restrict__ plan,
@@ -914,16 +980,14 @@ __global__ __launch_bounds__(STREAM_THREADS) void expert_stream_kernel(StreamArg
   in.mode = MODE;
   in.d = a.d; in.I = a.I; in.S = a.S; in.T = a.T; in.part_k = a.part_k;
   in.shared_stream = a.shared_stream;
-  in.n_small_e = n_small_e; in.n_b64_e = FP8 ? 0 : n_b64_e; in.n_b128_e = FP8 ? 0 : n_b128_e;
+  in.n_small_e = n_small_e; in.n_b64_e = n_b64_e; in.n_b128_e = FP8 ? 0 : n_b128_e;
   in.G = G; in.bid = bid;
   in.dyn_allowed = DYN ? 1 : 0;
   in.fp8 = FP8 ? 1 : 0;
   StreamSched sc;
   stream_schedule(in, const_cast<int32_t *>(plan) + PLAN_CTR + MODE, sc);
-  if constexpr (!FP8) {
-    run_class<MODE, CLS_W128, false>(a, tb_, sc.c128, smem);
-    run_class<MODE, CLS_W64, false>(a, tb_, sc.c64, smem);
-  }
+  if constexpr (!FP8) run_class<MODE, CLS_W128, false>(a, tb_, sc.c128, smem);
+  run_class<MODE, CLS_W64, FP8>(a, tb_, sc.c64, smem);
   run_class<MODE, CLS_SMALL, FP8>(a, tb_, sc.cs, smem);
 }
 
@@ -942,7 +1006,7 @@ static hipError_t launch_stream(int mode, const StreamArgs &a, hipStream_t s) {
   const long per_s = mode == MODE_GATE_UP ? (a.S + srows / 2 - 1) / (srows / 2) : (a.d + srows - 1) / srows;
   const long parts = (mode == MODE_DOWN && a.S > 0) ? (a.S + a.part_k - 1) / a.part_k : 1;
   const long e_max = (long)a.T * a.K < a.E ? (long)a.T * a.K : a.E;
-  const long small_max = e_max * per_r + ((a.S > 0 && (a.T <= SMALL_M || (a.fp8 && a.shared_stream)))
+  const long small_max = e_max * per_r + ((a.S > 0 && (a.T <= SMALL_M || (a.fp8 && a.shared_stream && a.T > W64_TB)))
                                               ? per_s * parts * ((a.T + SMALL_M - 1) / SMALL_M) : 0);
   const bool dyn = DYN_STATIC_PCT < 100 && small_max * nkb_s >= (long)DYN_MIN_SLOTS * n_cu &&
                    small_max >= (long)DYN_MIN_TILES * n_cu;

@@ -87,10 +87,10 @@ __device__ __forceinline__ void permute_body(
   if (lane == 0 && wideb) atomicAdd(&wide_tot, __popcll(wideb));
   if (lane == 0 && largeb) atomicAdd(&large_tot, __popcll(largeb));
   __syncthreads();
-  const bool no_wide = wide_fill_min == PLAN_NO_WIDE;
-  const int b128_max = no_wide ? 16 : ((large_tot > 0 && wide_tot < wide_fill_min) ? 64 : PLAN_BIG_MAX_ROWS);
+  const bool w64_only = wide_fill_min == PLAN_WIDE64_ONLY;  // (8-bit weights: no 128-row wide class)
+  const int b128_max = w64_only ? 64 : ((large_tot > 0 && wide_tot < wide_fill_min) ? 64 : PLAN_BIG_MAX_ROWS);
   const int v_small = (v >= 1 && v <= 16) ? 1 : 0;
-  const int v_b64 = (!no_wide && v > 16 && v <= 64) ? 1 : 0;
+  const int v_b64 = (v > 16 && v <= 64) ? 1 : 0;
   const int v_b128 = (v > 64 && v <= b128_max) ? 1 : 0;
   const int v_large = (v > b128_max) ? (v + 255) / 256 : 0;
   int incl = v, incl_s = v_small, incl_b = v_b64, incl_c = v_b128, incl_l = v_large;

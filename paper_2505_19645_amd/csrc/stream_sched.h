@@ -88,7 +88,9 @@ struct StreamSched {
 
 // Where the shared expert runs: with at most 16 tokens in the small class, up to 64 in the first
 // wide class (one token block), beyond that in the second (blocks of 128 tokens) if the streaming
-// kernels keep it at all.
+// kernels keep it at all.  8-bit weights have the first wide class only (its weight slots hold 128 rows
+// of codes instead of 64 rows of bf16, so a tile has twice the weight rows); beyond 64 tokens the shared
+// expert, if the streaming kernels keep it, passes through the small class in blocks of 16 tokens.
 MOESD_SCHED_FN void stream_schedule(const SchedIn &in, int32_t *ctr, StreamSched &out) {
   const bool gu = in.mode == MODE_GATE_UP;
   const bool has_shared = in.S > 0;
@@ -101,11 +103,12 @@ MOESD_SCHED_FN void stream_schedule(const SchedIn &in, int32_t *ctr, StreamSched
   const int srows = in.fp8 ? 64 : 32;
   cs.per_r = gu ? (in.I + srows / 2 - 1) / (srows / 2) : (in.d + srows - 1) / srows;
   cs.per_s = gu ? (in.S + srows / 2 - 1) / (srows / 2) : (in.d + srows - 1) / srows;
-  c64.per_r = c128.per_r = gu ? (in.I + WHROWS - 1) / WHROWS : (in.d + 2 * WHROWS - 1) / (2 * WHROWS);
-  c64.per_s = c128.per_s = gu ? (in.S + WHROWS - 1) / WHROWS : (in.d + 2 * WHROWS - 1) / (2 * WHROWS);
-  cs.n_sh = (has_shared && (in.T <= SMALL_M || (in.fp8 && in.shared_stream)))
+  const int wh = in.fp8 ? 2 * WHROWS : WHROWS;  // rows of each operand half in a wide tile
+  c64.per_r = c128.per_r = gu ? (in.I + wh - 1) / wh : (in.d + 2 * wh - 1) / (2 * wh);
+  c64.per_s = c128.per_s = gu ? (in.S + wh - 1) / wh : (in.d + 2 * wh - 1) / (2 * wh);
+  cs.n_sh = (has_shared && (in.T <= SMALL_M || (in.fp8 && in.shared_stream && in.T > W64_TB)))
                 ? cs.per_s * parts * ((in.T + SMALL_M - 1) / SMALL_M) : 0;
-  c64.n_sh = (has_shared && !in.fp8 && in.T > SMALL_M && in.T <= W64_TB) ? c64.per_s * parts : 0;
+  c64.n_sh = (has_shared && in.T > SMALL_M && in.T <= W64_TB) ? c64.per_s * parts : 0;
   c128.n_sh = (has_shared && !in.fp8 && in.T > W64_TB && in.shared_stream)
                   ? c128.per_s * parts * ((in.T + W128_TB - 1) / W128_TB) : 0;
   const int n128 = c128.n_sh + in.n_b128_e * c128.per_r;
