@@ -78,12 +78,18 @@
 #ifndef W128_FRAG_DEPTH
 #define W128_FRAG_DEPTH 2  // chunks of weight fragments in flight in the 128-row class
 #endif
+// The 128-row wide class comes in two widths (weight slots per block, stream_sched.h): class 3 is the one
+// with WIDE_WN_MANY weight slots.
+enum { CLS_W128X = 3 };
 // token slots per block of a class (the small class keeps its tokens inside the one slot)
 template <int CLS> struct ClsGeo {
   static constexpr bool WIDE = CLS != CLS_SMALL;
-  static constexpr int NTS = CLS == CLS_W128 ? 2 : 1;
-  static constexpr int NSUB = WIDE ? NTS + WNW : 1;  // slots per block
-  static constexpr int ROWS = CLS == CLS_SMALL ? SMALL_M : (CLS == CLS_W64 ? W64_TB : W128_TB);
+  static constexpr bool T128 = CLS == CLS_W128 || CLS == CLS_W128X;  // 128 token rows per tile
+  static constexpr int NTS = T128 ? 2 : 1;
+  static constexpr int WN = CLS == CLS_W128X ? WIDE_WN_MANY : WIDE_WN_FEW;  // weight slots per block
+  static constexpr int WH = 32 * WN;                 // rows of each operand half in a tile (bf16)
+  static constexpr int NSUB = WIDE ? NTS + WN : 1;  // slots per block
+  static constexpr int ROWS = CLS == CLS_SMALL ? SMALL_M : (T128 ? W128_TB : W64_TB);
 };
 
 
@@ -248,7 +254,7 @@ __device__ __forceinline__ Entry load_entry(const StreamArgs &a, const Tables &t
     const int per = c.per_r;
     const int entry = (id - c.n_sh) / per;
     // the class's list of expert ids in the plan; an expert is one block of its class
-    const int list = CLS == CLS_SMALL ? PLAN_HDR : (CLS == CLS_W64 ? PLAN_BIG64_OFF(a.E) : PLAN_BIG128_OFF(a.E));
+    const int list = CLS == CLS_SMALL ? PLAN_HDR : (ClsGeo<CLS>::T128 ? PLAN_BIG128_OFF(a.E) : PLAN_BIG64_OFF(a.E));
     const int e = sload(tb_.plan, list + entry);
     int beg, end;
     sload2(tb_.offsets, e, e + 1, beg, end);
@@ -263,10 +269,12 @@ __device__ __forceinline__ Entry load_entry(const StreamArgs &a, const Tables &t
 }
 
 // first weight row of row tile rt (small tiles: 16 + 16 or 32 rows of bf16, 32 + 32 or 64 rows of 8-bit codes)
-template <int MODE, bool WIDE, bool FP8>
+template <int MODE, int CLS, bool FP8>
 __device__ __forceinline__ int tile_i0(int rt) {
-  if (MODE == MODE_GATE_UP) return WIDE ? rt * (FP8 ? 2 : 1) * WHROWS : rt * (FP8 ? 32 : 16);
-  return WIDE ? rt * (FP8 ? 4 : 2) * WHROWS : rt * (FP8 ? 64 : 32);
+  constexpr bool WIDE = ClsGeo<CLS>::WIDE;
+  constexpr int WH = ClsGeo<CLS>::WH;
+  if (MODE == MODE_GATE_UP) return WIDE ? rt * (FP8 ? 2 : 1) * WH : rt * (FP8 ? 32 : 16);
+  return WIDE ? rt * (FP8 ? 4 : 2) * WH : rt * (FP8 ? 64 : 32);
 }
 
 // Per-lane source pointers of the DMA instructions this wave issues.
@@ -318,7 +326,7 @@ __device__ __forceinline__ void setup_b(LoadPtrs<CLS> &lp, const Entry &en,
 template <int MODE, int CLS, bool FP8>
 __device__ __forceinline__ void setup_a(LoadPtrs<CLS> &lp, const Entry &en, int rt, int wave, int lane) {
   constexpr bool WIDE = ClsGeo<CLS>::WIDE;
-  const int i0 = tile_i0<MODE, WIDE, FP8>(rt);
+  const int i0 = tile_i0<MODE, CLS, FP8>(rt);
   if (!WIDE && !FP8) {
     // valid rows in each 16-row half of this tile (at least 1 after clamping)
     const int rv0 = min(16, en.n_rows - i0);
@@ -356,7 +364,7 @@ template <int MODE, int CLS, bool FP8>
 __device__ __forceinline__ void issue_slot(const LoadPtrs<CLS> &lp, const Entry &en, int kb, int sub,
                                            uint32_t slot_base, int wave, int lane) {
   constexpr bool WIDE = ClsGeo<CLS>::WIDE;
-  constexpr int NTS = ClsGeo<CLS>::NTS;
+  constexpr int NTS = ClsGeo<CLS>::NTS, WNW = ClsGeo<CLS>::WN, WHROWS = ClsGeo<CLS>::WH;
   const int klen = en.klen;
   if (!WIDE) {
     const int k0 = kb * KB;
@@ -488,8 +496,9 @@ __device__ __forceinline__ void store_out4(void *out, int out_n, size_t orow, in
 template <int MODE, int CLS, bool FP8>
 __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_, const ClassCfg &c,
                                           char *smem) {
-  constexpr bool WIDE = ClsGeo<CLS>::WIDE;
+  constexpr bool WIDE = ClsGeo<CLS>::WIDE, T128 = ClsGeo<CLS>::T128;
   constexpr int NTS = ClsGeo<CLS>::NTS, NSUB = ClsGeo<CLS>::NSUB;
+  constexpr int WNW = ClsGeo<CLS>::WN, WHROWS = ClsGeo<CLS>::WH;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = uni(tid >> 6);
   const int r16 = lane & 15, q = lane >> 4;
@@ -645,17 +654,17 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
     // in registers.  64-row class: the waves form 2 (row halves of a weight slot) x 2 (token halves) and a
     // wave multiplies 2 row tiles of every weight slot; 128-row class: wave w owns token rows 32w .. 32w+31
     // (token slot w >> 1) and multiplies all 4 row tiles of every weight slot.
-    constexpr int NRT = (CLS == CLS_W128 || FP8) ? 4 : 2;  // row tiles of a weight slot per wave (8-bit codes: slots of 128 rows)
+    constexpr int NRT = (T128 || FP8) ? 4 : 2;  // row tiles of a weight slot per wave (8-bit codes: slots of 128 rows)
     u32x4 fbw[WIDE ? 2 : 1][WIDE ? 8 : 1];
     f32x4 accw[WIDE ? WNW : 1][WIDE ? NRT : 1][2];  // [weight slot][row tile of the wave][token tile of the wave]
 #pragma unroll
     for (int w = 0; w < (WIDE ? WNW : 1); ++w)
 #pragma unroll
       for (int i = 0; i < (WIDE ? NRT : 1) * 2; ++i) accw[w][i >> 1][i & 1] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    const int wr = CLS == CLS_W128 ? 0 : (wave & 1);           // first row tile of the wave: NRT * wr
-    const int wt = CLS == CLS_W128 ? wave : (wave >> 1);       // token rows 32 wt .. 32 wt + 31 of the tile
-    const int tok_sub = CLS == CLS_W128 ? (wave >> 1) : 0;     // the token slot they arrive in
-    const int tok_row = CLS == CLS_W128 ? 32 * (wave & 1) : 32 * wt;  // their first row inside that slot
+    const int wr = T128 ? 0 : (wave & 1);           // first row tile of the wave: NRT * wr
+    const int wt = T128 ? wave : (wave >> 1);       // token rows 32 wt .. 32 wt + 31 of the tile
+    const int tok_sub = T128 ? (wave >> 1) : 0;     // the token slot they arrive in
+    const int tok_row = T128 ? 32 * (wave & 1) : 32 * wt;  // their first row inside that slot
 
     while (true) {
       bool tile_done = false;
@@ -796,7 +805,7 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
           wg_barrier();
           const char *sb = smem + (size_t)(c_slot % RG) * SLOTB;
           if (busy) {
-            if constexpr (CLS == CLS_W128) {
+            if constexpr (T128) {
               // 8 chunks of (2 row tiles) x (2 steps): the fragments of the next chunks are read while this
               // one is multiplied, and consecutive MFMAs go to 4 different accumulators.  All 8 steps of 2
               // row tiles at once would not fit the registers beside 64 accumulator and 64 token-fragment
@@ -877,7 +886,7 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
 
       if (tile_done) {
         const int id = c_id;
-        const int i0 = tile_i0<MODE, WIDE, FP8>(id - cen.first);
+        const int i0 = tile_i0<MODE, CLS, FP8>(id - cen.first);
         if (WIDE) {
           // straight from the accumulators: token row 32wt + 16tt + r16; slot w < WNW/2 pairs with slot
           // w + WNW/2 (gate with up rows; down: WHROWS features further on)
@@ -986,8 +995,13 @@ __global__ __launch_bounds__(STREAM_THREADS) void expert_stream_kernel(StreamArg
   in.fp8 = FP8 ? 1 : 0;
   StreamSched sc;
   stream_schedule(in, const_cast<int32_t *>(plan) + PLAN_CTR + MODE, sc);
-  if constexpr (!FP8) run_class<MODE, CLS_W128, false>(a, tb_, sc.c128, smem);
-  run_class<MODE, CLS_W64, FP8>(a, tb_, sc.c64, smem);
+  if constexpr (!FP8) {
+    if (sc.c128.wn == WIDE_WN_MANY) run_class<MODE, CLS_W128X, false>(a, tb_, sc.c128, smem);
+    else run_class<MODE, CLS_W128, false>(a, tb_, sc.c128, smem);
+    run_class<MODE, CLS_W64, false>(a, tb_, sc.c64, smem);
+  } else {
+    run_class<MODE, CLS_W64, true>(a, tb_, sc.c64, smem);
+  }
   run_class<MODE, CLS_SMALL, FP8>(a, tb_, sc.cs, smem);
 }
 

@@ -24,10 +24,15 @@ enum { CLS_SMALL = 0, CLS_W64 = 1, CLS_W128 = 2 };
 #define W128_TB 128  // of the second
 #define KB 512       // contraction elements per block, small tiles
 #define KBW 256      // wide tiles
-#ifndef WNW
-#define WNW 2        // weight slots per block: a wide tile has 64 * WNW weight rows (4 measured no
-#endif               // faster where tiles abound and much slower where they are few)
-#define WHROWS (32 * WNW)  // rows of each operand half in a wide tile
+// Weight slots (of 64 rows of bf16) per block of a wide tile: a wide tile has 64 * wn weight rows, and its
+// token rows are fetched once per that many.  Two; in the 128-row class four where the class then still
+// has WIDE4_MIN_TILES_PER_WG tiles per workgroup (its two token slots are then a third instead of half of
+// what the loading waves move: DeepSeek-V3-shaped layer at T = 2560 5.23 -> 4.87 ms).  With few tiles the
+// longer ones leave compute units idle (Mixtral-shaped down projection at T = 64 when forced: 0.78 -> 0.57
+// of the HBM peak), and in the 64-row class the wider tile measured slower in mixed launches.
+#define WIDE_WN_FEW 2
+#define WIDE_WN_MANY 4
+#define WIDE4_MIN_TILES_PER_WG 2
 // the schedule's cost model, in hundredths of a routed expert's small slot
 #define COST_WIDE_SLOT 100
 #define COST_CLASS_SWITCH 650
@@ -50,6 +55,7 @@ struct ClassCfg {
   int per_s;   // row tiles per shared entry
   int per_r;   // row tiles per routed entry
   int parts;   // k-parts of the shared down projection (1 for gate/up)
+  int wn;      // wide classes: weight slots per block (WIDE_WN_FEW or WIDE_WN_MANY)
   // Small tiles only: after its own range (n_mine tiles from id0) the workgroup draws units of
   // further tiles from a counter shared by all workgroups.  Units u < n_double hold 2 * ut tiles,
   // the others ut, the last one also what is left of the line; all lie in [pool0, n_tiles).
@@ -103,14 +109,27 @@ MOESD_SCHED_FN void stream_schedule(const SchedIn &in, int32_t *ctr, StreamSched
   const int srows = in.fp8 ? 64 : 32;
   cs.per_r = gu ? (in.I + srows / 2 - 1) / (srows / 2) : (in.d + srows - 1) / srows;
   cs.per_s = gu ? (in.S + srows / 2 - 1) / (srows / 2) : (in.d + srows - 1) / srows;
-  const int wh = in.fp8 ? 2 * WHROWS : WHROWS;  // rows of each operand half in a wide tile
-  c64.per_r = c128.per_r = gu ? (in.I + wh - 1) / wh : (in.d + 2 * wh - 1) / (2 * wh);
-  c64.per_s = c128.per_s = gu ? (in.S + wh - 1) / wh : (in.d + 2 * wh - 1) / (2 * wh);
   cs.n_sh = (has_shared && (in.T <= SMALL_M || (in.fp8 && in.shared_stream && in.T > W64_TB)))
                 ? cs.per_s * parts * ((in.T + SMALL_M - 1) / SMALL_M) : 0;
-  c64.n_sh = (has_shared && in.T > SMALL_M && in.T <= W64_TB) ? c64.per_s * parts : 0;
-  c128.n_sh = (has_shared && !in.fp8 && in.T > W64_TB && in.shared_stream)
-                  ? c128.per_s * parts * ((in.T + W128_TB - 1) / W128_TB) : 0;
+  cs.wn = 0;
+  // the wide classes: the shared expert's token blocks, and the tile width each class gets
+  const int sh64 = (has_shared && in.T > SMALL_M && in.T <= W64_TB) ? parts : 0;
+  const int sh128 = (has_shared && !in.fp8 && in.T > W64_TB && in.shared_stream)
+                        ? parts * ((in.T + W128_TB - 1) / W128_TB) : 0;
+  auto wide_cfg = [&](ClassCfg &c, int n_sh_blocks, int n_e, bool may_widen) {
+    int wn = (in.fp8 || !may_widen) ? WIDE_WN_FEW : WIDE_WN_MANY;
+    for (;;) {
+      const int wh = (in.fp8 ? 64 : 32) * wn;  // rows of each operand half in a wide tile (8-bit: slots of 128 rows)
+      c.per_r = gu ? (in.I + wh - 1) / wh : (in.d + 2 * wh - 1) / (2 * wh);
+      c.per_s = gu ? (in.S + wh - 1) / wh : (in.d + 2 * wh - 1) / (2 * wh);
+      c.n_sh = n_sh_blocks * c.per_s;
+      c.wn = wn;
+      if (wn == WIDE_WN_FEW || (long)c.n_sh + (long)n_e * c.per_r >= (long)WIDE4_MIN_TILES_PER_WG * G) break;
+      wn = WIDE_WN_FEW;
+    }
+  };
+  wide_cfg(c64, sh64, in.n_b64_e, false);
+  wide_cfg(c128, sh128, in.n_b128_e, true);
   const int n128 = c128.n_sh + in.n_b128_e * c128.per_r;
   const int n64 = c64.n_sh + in.n_b64_e * c64.per_r;
   const int n_small = cs.n_sh + in.n_small_e * cs.per_r;
@@ -138,8 +157,8 @@ MOESD_SCHED_FN void stream_schedule(const SchedIn &in, int32_t *ctr, StreamSched
   // all distinct (the shared expert at T = 16) takes 1.15x as long as one with a few.
   const int kr = gu ? in.d : in.I;
   const int nkb_s = (kr + KB - 1) / KB, nkb_w = (kr + KBW - 1) / KBW;
-  const double c_w64 = (double)(nkb_w * (WNW + 1) * 2 * COST_WIDE_SLOT) / 3.0;  // a wide slot is 2/3 of a small one
-  const double c_w128 = (double)(nkb_w * (WNW + 2) * 2 * COST_WIDE_SLOT) / 3.0;
+  const double c_w64 = (double)(nkb_w * (c64.wn + 1) * 2 * COST_WIDE_SLOT) / 3.0;  // a wide slot is 2/3 of a small one
+  const double c_w128 = (double)(nkb_w * (c128.wn + 2) * 2 * COST_WIDE_SLOT) / 3.0;
   const double c_sh = (double)(nkb_s * (100 + COST_DISTINCT_ROWS * (in.T < SMALL_M ? in.T : SMALL_M) / SMALL_M));
   const double c_r = (double)(nkb_s * 100);
   const int n_shs = cs.n_sh, n_rs = n_small - cs.n_sh;

@@ -145,6 +145,18 @@ def test_many_rows_per_expert(gpu, oracle, shape, T):
 
 
 @pytest.mark.parametrize("shape,T", [
+    # about 90 rows per expert and enough tiles that the 128-row streaming class takes its wide form (four
+    # weight slots per block) in the gate/up kernel (64 experts x 9 tiles, the last one ragged in rows and in k)
+    (LayerShape("wide4-gate-up", d=328, E=64, top_k=8, inter=1096, shared_inter=200, shared_gate=1, seed=38), 700),
+    # the same for the down projection (64 experts x 9 tiles of 512 output rows, the last with 8)
+    (LayerShape("wide4-down", d=4104, E=64, top_k=8, inter=520, seed=39), 720),
+])
+def test_wide_tiles_with_four_weight_slots(gpu, oracle, shape, T):
+    got, ref = run_case(gpu, oracle, shape, T)
+    assert ((got["counts"] > 64) & (got["counts"] <= 128)).sum() >= 56
+
+
+@pytest.mark.parametrize("shape,T", [
     # many row tiles and few stages: the persistent schedule cuts gate/up tiles (routed and shared region)
     (LayerShape("cut-gate-up", d=192, E=1, top_k=1, inter=12800, shared_inter=6400, seed=35), 520),
     # many token blocks x row tiles of the down projection: cuts there
