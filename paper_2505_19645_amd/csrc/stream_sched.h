@@ -81,11 +81,11 @@ struct SchedIn {
   int mode;                  // MODE_GATE_UP or MODE_DOWN
   int d, I, S, T, part_k;    // layer shape, tokens, k-part length of the shared down projection
   int shared_stream;         // the streaming kernels take the shared expert also above 128 tokens (8-bit
-                             // weights: above 16 tokens, in token blocks of 16 through the small class)
+                             // weights: above 64 tokens, in token blocks of 16 through the small class)
   int n_small_e, n_b64_e, n_b128_e;  // experts with 1..16, 17..64, 65..128 rows
   int G, bid;                // workgroups, this workgroup
   int dyn_allowed;           // the launched kernel can draw units
-  int fp8;                   // 8-bit weights: small tiles of 64 weight rows, no wide classes
+  int fp8;                   // 8-bit weights: small tiles of 64 weight rows, no 128-row wide class
 };
 
 struct StreamSched {

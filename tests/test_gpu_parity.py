@@ -193,8 +193,8 @@ def test_group_limited_selection(gpu, oracle, shape, T):
 @pytest.mark.parametrize("T", [1, 5, 16, 17, 40, 64, 130, 300])
 def test_fp8_weights_small_shapes(gpu, oracle, T):
     # expert weights as E4M3 codes with a scale per output row (64-row small tiles in the streaming kernels up to 16
-    # rows per expert; beyond that, and the shared expert beyond 16 tokens, the MFMA-tiled kernels, which widen the
-    # codes on their way into LDS); ragged sizes (multiples of 16), gated shared expert
+    # rows per expert, the 64-row wide class up to 64; beyond that, and the shared expert beyond 64 tokens, the
+    # MFMA-tiled kernels, which widen the codes on their way into LDS); ragged sizes (multiples of 16), gated shared expert
     shape = LayerShape("fp8-ragged", d=400, E=12, top_k=3, inter=208, shared_inter=144, shared_gate=1,
                        weight_format=1, seed=51)
     run_case(gpu, oracle, shape, T)
@@ -213,15 +213,17 @@ def test_fp8_weights_variants(gpu, oracle, shape, T, skew):
 
 def test_fp8_weights_benchmark_shapes_full_size(gpu, oracle):
     # benchmark configs 1 and 2 with their expert weights quantised to E4M3 (row scales), full size: T = 16 with
-    # every token compared, T = 64 (the shared expert in the MFMA-tiled kernels) on tokens chosen from the permutation
+    # every token compared; T = 64 (the shared expert in the 64-row wide class) and T = 200 (experts with more than
+    # 64 rows and the shared expert in the MFMA-tiled kernels) on tokens chosen from the permutation
     for name, pt in (("qwen1.5-moe-a2.7b", 180), ("qwen2-57b-a14b", 280)):
         shape = dataclasses.replace(PRESETS[name], name=name + "-fp8", weight_format=1)
         w = synth.make_layer(shape, threads=16)
         layer = gpu.GpuLayer(shape, w)
         run_case(gpu, oracle, shape, 16, point=pt, weights=w, layer=layer)
-        x = synth.make_tokens(shape, 64, point=pt + 1)
-        run_case(gpu, oracle, shape, 64, tokens=tokens_from_permutation(oracle, shape, w, x), point=pt + 1, weights=w,
-                 layer=layer)
+        for i, T in enumerate((64, 200)):
+            x = synth.make_tokens(shape, T, point=pt + 1 + i)
+            run_case(gpu, oracle, shape, T, tokens=tokens_from_permutation(oracle, shape, w, x), point=pt + 1 + i,
+                     weights=w, layer=layer)
         del layer, w
 
 
