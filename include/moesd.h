@@ -147,7 +147,7 @@ int64_t moesd_token_threshold(int32_t E, int32_t K, double tau);
  * T_max tokens (256-byte aligned pieces; the caller's buffer must itself be
  * 256-byte aligned).  Besides the per-token buffers (logits, routing outputs,
  * the bf16 activation [T*K, I] and the fp32 expert outputs [T*K, d]) it holds,
- * for T_max > 128 (E4M3 weights: T_max > 64), 128 MB of partial-sum space for the
+ * for T_max > 128, 128 MB of partial-sum space for the
  * MFMA-tiled expert kernels (512 KB for each of at most 256 persistent workgroups).  The size depends on
  * the arguments only, not on the device.  Returns 0 if the descriptor or T_max
  * is invalid. */

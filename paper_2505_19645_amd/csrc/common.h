@@ -109,9 +109,7 @@ hipError_t launch_topk(const double *logits, int T, int E, int K, int score_func
                        float *gate, hipStream_t s);
 // row_token / plan may be NULL (standalone permutation).  wide_fill_min: experts with 65..128 rows
 // go to the tiled kernels' list if some expert has more than 128 rows and fewer than that many
-// experts have 17..128 rows (0: never; -1: there is no 128-row wide class, every expert with more than
-// 64 rows goes to the tiled kernels' list).
-#define PLAN_WIDE64_ONLY (-1)
+// experts have 17..128 rows (0: never).
 hipError_t launch_permute(const int32_t *ids, int64_t n, int E, int K, int32_t *counts,
                           int32_t *offsets, int32_t *perm, int32_t *inv, int32_t *n_active,
                           int32_t *row_token, int32_t *plan, int wide_fill_min, hipStream_t s);

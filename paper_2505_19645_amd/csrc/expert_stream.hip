@@ -654,7 +654,7 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
     // in registers.  64-row class: the waves form 2 (row halves of a weight slot) x 2 (token halves) and a
     // wave multiplies 2 row tiles of every weight slot; 128-row class: wave w owns token rows 32w .. 32w+31
     // (token slot w >> 1) and multiplies all 4 row tiles of every weight slot.
-    constexpr int NRT = (T128 || FP8) ? 4 : 2;  // row tiles of a weight slot per wave (8-bit codes: slots of 128 rows)
+    constexpr int NRT = (T128 ? 4 : 2) * (FP8 ? 2 : 1);  // row tiles of a weight slot per wave (8-bit codes: slots of 128 rows)
     u32x4 fbw[WIDE ? 2 : 1][WIDE ? 8 : 1];
     f32x4 accw[WIDE ? WNW : 1][WIDE ? NRT : 1][2];  // [weight slot][row tile of the wave][token tile of the wave]
 #pragma unroll
@@ -805,7 +805,34 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
           wg_barrier();
           const char *sb = smem + (size_t)(c_slot % RG) * SLOTB;
           if (busy) {
-            if constexpr (T128) {
+            if constexpr (FP8) {
+              // 128 rows of 256 codes: the wave's NRT row tiles (64-row class: its half of the slot; 128-row
+              // class: all of it), 4 chunks of 64 contraction elements each
+#pragma unroll
+              for (int rtl = 0; rtl < NRT; ++rtl) {
+                const char *pa = sb + (size_t)(16 * (NRT * wr + rtl) + r16) * 256;
+                u32x4 codes[4];
+#pragma unroll
+                for (int ch = 0; ch < 4; ++ch)
+                  codes[ch] = *reinterpret_cast<const u32x4 *>(pa + (((4 * ch + q) ^ r16) << 4));
+#pragma unroll
+                for (int ch = 0; ch < 4; ++ch) {
+                  u32x4 lo, hi;
+#pragma unroll
+                  for (int dw = 0; dw < 2; ++dw) {
+                    lo[2 * dw] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(codes[ch][dw], 1.0f, false));
+                    lo[2 * dw + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(codes[ch][dw], 1.0f, true));
+                    hi[2 * dw] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(codes[ch][2 + dw], 1.0f, false));
+                    hi[2 * dw + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(codes[ch][2 + dw], 1.0f, true));
+                  }
+#pragma unroll
+                  for (int tt = 0; tt < 2; ++tt) {
+                    accw[w][rtl][tt] = mfma16(lo, fbw[tt][2 * ch], accw[w][rtl][tt]);
+                    accw[w][rtl][tt] = mfma16(hi, fbw[tt][2 * ch + 1], accw[w][rtl][tt]);
+                  }
+                }
+              }
+            } else if constexpr (T128) {
               // 8 chunks of (2 row tiles) x (2 steps): the fragments of the next chunks are read while this
               // one is multiplied, and consecutive MFMAs go to 4 different accumulators.  All 8 steps of 2
               // row tiles at once would not fit the registers beside 64 accumulator and 64 token-fragment
@@ -836,32 +863,6 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
                       accw[w][rt][tt] = mfma16(fa[ch % DEPTH][2 * ri + si], fbw[tt][st], accw[w][rt][tt]);
                   }
                 __builtin_amdgcn_sched_barrier(0);  // keeps the reads DEPTH - 1 chunks ahead, not more
-              }
-            } else if constexpr (FP8) {
-              // 128 rows of 256 codes: the wave's 4 row tiles, 4 chunks of 64 contraction elements each
-#pragma unroll
-              for (int rtl = 0; rtl < NRT; ++rtl) {
-                const char *pa = sb + (size_t)(16 * (NRT * wr + rtl) + r16) * 256;
-                u32x4 codes[4];
-#pragma unroll
-                for (int ch = 0; ch < 4; ++ch)
-                  codes[ch] = *reinterpret_cast<const u32x4 *>(pa + (((4 * ch + q) ^ r16) << 4));
-#pragma unroll
-                for (int ch = 0; ch < 4; ++ch) {
-                  u32x4 lo, hi;
-#pragma unroll
-                  for (int dw = 0; dw < 2; ++dw) {
-                    lo[2 * dw] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(codes[ch][dw], 1.0f, false));
-                    lo[2 * dw + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(codes[ch][dw], 1.0f, true));
-                    hi[2 * dw] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(codes[ch][2 + dw], 1.0f, false));
-                    hi[2 * dw + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(codes[ch][2 + dw], 1.0f, true));
-                  }
-#pragma unroll
-                  for (int tt = 0; tt < 2; ++tt) {
-                    accw[w][rtl][tt] = mfma16(lo, fbw[tt][2 * ch], accw[w][rtl][tt]);
-                    accw[w][rtl][tt] = mfma16(hi, fbw[tt][2 * ch + 1], accw[w][rtl][tt]);
-                  }
-                }
               }
             } else {
 #pragma unroll
@@ -972,7 +973,7 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
 
 // DYN: the variant that can draw units of small tiles from the counter (the host launches the
 // other one, which is a little quicker to start, when the small line is certainly too short for it).
-// FP8: expert weights are E4M3 codes with a scale per output row; small tiles and the 64-row wide class.
+// FP8: expert weights are E4M3 codes with a scale per output row.
 template <int MODE, bool DYN, bool FP8>
 __global__ __launch_bounds__(STREAM_THREADS) void expert_stream_kernel(StreamArgs a,
                                                             const int32_t *__restrict__ plan,
@@ -989,7 +990,7 @@ __global__ __launch_bounds__(STREAM_THREADS) void expert_stream_kernel(StreamArg
   in.mode = MODE;
   in.d = a.d; in.I = a.I; in.S = a.S; in.T = a.T; in.part_k = a.part_k;
   in.shared_stream = a.shared_stream;
-  in.n_small_e = n_small_e; in.n_b64_e = n_b64_e; in.n_b128_e = FP8 ? 0 : n_b128_e;
+  in.n_small_e = n_small_e; in.n_b64_e = n_b64_e; in.n_b128_e = n_b128_e;
   in.G = G; in.bid = bid;
   in.dyn_allowed = DYN ? 1 : 0;
   in.fp8 = FP8 ? 1 : 0;
@@ -1000,6 +1001,7 @@ __global__ __launch_bounds__(STREAM_THREADS) void expert_stream_kernel(StreamArg
     else run_class<MODE, CLS_W128, false>(a, tb_, sc.c128, smem);
     run_class<MODE, CLS_W64, false>(a, tb_, sc.c64, smem);
   } else {
+    run_class<MODE, CLS_W128, true>(a, tb_, sc.c128, smem);
     run_class<MODE, CLS_W64, true>(a, tb_, sc.c64, smem);
   }
   run_class<MODE, CLS_SMALL, FP8>(a, tb_, sc.cs, smem);
@@ -1020,7 +1022,7 @@ static hipError_t launch_stream(int mode, const StreamArgs &a, hipStream_t s) {
   const long per_s = mode == MODE_GATE_UP ? (a.S + srows / 2 - 1) / (srows / 2) : (a.d + srows - 1) / srows;
   const long parts = (mode == MODE_DOWN && a.S > 0) ? (a.S + a.part_k - 1) / a.part_k : 1;
   const long e_max = (long)a.T * a.K < a.E ? (long)a.T * a.K : a.E;
-  const long small_max = e_max * per_r + ((a.S > 0 && (a.T <= SMALL_M || (a.fp8 && a.shared_stream && a.T > W64_TB)))
+  const long small_max = e_max * per_r + ((a.S > 0 && a.T <= SMALL_M)
                                               ? per_s * parts * ((a.T + SMALL_M - 1) / SMALL_M) : 0);
   const bool dyn = DYN_STATIC_PCT < 100 && small_max * nkb_s >= (long)DYN_MIN_SLOTS * n_cu &&
                    small_max >= (long)DYN_MIN_TILES * n_cu;

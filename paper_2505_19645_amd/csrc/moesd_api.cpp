@@ -69,11 +69,8 @@ struct Workspace {
 };
 
 // Above how many tokens the MFMA-tiled kernels run (and need their partial-sum space): they take
-// the experts with more than 128 rows; 8-bit weights have the 64-row wide streaming class only, so
-// there they take every expert (and normally the shared expert) with more than 64 rows.
-inline int32_t tiled_from(const moesd_layer_desc *c) {
-  return c->weight_format == MOESD_WEIGHTS_FP8_E4M3 ? 64 : PLAN_BIG_MAX_ROWS;
-}
+// the experts with more than 128 rows.
+inline int32_t tiled_from(const moesd_layer_desc *) { return PLAN_BIG_MAX_ROWS; }
 
 // the group-limited selection's two settings in one launch argument (0: unconstrained)
 inline int groups_of(const moesd_layer_desc *c) {
@@ -277,14 +274,14 @@ int32_t run_forward(const moesd_layer_desc *desc, const moesd_weights *wt, const
   if (T <= MOESD_FUSED_TOPK_MAX_T && desc->E <= 256) {
     MOESD_TRY(launch_topk_permute(ws.logits, T, desc->E, desc->top_k, desc->score_func,
                                   desc->renormalize, desc->routed_scale, groups_of(desc), gated ? 1 : 0, ids, w,
-                                  ws.gate, cnt, off, pm, iv, na, ws.row_token, ws.plan, fp8 ? PLAN_WIDE64_ONLY : 0, s))
+                                  ws.gate, cnt, off, pm, iv, na, ws.row_token, ws.plan, 0, s))
   } else {
     MOESD_TRY(launch_topk(ws.logits, T, desc->E, desc->top_k, desc->score_func, desc->renormalize,
                           desc->routed_scale, groups_of(desc), gated ? 1 : 0, ids, w, ws.gate, s))
     // the wide classes of the streaming kernels fill the chip when their tiles of the down projection
     // (128 output rows each), the shorter of the two lists, number at least one per compute unit
     const int wide_rt = (desc->d + 127) / 128;
-    const int wide_fill_min = fp8 ? PLAN_WIDE64_ONLY : (T > PLAN_BIG_MAX_ROWS ? (n_cu + wide_rt - 1) / wide_rt : 0);
+    const int wide_fill_min = T > PLAN_BIG_MAX_ROWS ? (n_cu + wide_rt - 1) / wide_rt : 0;
     MOESD_TRY(launch_permute(ids, (int64_t)T * desc->top_k, desc->E, desc->top_k, cnt, off, pm, iv, na,
                              ws.row_token, ws.plan, wide_fill_min, s))
   }
@@ -319,15 +316,7 @@ int32_t run_forward(const moesd_layer_desc *desc, const moesd_weights *wt, const
   a.I = desc->inter;
   a.S = desc->shared_inter;
   a.T = T;
-  // 8-bit weights have no 128-row wide streaming class: above 64 tokens the shared expert either passes
-  // through the small class once per 16 tokens (its weights stream that often) or goes to the tiled
-  // kernels; the latter when its 128-row tiles there would fill at least half the chip, or beyond 128 tokens
-  if (fp8) {
-    const long tiles = (long)((desc->shared_inter + 127) / 128) * ((T + 255) / 256);
-    a.shared_stream = (T <= 64 || (T <= PLAN_BIG_MAX_ROWS && 2 * tiles < n_cu)) ? 1 : 0;
-  } else {
-    a.shared_stream = shared_expert_streams(T, desc->d, desc->shared_inter, ws.part_k, desc->top_k, desc->E, n_cu);
-  }
+  a.shared_stream = shared_expert_streams(T, desc->d, desc->shared_inter, ws.part_k, desc->top_k, desc->E, n_cu);
   // A shared expert that goes to the tiled kernels need not be split into k-parts: their own schedule cuts
   // contractions where that balances the chip, and every extra part costs T * d * 4 bytes written by the
   // down projection and read again by the combine.  That schedule counts every stage alike, though, and

@@ -87,8 +87,7 @@ __device__ __forceinline__ void permute_body(
   if (lane == 0 && wideb) atomicAdd(&wide_tot, __popcll(wideb));
   if (lane == 0 && largeb) atomicAdd(&large_tot, __popcll(largeb));
   __syncthreads();
-  const bool w64_only = wide_fill_min == PLAN_WIDE64_ONLY;  // (8-bit weights: no 128-row wide class)
-  const int b128_max = w64_only ? 64 : ((large_tot > 0 && wide_tot < wide_fill_min) ? 64 : PLAN_BIG_MAX_ROWS);
+  const int b128_max = (large_tot > 0 && wide_tot < wide_fill_min) ? 64 : PLAN_BIG_MAX_ROWS;
   const int v_small = (v >= 1 && v <= 16) ? 1 : 0;
   const int v_b64 = (v > 16 && v <= 64) ? 1 : 0;
   const int v_b128 = (v > 64 && v <= b128_max) ? 1 : 0;

@@ -80,12 +80,12 @@ MOESD_SCHED_FN void unit_range(const ClassCfg &c, int u, int &t0, int &t1) {
 struct SchedIn {
   int mode;                  // MODE_GATE_UP or MODE_DOWN
   int d, I, S, T, part_k;    // layer shape, tokens, k-part length of the shared down projection
-  int shared_stream;         // the streaming kernels take the shared expert also above 128 tokens (8-bit
-                             // weights: above 64 tokens, in token blocks of 16 through the small class)
+  int shared_stream;         // the streaming kernels take the shared expert also above 128 tokens
+                             // (in token blocks of 128 through the second wide class)
   int n_small_e, n_b64_e, n_b128_e;  // experts with 1..16, 17..64, 65..128 rows
   int G, bid;                // workgroups, this workgroup
   int dyn_allowed;           // the launched kernel can draw units
-  int fp8;                   // 8-bit weights: small tiles of 64 weight rows, no 128-row wide class
+  int fp8;                   // 8-bit weights: small tiles of 64 weight rows, wide slots of 128
 };
 
 struct StreamSched {
@@ -94,9 +94,8 @@ struct StreamSched {
 
 // Where the shared expert runs: with at most 16 tokens in the small class, up to 64 in the first
 // wide class (one token block), beyond that in the second (blocks of 128 tokens) if the streaming
-// kernels keep it at all.  8-bit weights have the first wide class only (its weight slots hold 128 rows
-// of codes instead of 64 rows of bf16, so a tile has twice the weight rows); beyond 64 tokens the shared
-// expert, if the streaming kernels keep it, passes through the small class in blocks of 16 tokens.
+// kernels keep it at all.  With 8-bit weights a wide weight slot holds 128 rows of codes instead of 64
+// rows of bf16, so a wide tile has twice the weight rows.
 MOESD_SCHED_FN void stream_schedule(const SchedIn &in, int32_t *ctr, StreamSched &out) {
   const bool gu = in.mode == MODE_GATE_UP;
   const bool has_shared = in.S > 0;
@@ -109,12 +108,11 @@ MOESD_SCHED_FN void stream_schedule(const SchedIn &in, int32_t *ctr, StreamSched
   const int srows = in.fp8 ? 64 : 32;
   cs.per_r = gu ? (in.I + srows / 2 - 1) / (srows / 2) : (in.d + srows - 1) / srows;
   cs.per_s = gu ? (in.S + srows / 2 - 1) / (srows / 2) : (in.d + srows - 1) / srows;
-  cs.n_sh = (has_shared && (in.T <= SMALL_M || (in.fp8 && in.shared_stream && in.T > W64_TB)))
-                ? cs.per_s * parts * ((in.T + SMALL_M - 1) / SMALL_M) : 0;
+  cs.n_sh = (has_shared && in.T <= SMALL_M) ? cs.per_s * parts : 0;
   cs.wn = 0;
   // the wide classes: the shared expert's token blocks, and the tile width each class gets
   const int sh64 = (has_shared && in.T > SMALL_M && in.T <= W64_TB) ? parts : 0;
-  const int sh128 = (has_shared && !in.fp8 && in.T > W64_TB && in.shared_stream)
+  const int sh128 = (has_shared && in.T > W64_TB && in.shared_stream)
                         ? parts * ((in.T + W128_TB - 1) / W128_TB) : 0;
   auto wide_cfg = [&](ClassCfg &c, int n_sh_blocks, int n_e, bool may_widen) {
     int wn = (in.fp8 || !may_widen) ? WIDE_WN_FEW : WIDE_WN_MANY;

@@ -50,8 +50,7 @@ def check(L, mode, d, I, S, T, part_k, shared_stream, ns, n64, n128, G, dyn, fp8
         assert (taken == 1).all(), (label, "wide class", rows_per)
         # where the shared expert is
         want_sh = 0
-        # (8-bit weights have the 64-row wide class only)
-        if S > 0 and ((ci == 1 and 16 < T <= 64) or (ci == 0 and not fp8 and T > 64 and shared_stream)):
+        if S > 0 and ((ci == 1 and 16 < T <= 64) or (ci == 0 and T > 64 and shared_stream)):
             want_sh = per_s * parts * (-(-T // rows_per) if ci == 0 else 1)
         assert n_sh == want_sh, (label, ci)
     # the small line: fixed ranges are consecutive, start at 0 and end where the drawn part begins
@@ -64,7 +63,7 @@ def check(L, mode, d, I, S, T, part_k, shared_stream, ns, n64, n128, G, dyn, fp8
         assert stride == 1 and n_mine >= 0 and id0 == pos, (label, b, id0, pos)
         pos += n_mine
     assert pos == n_stat, label
-    want_small = ns * r[0, 17] + (r[0, 16] * parts * -(-T // 16) if (S > 0 and (T <= 16 or (fp8 and shared_stream and T > 64))) else 0)
+    want_small = ns * r[0, 17] + (r[0, 16] * parts * -(-T // 16) if (S > 0 and T <= 16) else 0)
     assert n_tiles == want_small, label
     srows = 64 if fp8 else 32          # weight rows of a small tile
     assert r[0, 17] == (-(-I // (srows // 2)) if mode == 0 else -(-d // srows)), label
@@ -115,8 +114,6 @@ def test_random_splits(sched):
         if rng.random() < 0.2:
             ns = 0
         fp8 = int(rng.random() < 0.3)
-        if fp8:
-            n128 = 0                # 8-bit weights have no 128-row wide class: the plan lists none
         check(sched, int(rng.integers(0, 2)), d, I, S, T, part_k, int(rng.integers(0, 2)), ns, n64, n128, G,
               int(rng.integers(0, 2)), fp8)
 
