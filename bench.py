@@ -683,7 +683,7 @@ def main():
 
     # ---- the headline shape's sweep, then the other shapes -------------------------
     configs, sweeps, fits, mfma, fp8 = [], {}, {}, {}, {}
-    FP8_TS = (1, 16, 64)
+    FP8_TS = (1, 16, 64, 256)
 
     def bf16_times(run_, sh_, rows_):
         """bf16 layer times at the token counts of the fp8 comparison (from the sweep where it has them)."""
