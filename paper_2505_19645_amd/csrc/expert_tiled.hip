@@ -6,7 +6,8 @@
 // into blocks of 256 rows and handled here: a workgroup computes a 256-token x
 // 256-weight-row tile (128 w_gate rows + the same 128 w_up rows with SwiGLU
 // fused, or 256 w_down rows), marching over the contraction dimension in
-// 64-element stages through two LDS buffers, with v_mfma_f32_16x16x32_bf16.
+// 64-element stages through LDS (three weight buffers and two token buffers of
+// 32 KB), with v_mfma_f32_16x16x32_bf16.
 //
 //  * The card runs these kernels against its power limit, not its clock limit (registers-only
 //    MFMA loops on random bf16 data sustain 0.80 of the 2.5 PFLOP/s peak with the 32x32x16
@@ -16,11 +17,10 @@
 //    2 (row halves) x 4 (token quarters); a wave owns 2 x 4 16-row tiles (gate
 //    and up rows 64wr..64wr+63, or two 64-row groups of w_down) x four 16-token
 //    tiles = 32 accumulator tiles; 131 flops per byte brought into LDS.
-//  * Operands travel global memory -> registers -> LDS: every lane fetches eight
-//    16-byte pieces of a stage (whole 128-byte lines per row) about one stage ahead of
-//    the multiplication and stores them when the other buffer has been read.
-//    (Measured on this chip: the same traffic through global_load_lds tops out at
-//    about two thirds of this path's rate, and 64-byte row pieces at less again.)
+//  * Operands travel global memory -> LDS by global_load_lds (no registers, no LDS store
+//    instructions): every wave moves 32 rows of each operand per stage, whole 128-byte lines per
+//    row, the weights two stages ahead of the multiplication and the tokens (which come from L2)
+//    one.  E4M3 weights are widened to bf16 on the way and pass through registers instead.
 //  * Rows are 128 bytes in LDS, their eight 16-byte pieces XOR-swizzled by
 //    (row >> 1) & 7: two rows share a 256-byte bank line, so the 16 rows a
 //    quarter-wave reads, and the 2 rows x 8 pieces it writes, fall into 16

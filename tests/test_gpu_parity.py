@@ -157,6 +157,28 @@ def test_wide_tiles_with_four_weight_slots(gpu, oracle, shape, T):
 
 
 @pytest.mark.parametrize("shape,T", [
+    # about 280 rows per expert: a full 256-row block and a last block of a few dozen rows, which the tiled
+    # kernels take as a 64-token tile drawn from a counter; ragged contraction lengths and row tiles
+    (LayerShape("narrow-tail", d=328, E=4, top_k=2, inter=520, seed=46), 560),
+    (LayerShape("narrow-tail-shared", d=264, E=2, top_k=1, inter=200, shared_inter=136, shared_gate=1, seed=47), 580),
+    (LayerShape("narrow-tail-fp8", d=336, E=4, top_k=2, inter=528, weight_format=1, seed=48), 560),
+    # 16 experts with 512 +- 20 rows: narrow tiles beside a schedule of many whole tiles
+    (LayerShape("narrow-tail-many", d=192, E=16, top_k=2, inter=1160, seed=49), 4096),
+])
+def test_last_blocks_with_few_rows(gpu, oracle, shape, T):
+    tokens = None
+    if T > 1000:
+        w = synth.make_layer(shape, threads=16)
+        x = synth.make_tokens(shape, T, point=0)
+        tokens = tokens_from_permutation(oracle, shape, w, x, budget=40)
+        got, ref = run_case(gpu, oracle, shape, T, tokens=tokens, weights=w, x=x)
+    else:
+        got, ref = run_case(gpu, oracle, shape, T)
+    c = got["counts"]
+    assert ((c > 256) & ((c - 1) % 256 < 64)).sum() >= 1
+
+
+@pytest.mark.parametrize("shape,T", [
     # many row tiles and few stages: the persistent schedule cuts gate/up tiles (routed and shared region)
     (LayerShape("cut-gate-up", d=192, E=1, top_k=1, inter=12800, shared_inter=6400, seed=35), 520),
     # many token blocks x row tiles of the down projection: cuts there
