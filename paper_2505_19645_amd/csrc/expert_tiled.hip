@@ -3,7 +3,7 @@
 // Once an expert's load T_exp passes the ridge point the layer turns from
 // loading weights to computing (the k3*G(T_exp) term of the paper's Sec. 3.3
 // model).  Experts (or the shared expert) with more than 128 token rows are cut
-// into blocks of 256 rows and handled here: a workgroup computes a 256-token x
+// into equal blocks of at most 256 rows and handled here: a workgroup computes a 256-token x
 // 256-weight-row tile (128 w_gate rows + the same 128 w_up rows with SwiGLU
 // fused, or 256 w_down rows), marching over the contraction dimension in
 // 64-element stages through LDS (three weight buffers and two token buffers of
@@ -16,7 +16,8 @@
 //  * Eight waves (two per SIMD, so one multiplies while the other waits) as
 //    2 (row halves) x 4 (token quarters); a wave owns 2 x 4 16-row tiles (gate
 //    and up rows 64wr..64wr+63, or two 64-row groups of w_down) x four 16-token
-//    tiles = 32 accumulator tiles; 131 flops per byte brought into LDS.
+//    tiles (tiles wt, wt+4, wt+8, wt+12 of the block's 16) = 32 accumulator tiles; 131 flops
+//    per byte brought into LDS.
 //  * Operands travel global memory -> LDS by global_load_lds (no registers, no LDS store
 //    instructions): every wave moves 32 rows of each operand per stage, whole 128-byte lines per
 //    row, the weights two stages ahead of the multiplication and the tokens (which come from L2)
@@ -25,8 +26,9 @@
 //    (row >> 1) & 7: two rows share a 256-byte bank line, so the 16 rows a
 //    quarter-wave reads, and the 2 rows x 8 pieces it writes, fall into 16
 //    different 16-byte bank groups.
-//  * A wave whose 64 token rows are all padding multiplies nothing (it still loads and
-//    stores its share of the stages): a block of at most 128 rows costs half the MFMA time.
+//  * Token tiles that are all padding are neither read nor multiplied (the stage loop is a template
+//    over the number of a wave's tiles that hold rows; every wave still moves its share of the
+//    stages): the MFMA time of a block follows its rows in steps of 32.
 //  * A stage is two steps of 32 contraction elements.  The 8 weight fragments of a step are
 //    refilled in place, each right after the four MFMAs that read it, with the fragment of the
 //    next step; the 4 token fragments alternate between two register sets.  One s_barrier per
@@ -73,6 +75,17 @@ enum { TMODE_GATE_UP = 0, TMODE_DOWN = 1 };
 __device__ __forceinline__ void t_barrier() {
   asm volatile("" ::: "memory");
   __builtin_amdgcn_s_waitcnt(0xC07F);  // vmcnt and expcnt unconstrained, lgkmcnt(0)
+  asm volatile("s_barrier" ::: "memory");
+}
+
+// The barrier that opens a piece also waits for every vector memory operation of the wave (nothing of this
+// piece is in flight yet; what remains are the previous piece's output stores and register reloads the
+// compiler placed before the stage loop).  As a builtin it tells the compiler's wait-count bookkeeping that
+// those reloads have landed; otherwise it puts a wait for them inside the stage loop, where, not knowing of
+// the LDS-DMA loads the asm statements issue, it waits for all of those as well, every stage.
+__device__ __forceinline__ void t_barrier_opening() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0), expcnt unconstrained, lgkmcnt(0)
   asm volatile("s_barrier" ::: "memory");
 }
 
@@ -135,6 +148,18 @@ __device__ __forceinline__ TiledWork tiled_work(const StreamArgs &a, const Tiled
 // when runs are cut: first unit of team g's share (g = n_teams: one past the end)
 __device__ __forceinline__ long tiled_team_start(const TiledWork &w, int g) { return (w.W * g) / w.n_teams; }
 
+// The rows of an expert (or the tokens of the shared expert) go into nb = ceil(rows / 256) blocks.  The
+// multiplying work of a tile follows its rows in steps of 32 (see idle token tiles below), and the blocks of
+// one expert are walked in step by a team, so an even split (in multiples of 16 rows) is taken where it
+// makes every block cheaper than a whole tile: three blocks of 176 rows instead of 256 + 256 + 16.  Where
+// the even blocks would be (nearly) whole tiles anyway, the blocks are 256 rows and the last one holds the
+// rest.  Block blk holds rows [blk * per, min(rows, (blk + 1) * per)); (nb - 1) * per < rows either way.
+__device__ __forceinline__ int tiled_block_rows(int rows) {
+  const int nb = (rows + TBM - 1) / TBM;
+  const int per = ((rows + nb - 1) / nb + 15) & ~15;
+  return per > TBM - 32 ? TBM : per;
+}
+
 // One piece: stages [st0, st1) of one tile (stage numbers in units of the region's nkb_reg).
 // FIXUP: no multiplication; the accumulators are the sum of the tile's stored pieces, and the workgroup
 // finishes only token tile tq of every wave (a quarter of the tile: 32 accumulator registers instead of
@@ -145,7 +170,12 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
                                             int team_member, const TiledWork &w, int tq = 0) {
   constexpr int NT = FIXUP ? 1 : 4;  // token tiles held per wave
   const int n_large = w.n_large;
-  const int tid = threadIdx.x, lane = tid & 63;
+  // (the thread id passes through an empty asm so that what is derived from it is computed anew for every
+  // piece: kept across pieces, those values were spilled, and a reload placed before the stage loop made
+  // the compiler wait, inside the loop, for everything in flight)
+  int tid_ = threadIdx.x;
+  asm volatile("" : "+v"(tid_));
+  const int tid = tid_, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wr = wave & 1, wt = wave >> 1;  // weight row half, token quarter
   const int r16 = lane & 15, q = lane >> 4;
@@ -173,8 +203,9 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
   if (entry < n_shared_entries) {
     const int part = (MODE == TMODE_DOWN) ? entry % parts : 0;
     const int blk = (MODE == TMODE_DOWN) ? entry / parts : entry;
-    row0 = blk * TBM;
-    m = min(a.T - row0, TBM);
+    const int per = tiled_block_rows(a.T);
+    row0 = blk * per;
+    m = min(a.T - row0, per);
     use_map = false;
     if (MODE == TMODE_GATE_UP) {
       A0 = reinterpret_cast<const char *>(a.ws_gate); A1 = reinterpret_cast<const char *>(a.ws_up);
@@ -194,8 +225,9 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
     const int base = PLAN_LARGE_OFF(a.E);
     const int e = a.plan[base + 2 * le], blk = a.plan[base + 2 * le + 1];
     const int beg = a.offsets[e], end = a.offsets[e + 1];
-    row0 = beg + blk * TBM;
-    m = min(end - row0, TBM);
+    const int per = tiled_block_rows(end - beg);
+    row0 = beg + blk * per;
+    m = min(end - row0, per);
     if (MODE == TMODE_GATE_UP) {
       A0 = reinterpret_cast<const char *>(a.w_gate) + (size_t)e * a.I * a.d * esz;
       A1 = reinterpret_cast<const char *>(a.w_up) + (size_t)e * a.I * a.d * esz;
@@ -303,13 +335,13 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
   // Operand fragments of one 32-element step: 8 weight tiles and 4 token tiles of 16 rows.
   const int key = (r16 >> 1) & 7;
   const char *pa0 = smem + (64 * wr + r16) * T_ROW_BYTES;
-  const char *pb0 = smem + B_BASE + (64 * wt + r16) * T_ROW_BYTES;
+  const char *pb0 = smem + B_BASE + (16 * wt + r16) * T_ROW_BYTES;  // token tile t of this wave: rows 16 (wt + 4 t) ..
   auto frag_off = [&](int ks) __attribute__((always_inline)) { return ((4 * ks + q) ^ key) << 4; };
   auto read_a = [&](int ab, int ks, int h) __attribute__((always_inline)) {
     return *reinterpret_cast<const u32x4 *>(pa0 + ab * T_A_BYTES + frag_off(ks) + ((h >> 2) * 128 + (h & 3) * 16) * T_ROW_BYTES);
   };
   auto read_b = [&](int bb, int ks, int t) __attribute__((always_inline)) {
-    return *reinterpret_cast<const u32x4 *>(pb0 + bb * T_B_BYTES + frag_off(ks) + t * 16 * T_ROW_BYTES);
+    return *reinterpret_cast<const u32x4 *>(pb0 + bb * T_B_BYTES + frag_off(ks) + t * 64 * T_ROW_BYTES);
   };
 
   const int nkb = (klen + TBK - 1) / TBK;          // this tile's own stage count (<= nkb_reg)
@@ -324,16 +356,18 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
   // and the barrier; in the shadow of the second step the fragments of the next stage's first step are
   // read and loads are issued into the buffers just left: the tokens of stage j + 2, then the weights of
   // stage j + NAB.  (Scheduling groups: 0x008 MFMA, 0x100 DS read.)
-  auto mfma_group = [&](int h, int set) __attribute__((always_inline)) {
+  auto mfma_group = [&](int h, int set, auto ntv) __attribute__((always_inline)) {
+    constexpr int NTV = decltype(ntv)::value;
 #pragma unroll
-    for (int t = 0; t < 4; ++t) acc[h][t] = mfma16(fa[h], fb[set][t], acc[h][t]);
+    for (int t = 0; t < NTV; ++t) acc[h][t] = mfma16(fa[h], fb[set][t], acc[h][t]);
   };
-  auto group_shadow = [&](bool reads, bool two) __attribute__((always_inline)) {
+  auto group_shadow = [&](bool reads, bool two, auto ntv) __attribute__((always_inline)) {
+    constexpr int NTV = decltype(ntv)::value;
     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
     if (reads) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    if constexpr (NTV >= 2) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
     if (reads && two) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+    if constexpr (NTV > 2) __builtin_amdgcn_sched_group_barrier(0x008, NTV - 2, 0);
     __builtin_amdgcn_sched_barrier(0);
   };
   using std::integral_constant;
@@ -341,34 +375,36 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
   using N = std::false_type;
   // ab: weight buffer of stage j.  H1, H2, H3: stages j+1, j+2, j+3 exist in this piece.  At the wait,
   // the youngest instructions in flight are the 4 weight loads of stage j + 2 (3 weight buffers), if any.
-  auto step = [&](int j, int ab, auto h1, auto h2, auto h3, auto mult) __attribute__((always_inline)) {
+  auto step = [&](int j, int ab, auto h1, auto h2, auto h3, auto ntv) __attribute__((always_inline)) {
     constexpr bool H1 = decltype(h1)::value, H2 = decltype(h2)::value, H3 = decltype(h3)::value;
-    constexpr bool MULT = decltype(mult)::value;  // false: a wave whose token rows are all padding
+    constexpr int NTV = decltype(ntv)::value;  // this wave's token tiles that hold rows (they are its first ones)
+    constexpr bool MULT = NTV > 0;             // false: a wave whose token rows are all padding
     constexpr bool HA = NAB == 3 ? H3 : H2;       // the weights to issue in this stage exist
     const int bb = j & 1;
     const int ab1 = ab + 1 == NAB ? 0 : ab + 1;
     if constexpr (MULT) {
 #pragma unroll
       for (int h = 0; h < 8; ++h) {
-        mfma_group(h, 0);
+        mfma_group(h, 0, ntv);
         fa[h] = read_a(ab, 1, h);
-        if (h < 4) fb[1][h] = read_b(bb, 1, h);
-        group_shadow(true, h < 4);
+        if (h < NTV) fb[1][h] = read_b(bb, 1, h);
+        group_shadow(true, h < NTV, ntv);
       }
     }
     if constexpr (H1) {
-      finish_stage(s0 + j + 1, ab1, ragged && j + 2 == n, integral_constant<int, (NAB == 3 && H2) ? 4 : 0>{});
+      // (stage j + 1 is the last one, the only one that can be ragged, exactly when stage j + 2 does not exist)
+      finish_stage(s0 + j + 1, ab1, H2 ? false : ragged, integral_constant<int, (NAB == 3 && H2) ? 4 : 0>{});
       t_barrier();  // the next stage is in LDS for everyone; everyone has read this one
     }
     if constexpr (MULT) {
 #pragma unroll
       for (int h = 0; h < 8; ++h) {
-        mfma_group(h, 1);
+        mfma_group(h, 1, ntv);
         if constexpr (H1) {
           fa[h] = read_a(ab1, 0, h);
-          if (h < 4) fb[0][h] = read_b(bb ^ 1, 0, h);
+          if (h < NTV) fb[0][h] = read_b(bb ^ 1, 0, h);
         }
-        group_shadow(H1, h < 4);
+        group_shadow(H1, h < NTV, ntv);
         if (h < 4) {
           if constexpr (H2) issue_b(s0 + j + 2, bb, h);
         } else {
@@ -384,20 +420,23 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
         if constexpr (HA) issue_a(s0 + j + NAB, ab, i);
     }
   };
-  // A wave whose 64 token rows are all padding (a block with few rows: the last one of an expert, or an
-  // expert with 65..128 rows) only keeps moving its share of the stages and the barriers.
-  // With the usual placement of a workgroup's waves (wave i on SIMD i mod 4) a block of at most 128
-  // rows then leaves one multiplying wave per SIMD instead of two.
-  const bool idle_wave = 64 * wt >= m;
+  // Idle token tiles.  The 16 token tiles of a block are dealt round-robin to the four token quarters (wave
+  // wt holds tiles wt, wt + 4, wt + 8, wt + 12), so a block of m rows leaves every wave its first
+  // ceil((ceil(m / 16) - wt) / 4) tiles; the others are padding and are neither read nor multiplied.  With the
+  // usual placement of a workgroup's waves (wave i on SIMD i mod 4) the multiplying work of every SIMD then
+  // follows the rows in steps of 32.  A wave without any tile only keeps moving its share of the stages and
+  // keeps the barriers.
+  const int n_tiles16 = (m + 15) >> 4;
+  const int my_tiles = min(4, (n_tiles16 - wt + 3) >> 2);
   // the stages of a piece; the last ones are straight-line sequences chosen by how many remain, so the
   // steady state is branch-free
   auto run_stages = [&](auto mult) __attribute__((always_inline)) {
-    constexpr bool MULT = decltype(mult)::value;
-    if constexpr (MULT) {
+    constexpr int NTV = decltype(mult)::value;
+    if constexpr (NTV > 0) {
 #pragma unroll
       for (int h = 0; h < 8; ++h) fa[h] = read_a(0, 0, h);
 #pragma unroll
-      for (int t = 0; t < 4; ++t) fb[0][t] = read_b(0, 0, t);
+      for (int t = 0; t < NTV; ++t) fb[0][t] = read_b(0, 0, t);
     }
     int j = 0, ab = 0;
     for (; j + 3 < n; ++j) {
@@ -417,7 +456,7 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
     step(j, ab, N{}, N{}, N{}, mult);
   };
   if (!FIXUP && n > 0) {
-    t_barrier();  // everyone is done with the LDS of the previous piece
+    t_barrier_opening();  // everyone is done with the LDS of the previous piece
     // in flight before the loop: stage 0; the tokens of stage 1; the weights of stages 1 .. NAB-1
 #pragma unroll
     for (int i = 0; i < 4; ++i) issue_b(s0, 0, i);
@@ -442,8 +481,13 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
       }
     }
     t_barrier();
-    if (idle_wave) run_stages(N{});
-    else run_stages(Y{});
+    switch (my_tiles) {  // wave-uniform; every variant keeps the same barriers
+      case 0: run_stages(integral_constant<int, 0>{}); break;
+      case 1: run_stages(integral_constant<int, 1>{}); break;
+      case 2: run_stages(integral_constant<int, 2>{}); break;
+      case 3: run_stages(integral_constant<int, 3>{}); break;
+      default: run_stages(integral_constant<int, 4>{}); break;
+    }
   }
 
   // ---- a tile cut by the schedule: its pieces meet in memory, the second kernel finishes it --
@@ -478,12 +522,12 @@ __device__ __forceinline__ void tiled_piece(const StreamArgs &a, const TiledSche
     }
   }
 
-  // ---- epilogue: lane holds, for token (64wt + 16t + r16), features 4q .. 4q+3 of every weight tile ------
+  // ---- epilogue: lane holds, for token 16 (wt + 4t) + r16, features 4q .. 4q+3 of every weight tile ------
   // weight tile h: half (h >> 2), rows 64wr + 16(h & 3) .. +15 of that half
 #pragma unroll
   for (int tl = 0; tl < NT; ++tl) {
     const int t = FIXUP ? tq : tl;  // which of the wave's four token tiles acc[.][tl] is
-    const int j = 64 * wt + 16 * t + r16;
+    const int j = 16 * (wt + 4 * t) + r16;
     if (j < m) {
       const size_t orow = (size_t)(row0 + j);
 #pragma unroll
