@@ -617,7 +617,9 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
     bool pend = false;
     int pend_m = 0, pend_row0 = 0, pend_i0 = 0, pend_n = 0;
     void *pend_out = nullptr;
-    const float *pend_s0 = nullptr, *pend_s1 = nullptr;  // (8-bit weights: its row scales)
+    // (8-bit weights: the row scales of this thread's four sums, fetched when the tile is finished so that
+    // they have landed when the sums are added, a barrier later)
+    float pend_c0[2] = {0.f, 0.f}, pend_c1[2] = {0.f, 0.f};
 
     // After a barrier: add the waves' partial tiles.  Thread t takes token row t >> 4 and feature
     // t & 15 (of both halves), so 16 neighbouring lanes store 16 neighbouring features of a row.
@@ -637,9 +639,7 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
 #pragma unroll
         for (int hh = 0; hh < 2; ++hh) {
           const int i = pend_i0 + 16 * hh + fi;  // feature (gate/up) or first of the two output rows (down)
-          const int i1 = (MODE == MODE_GATE_UP) ? i : i + 32;
-          const float c0 = (j < pend_m && i < pend_n) ? pend_s0[i] : 0.f;
-          const float c1 = (j < pend_m && i1 < pend_n) ? pend_s1[i1] : 0.f;
+          const float c0 = pend_c0[hh], c1 = pend_c1[hh];
           const float s0 = red[(0 * 4 + hh * 2 + 0) * RED_TILE + j * RED_ROW + fi] +
                            red[(1 * 4 + hh * 2 + 0) * RED_TILE + j * RED_ROW + fi];
           const float s1 = red[(0 * 4 + hh * 2 + 1) * RED_TILE + j * RED_ROW + fi] +
@@ -891,38 +891,36 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
         if (WIDE) {
           // straight from the accumulators: token row 32wt + 16tt + r16; slot w < WNW/2 pairs with slot
           // w + WNW/2 (gate with up rows; down: WHROWS features further on)
+          // (8-bit weights: one scale per weight row = per output feature, fetched once per row tile for both
+          // token tiles, from clamped addresses: a feature past the end gets some other row's scale and its
+          // store is skipped.  The registers are nearly all taken here, so no further ahead than that.)
 #pragma unroll
-          for (int tt = 0; tt < 2; ++tt) {
-            const int j = 32 * wt + 16 * tt + r16;
-            if (j < cen.m) {
+          for (int w = 0; w < WNW / 2; ++w)
 #pragma unroll
-              for (int w = 0; w < WNW / 2; ++w)
+            for (int rtl = 0; rtl < NRT; ++rtl) {
+              const int i = i0 + (FP8 ? 128 : 64) * w + 16 * (NRT * wr + rtl) + 4 * q;
+              f32x4 c0 = {1.f, 1.f, 1.f, 1.f}, c1 = {1.f, 1.f, 1.f, 1.f};
+              if constexpr (FP8) {
+                const int i1 = (MODE == MODE_GATE_UP) ? i : i + 2 * WHROWS;
+                c0 = *reinterpret_cast<const f32x4 *>(cen.s0 + min(i, cen.out_n - 4));
+                c1 = *reinterpret_cast<const f32x4 *>(cen.s1 + min(i1, cen.out_n - 4));
+              }
 #pragma unroll
-                for (int rtl = 0; rtl < NRT; ++rtl) {
-                  if constexpr (!FP8) {
-                    store_out4<MODE>(cen.out, cen.out_n, (size_t)(cen.row0 + j),
-                                     i0 + 64 * w + 16 * (NRT * wr + rtl) + 4 * q, WHROWS, accw[w][rtl][tt],
-                                     accw[w + WNW / 2][rtl][tt]);
-                  } else {
-                    // one scale per weight row = per output feature (both halves' rows exist or the store is skipped)
-                    const int i = i0 + 128 * w + 16 * (NRT * wr + rtl) + 4 * q;
-                    const int i1 = (MODE == MODE_GATE_UP) ? i : i + 2 * WHROWS;
-                    f32x4 v0 = accw[w][rtl][tt], v1 = accw[w + WNW / 2][rtl][tt];
-                    if (i < cen.out_n) {
-                      const f32x4 c0 = *reinterpret_cast<const f32x4 *>(cen.s0 + i);
+              for (int tt = 0; tt < 2; ++tt) {
+                const int j = 32 * wt + 16 * tt + r16;
+                if (j < cen.m) {
+                  f32x4 v0 = accw[w][rtl][tt], v1 = accw[w + WNW / 2][rtl][tt];
+                  if constexpr (FP8) {
 #pragma unroll
-                      for (int c = 0; c < 4; ++c) v0[c] *= c0[c];
+                    for (int c = 0; c < 4; ++c) {
+                      v0[c] *= c0[c];
+                      v1[c] *= c1[c];
                     }
-                    if (i1 < cen.out_n) {
-                      const f32x4 c1 = *reinterpret_cast<const f32x4 *>(cen.s1 + i1);
-#pragma unroll
-                      for (int c = 0; c < 4; ++c) v1[c] *= c1[c];
-                    }
-                    store_out4<MODE>(cen.out, cen.out_n, (size_t)(cen.row0 + j), i, 2 * WHROWS, v0, v1);
                   }
+                  store_out4<MODE>(cen.out, cen.out_n, (size_t)(cen.row0 + j), i, FP8 ? 2 * WHROWS : WHROWS, v0, v1);
                 }
+              }
             }
-          }
 #pragma unroll
           for (int w = 0; w < WNW; ++w)
 #pragma unroll
@@ -934,8 +932,16 @@ __device__ __forceinline__ void run_class(const StreamArgs &a, const Tables &tb_
           const int slot2 = FP8 ? 4 * (wave >> 1) + 2 * (wave & 1) : wave * 2;
           *reinterpret_cast<f32x4 *>(red + (slot2 + 0) * RED_TILE + r16 * RED_ROW + 4 * q) = acc0[0];
           *reinterpret_cast<f32x4 *>(red + (slot2 + 1) * RED_TILE + r16 * RED_ROW + 4 * q) = acc1[0];
-          pend_s0 = cen.s0;
-          pend_s1 = cen.s1;
+          if constexpr (FP8) {
+            const int pj = tid >> 4, pf = tid & 15;
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh) {
+              const int i = i0 + 16 * hh + pf;
+              const int i1 = (MODE == MODE_GATE_UP) ? i : i + 32;
+              pend_c0[hh] = (pj < cen.m && i < cen.out_n) ? cen.s0[i] : 0.f;
+              pend_c1[hh] = (pj < cen.m && i1 < cen.out_n) ? cen.s1[i1] : 0.f;
+            }
+          }
           pend = true;
           pend_m = cen.m;
           pend_row0 = cen.row0;
