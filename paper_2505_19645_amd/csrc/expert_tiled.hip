@@ -118,6 +118,20 @@ struct TiledWork {
   int nkb_s, nkb_r, n_teams;
   bool cut;           // shares end inside runs (else on run boundaries)
 };
+// Whether the shares of the teams end inside runs.  Cutting runs costs a round trip of partial sums through
+// memory and a second epilogue pass: only worth it when whole runs would leave the busiest team more than 15 %
+// above the mean, or when at least half the teams would idle and every team still gets 32 stages.  (Whole
+// runs are dealt region by region; the shared expert's runs are as long as its whole contraction, the routed
+// experts' as theirs.)  The host evaluates the same rule over every number of routed tiles a launch can have,
+// to leave out the second kernel where no launch can cut.
+__host__ __device__ inline bool tiled_cuts(long runs_s, long runs, int nkb_s, int nkb_r, long nt) {
+  const long W = runs_s * nkb_s + (runs - runs_s) * nkb_r;
+  const long busiest = (runs_s + nt - 1) / nt * nkb_s + (runs - runs_s + nt - 1) / nt * nkb_r;
+  const bool mixed = runs_s > 0 && runs > runs_s && nkb_s != nkb_r;
+  return ((runs > nt || (mixed && W >= 8 * nt)) && busiest * nt * 100 > W * 115) ||
+         (2 * runs <= nt && W >= 32L * nt);  // half the teams idle, and long contractions
+}
+
 __device__ __forceinline__ TiledWork tiled_work(const StreamArgs &a, const TiledSched &sc) {
   // Tiles are numbered densely per region: the shared expert's first (row tile major, its
   // token blocks adjacent), then the routed experts' (row tile major over the actual number
@@ -133,16 +147,7 @@ __device__ __forceinline__ TiledWork tiled_work(const StreamArgs &a, const Tiled
   w.n_teams = sc.n_teams;
   w.W_s = w.runs_s * sc.nkb_s;
   w.W = w.W_s + (w.runs - w.runs_s) * sc.nkb_r;
-  // Cutting runs costs a round trip of partial sums through memory and a second epilogue
-  // pass: only worth it when whole runs would leave the busiest team more than 15 % above
-  // the mean, or when at least half the teams would idle and every team still gets 32 stages.
-  // (Whole runs are dealt region by region; the shared expert's runs are as long as its whole
-  // contraction, the routed experts' as theirs.)
-  const long nt = w.n_teams;
-  const long busiest = (w.runs_s + nt - 1) / nt * sc.nkb_s + (w.runs - w.runs_s + nt - 1) / nt * sc.nkb_r;
-  const bool mixed = w.runs_s > 0 && w.runs > w.runs_s && sc.nkb_s != sc.nkb_r;
-  w.cut = ((w.runs > nt || (mixed && w.W >= 8 * nt)) && busiest * nt * 100 > w.W * 115) ||
-          (2 * w.runs <= nt && w.W >= 32L * nt);  // half the teams idle, and long contractions
+  w.cut = tiled_cuts(w.runs_s, w.runs, sc.nkb_s, sc.nkb_r, w.n_teams);
   return w;
 }
 // when runs are cut: first unit of team g's share (g = n_teams: one past the end)
@@ -722,7 +727,16 @@ static hipError_t launch_tiled(int mode, const StreamArgs &a, float *partials, h
   const unsigned grid = (unsigned)tiled_grid_for(n_cu);
   sc.n_teams = (int)grid / 4;
   hipLaunchKernelGGL(mains[which], dim3(grid), dim3(T_THREADS), T_LDS_BYTES(a.fp8), s, a, sc);
-  hipLaunchKernelGGL(fixups[which], dim3(4 * grid), dim3(T_THREADS), 0, s, a, sc);
+  // The second kernel only where some launch of this shape and size can cut.  The plan is on the device; what
+  // the host knows is a bound: an entry is an expert with more than 64 rows (fewer than T*K/64 of them, at
+  // most E) or one more 256-row block of one (fewer than T*K/256 in all).
+  const long tk = (long)a.T * a.K;
+  const long max_large = tk / 256 + (tk / 65 < a.E ? tk / 65 : a.E);
+  const long runs_s = ((long)sc.n_shared_entries * sc.rt_shared + 3) / 4;
+  bool may_cut = false;
+  for (long n_large = 0; n_large <= max_large && !may_cut; ++n_large)
+    may_cut = tiled_cuts(runs_s, runs_s + (n_large * sc.rt_routed + 3) / 4, sc.nkb_s, sc.nkb_r, sc.n_teams);
+  if (may_cut) hipLaunchKernelGGL(fixups[which], dim3(4 * grid), dim3(T_THREADS), 0, s, a, sc);
   return hipGetLastError();
 }
 
