@@ -421,6 +421,10 @@ def test_qwen2_shape_full_size_sampled_tokens(gpu, oracle):
         assert np.array_equal(again["perm"], got["perm"]) and again["n_active"] == got["n_active"]
     # the largest T of this shape's sweep (B=256, gamma=4): about 160 rows per expert, every kernel class at once
     full_case(gpu, oracle, "qwen2-57b-a14b", 1280, point=264)
+    # the compute-bound points the benchmark times beyond the sweep: 256 and 512 rows per expert on average
+    # (blocks split evenly, last blocks of a few rows, the shared expert in the tiled kernels without k-parts)
+    full_case(gpu, oracle, "qwen2-57b-a14b", 2048, point=265)
+    full_case(gpu, oracle, "qwen2-57b-a14b", 4096, point=266)
 
 
 @pytest.mark.parametrize("T", [16, 64, 1280])
@@ -469,6 +473,9 @@ def test_mixtral_shape_full_size_tiled_sampled_tokens(gpu, oracle):
     # T = 256 and 1024 of this shape's sweep: 64 and 256 rows per expert
     full_case(gpu, oracle, "mixtral-8x7b", 256, point=365)
     full_case(gpu, oracle, "mixtral-8x7b", 1024, point=366)
+    # T = 2048 and 8192, the other compute-bound points of the benchmark: 512 and 2048 rows per expert
+    full_case(gpu, oracle, "mixtral-8x7b", 2048, point=367)
+    full_case(gpu, oracle, "mixtral-8x7b", 8192, point=368)
 
 
 @pytest.mark.parametrize("T", [1, 4, 16])
