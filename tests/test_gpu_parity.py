@@ -54,13 +54,13 @@ def class_of(m):
     return next(i for i, (lo, hi) in enumerate(ROW_CLASSES) if lo <= m <= hi)
 
 
-def tokens_from_permutation(oracle, shape, w, x, budget=22):
+def tokens_from_permutation(oracle, shape, w, x, budget=32):
     """Tokens to compare at a size where the oracle cannot evaluate them all, chosen from the oracle's own
     routing so that every kind of row position is hit: for each class of expert size (1..16, 17..64, 65..128,
     more rows) the first and last row of its smallest and of its largest expert; the rows on both sides of a
     64-row block border, of a 256-row border (where the tiled kernels' waves pass from their first token tile
     to their second) and of a 512-row block border; a token whose K experts lie in different classes; the first
-    and the last token."""
+    and the last token; then tokens drawn at random (seeded) up to the budget."""
     T, K = x.shape[0], shape.top_k
     ids, _, _ = oracle.route(shape, x, w["w_router"], w.get("router_bias"))
     pr = oracle.permute(shape.E, K, ids)
@@ -87,6 +87,12 @@ def tokens_from_permutation(oracle, shape, w, x, budget=22):
             break
     out = []
     for t in toks:
+        if t not in out:
+            out.append(t)
+    # the rest of the budget: tokens drawn at random (seeded by the size), so that rows in the middle of tiles are hit too
+    for t in np.random.default_rng(T * 7919 + shape.E).permutation(T).tolist():
+        if len(out) >= budget:
+            break
         if t not in out:
             out.append(t)
     return np.array(sorted(out[:budget]), dtype=np.int32)
