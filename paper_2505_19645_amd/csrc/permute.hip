@@ -11,6 +11,7 @@
 
 #define PERM_WAVES 16
 #define PERM_THREADS (PERM_WAVES * 64)
+#define PERM_MAX_LDS (156 * 1024)  // dynamic LDS a launch may ask for (the kernel has a few hundred bytes of its own)
 
 // mask of the lanes (among `valid`) whose value equals this lane's
 __device__ __forceinline__ unsigned long long match_lanes(int v, int nbits, unsigned long long valid) {
@@ -27,9 +28,12 @@ __device__ __forceinline__ void permute_body(
     const int32_t *ids, int64_t n, int E, int K, int nbits, int32_t *__restrict__ counts,
     int32_t *__restrict__ offsets, int32_t *__restrict__ perm, int32_t *__restrict__ inv,
     int32_t *__restrict__ n_active, int32_t *__restrict__ row_token, int32_t *__restrict__ plan,
-    int wide_fill_min, int32_t *smem) {
+    int wide_fill_min, int32_t *smem, bool staged) {
   int32_t *hist = smem;                     // [PERM_WAVES][E]
   int32_t *scan = smem + PERM_WAVES * E;    // [PERM_THREADS] scratch for the scan over experts
+  // (staged) [n] the sorted order, collected here and written out in whole lines afterwards: scattered
+  // 4-byte stores from one compute unit were most of this kernel's time
+  int32_t *sorted = scan + PERM_THREADS;
   __shared__ int32_t wave_tot[5][PERM_WAVES];
   __shared__ int32_t active_tot, wide_tot, large_tot;
 
@@ -178,9 +182,21 @@ __device__ __forceinline__ void permute_body(
     base = __shfl(base, leader, 64);
     if (ok) {
       const int p = base + __popcll(below);
-      perm[p] = (int32_t)f;
       inv[f] = p;
-      if (row_token) row_token[p] = (int32_t)(f / K);
+      if (staged) {
+        sorted[p] = (int32_t)f;
+      } else {
+        perm[p] = (int32_t)f;
+        if (row_token) row_token[p] = (int32_t)(f / K);
+      }
+    }
+  }
+  if (staged) {
+    __syncthreads();
+    for (int64_t i = tid; i < n; i += PERM_THREADS) {
+      const int32_t f = sorted[i];
+      perm[i] = f;
+      if (row_token) row_token[i] = f / K;
     }
   }
 }
@@ -189,9 +205,10 @@ __global__ __launch_bounds__(PERM_THREADS) void permute_kernel(
     const int32_t *__restrict__ ids, int64_t n, int E, int K, int nbits,
     int32_t *__restrict__ counts, int32_t *__restrict__ offsets, int32_t *__restrict__ perm,
     int32_t *__restrict__ inv, int32_t *__restrict__ n_active, int32_t *__restrict__ row_token,
-    int32_t *__restrict__ plan, int wide_fill_min) {
+    int32_t *__restrict__ plan, int wide_fill_min, int staged) {
   extern __shared__ int32_t smem[];
-  permute_body(ids, n, E, K, nbits, counts, offsets, perm, inv, n_active, row_token, plan, wide_fill_min, smem);
+  permute_body(ids, n, E, K, nbits, counts, offsets, perm, inv, n_active, row_token, plan, wide_fill_min, smem,
+               staged != 0);
 }
 
 // Few tokens: the same workgroup first picks every token's top-K (wave w takes
@@ -210,7 +227,7 @@ __global__ __launch_bounds__(PERM_THREADS) void topk_permute_kernel(
   __threadfence_block();
   __syncthreads();
   permute_body(ids, (int64_t)T * K, E, K, nbits, counts, offsets, perm, inv, n_active, row_token, plan,
-               wide_fill_min, smem);  // (few tokens: no expert has more than 128 rows)
+               wide_fill_min, smem, false);  // (few tokens: no expert has more than 128 rows)
 }
 
 hipError_t launch_permute(const int32_t *ids, int64_t n, int E, int K, int32_t *counts,
@@ -218,17 +235,20 @@ hipError_t launch_permute(const int32_t *ids, int64_t n, int E, int K, int32_t *
                           int32_t *row_token, int32_t *plan, int wide_fill_min, hipStream_t s) {
   int nbits = 1;
   while ((1 << nbits) < E) ++nbits;
-  const size_t smem = sizeof(int32_t) * ((size_t)PERM_WAVES * E + PERM_THREADS);
-  if (smem > 48 * 1024) {  // above the default dynamic-LDS limit (E > 704); gfx950 has 160 KB per CU
+  size_t smem = sizeof(int32_t) * ((size_t)PERM_WAVES * E + PERM_THREADS);
+  // the sorted order is staged in LDS when it fits beside the histograms (gfx950 has 160 KB per CU)
+  const int staged = n > 0 && smem + sizeof(int32_t) * (size_t)n <= PERM_MAX_LDS ? 1 : 0;
+  if (staged) smem += sizeof(int32_t) * (size_t)n;
+  if (smem > 48 * 1024) {  // above the default dynamic-LDS limit
     static LdsLimitOnce once;
     int dev = 0, n_cu = 0;
     hipError_t e = current_device(&dev, &n_cu);
     if (e != hipSuccess) return e;
-    e = raise_dynamic_lds_limit(once, dev, reinterpret_cast<const void *>(permute_kernel), (int)(sizeof(int32_t) * ((size_t)PERM_WAVES * MOESD_MAX_E + PERM_THREADS)));
+    e = raise_dynamic_lds_limit(once, dev, reinterpret_cast<const void *>(permute_kernel), PERM_MAX_LDS);
     if (e != hipSuccess) return e;
   }
   hipLaunchKernelGGL(permute_kernel, dim3(1), dim3(PERM_THREADS), smem, s, ids, n, E, K, nbits,
-                     counts, offsets, perm, inv, n_active, row_token, plan, wide_fill_min);
+                     counts, offsets, perm, inv, n_active, row_token, plan, wide_fill_min, staged);
   return hipGetLastError();
 }
 
