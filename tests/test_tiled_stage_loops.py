@@ -19,7 +19,7 @@ CSRC = os.path.join(os.path.dirname(os.path.abspath(hip_build.__file__)), "csrc"
 
 
 def stage_loops(asm_lines):
-    """(mfma count, [vmcnt arguments], scratch op count) of every innermost loop with one barrier and MFMAs."""
+    """(mfma count, [vmcnt arguments], scratch op count) of every loop with one barrier, MFMAs and DMA loads."""
     labels = {}
     for i, line in enumerate(asm_lines):
         m = re.match(r"^(\.LBB\d+_\d+):", line)
@@ -34,7 +34,7 @@ def stage_loops(asm_lines):
         if sum("s_barrier" in x for x in seg) != 1:
             continue
         mfma = sum("v_mfma" in x for x in seg)
-        if mfma == 0:
+        if mfma == 0 or not any("global_load_lds" in x for x in seg):  # (a steady-state stage issues DMA loads)
             continue
         waits = [re.search(r"vmcnt\((\d+)\)", x).group(1) for x in seg if "vmcnt(" in x]
         out.append((mfma, waits, sum("scratch_" in x for x in seg)))
