@@ -255,6 +255,20 @@ def test_fp8_weights_benchmark_shapes_full_size(gpu, oracle):
         del layer, w
 
 
+def test_fp8_weights_mixtral_shape_full_size_tiled(gpu, oracle):
+    # benchmark config 3 with E4M3 expert weights at T = 1024 and 2048: 256 and 512 rows per expert, the
+    # MFMA-tiled kernels with the codes widened on the way into LDS, evenly split blocks, cut runs
+    name = "mixtral-8x7b"
+    shape = dataclasses.replace(PRESETS[name], name=name + "-fp8", weight_format=1)
+    w = synth.make_layer(shape, threads=16)
+    layer = gpu.GpuLayer(shape, w)
+    for i, T in enumerate((1024, 2048)):
+        x = synth.make_tokens(shape, T, point=380 + i)
+        run_case(gpu, oracle, shape, T, tokens=tokens_from_permutation(oracle, shape, w, x), point=380 + i,
+                 weights=w, layer=layer, x=x)
+    del layer, w
+
+
 def _random_shape(i):
     """A small layer with every size drawn at random (seeded): odd row counts, ragged contraction lengths,
     all expert classes, with and without shared expert, groups, bias."""
